@@ -1,0 +1,194 @@
+/*
+ * specee.h -- C ABI of the MI355X (gfx950) SpecEE speculative early-exit
+ * predictor library, libspecee.so.
+ *
+ * The library implements the per-layer predictor of SpecEE ("Speculation-based
+ * Lightweight Predictor", Sec. 4.3 of the paper), its token-tree variant
+ * ("Context-aware Merged Mapping", Sec. 6.2), the full-vocabulary LM head the
+ * predictor replaces (Sec. 4.1) with the verification step that follows a
+ * positive prediction (Sec. 4.3.3), and the online half of the two-level
+ * scheduler (Sec. 5.3).
+ *
+ * Conventions for every entry point
+ * ---------------------------------
+ *  - Half-precision tensors are IEEE binary16, passed as `specee_half`
+ *    (a 16-bit pattern); all are row-major and must be 16-byte aligned.
+ *  - Unless a parameter says HOST, pointers are DEVICE pointers owned by the
+ *    caller.  Inputs are only read, outputs only written; the library never
+ *    allocates or frees device memory and keeps no state between calls.
+ *  - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *    default stream) and the call returns without synchronising.  Outputs are
+ *    valid once the stream has reached the end of the enqueued work.
+ *  - Return value: SPECEE_OK or a negative specee_status.  Argument checks are
+ *    made on the host before anything is enqueued.  Conditions only the device
+ *    can see are reported in the outputs themselves: a speculative id outside
+ *    [0, V) makes that token's logits, probs and score NaN and its exit flag 0;
+ *    a tree whose merged set exceeds Mcap reports the true size in M_out and
+ *    NaN / 0 in that tree's other outputs.  No kernel reads out of bounds in
+ *    either case.
+ *  - Arithmetic: fp16 inputs are widened exactly; products and sums are fp32;
+ *    outputs are fp32 / int32.  Reductions have a fixed order, so results are
+ *    bit-identical from run to run.
+ *  - Calls that share a workspace must not overlap in time.
+ */
+#ifndef SPECEE_H
+#define SPECEE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef uint16_t specee_half;
+
+#define SPECEE_KMAX 16    /* speculative tokens per token / node */
+#define SPECEE_HMAX 2048  /* predictor hidden width */
+
+typedef enum specee_status {
+    SPECEE_OK = 0,
+    SPECEE_EINVAL = -1,     /* bad size, NULL required pointer, aliasing outputs */
+    SPECEE_EALIGN = -2,     /* a tensor pointer is not 16-byte aligned */
+    SPECEE_EWORKSPACE = -3, /* workspace missing or smaller than specee_workspace_bytes() */
+    SPECEE_EHIP = -4        /* the HIP runtime refused a launch */
+} specee_status;
+
+/* Model and predictor shape.  d: hidden size (multiple of 8), V: vocabulary,
+ * K: speculative tokens per token (1..SPECEE_KMAX), H: predictor hidden width
+ * (1..SPECEE_HMAX), eps: RMSNorm epsilon, threshold: exit iff score > threshold
+ * (Sec. 4.3.2 uses 0.5). */
+typedef struct specee_dims {
+    int32_t d, V, K, H;
+    float eps, threshold;
+} specee_dims;
+
+/* One predictor (Sec. 4.3.2: two-layer MLP, ReLU, sigmoid output).
+ * W1 [H][3K] (output x input), w2 [H]; b1 [H] and b2 [1] may be NULL (the
+ * parameter count of Sec. 7.4.2 has no bias terms).  The 3K inputs are
+ * [K logits | K local probabilities | K probability variations], each block in
+ * the caller's order of the K speculative tokens (Sec. 4.3.1).
+ * For the multi-layer entry point every array has a leading layer dimension:
+ * W1 [L][H][3K], w2 [L][H], b1 [L][H], b2 [L]. */
+typedef struct specee_mlp {
+    const specee_half *W1, *b1, *w2, *b2;
+} specee_mlp;
+
+/* Operation selector for specee_workspace_bytes(). */
+typedef enum specee_op {
+    SPECEE_OP_PREDICT = 0,
+    SPECEE_OP_PREDICT_SWEEP = 1,
+    SPECEE_OP_PREDICT_TREE = 2,
+    SPECEE_OP_LM_HEAD = 3,
+    SPECEE_OP_VERIFY = 4
+} specee_op;
+
+/*
+ * Per-layer predictor for B independent tokens (Sec. 4.3.1 features, Sec. 4.3.2
+ * judgment).  For each token: final RMSNorm of the hidden state (weight gamma),
+ * logits against the K LM-head rows named by ids, softmax over those K logits,
+ * variation against prev_probs, MLP, sigmoid, threshold.
+ *   hidden [B][d], gamma [d], lm_head [V][d] (row v = token v), ids [B][K],
+ *   prev_probs [B][K] fp32 (local probabilities of the last layer that ran a
+ *   predictor; zeros for the first).
+ *   logits [B][K], probs [B][K], scores [B] fp32; exit_flags [B] int32 (0/1).
+ * probs must not alias prev_probs.  Needs no workspace.
+ */
+int specee_predict(const specee_dims *dims, int B, const specee_half *hidden, const specee_half *gamma,
+                   const specee_half *lm_head, const int32_t *ids, const float *prev_probs,
+                   const specee_mlp *mlp /* HOST struct of device pointers */, float *logits, float *probs,
+                   float *scores, int32_t *exit_flags, void *stream);
+
+/*
+ * All L layers of B tokens in one call: layer l uses hidden[l], predictor l and
+ * the local probabilities of the nearest earlier active layer (prev0, or zeros
+ * if NULL, before the first).  Used when every layer's hidden state already
+ * exists (collecting predictor training data or exit statistics, Sec. 5.3
+ * offline scheduling and Sec. 7.4.4; benchmarking).
+ *   hidden [L][B][d], ids [B][K], prev0 [B][K] or NULL, mlp with leading L,
+ *   active [L] int32 or NULL (all active): inactive layers output zeros.
+ *   logits/probs [L][B][K], scores/exit_flags [L][B],
+ *   first_exit [B]: first active layer whose exit flag is 1, else -1.
+ * Needs no workspace.
+ */
+int specee_predict_sweep(const specee_dims *dims, int L, int B, const specee_half *hidden,
+                         const specee_half *gamma, const specee_half *lm_head, const int32_t *ids,
+                         const float *prev0, const specee_mlp *mlp /* HOST */, const int32_t *active,
+                         float *logits, float *probs, float *scores, int32_t *exit_flags, int32_t *first_exit,
+                         void *stream);
+
+/*
+ * Token trees under the merged mapping (Sec. 6.2).  G independent trees of N
+ * nodes; the N*K speculative ids of a tree are merged into their sorted
+ * distinct set (M <= Mcap entries), all N nodes are projected onto the M
+ * LM-head rows in one contraction, and each node reads back its K columns and
+ * is scored like a single token.
+ *   hidden [G][N][d], ids [G][N][K], prev_probs [G][N][K],
+ *   parent [G][N] or NULL: -1 for a root, otherwise an index smaller than the
+ *   node's own.
+ *   merged_ids [G][Mcap] ascending, tail -1; M_out [G]; cols [G][N][K] with
+ *   merged_ids[g][cols[g][n][k]] == ids[g][n][k];
+ *   logits/probs [G][N][K], scores/exit_flags [G][N];
+ *   path_exit [G][N] or NULL (needs parent): 1 iff the node and all its
+ *   ancestors exit -- a token path exits at the rearmost exit of its tokens.
+ * Limits: N*K <= 4096, Mcap <= 4096.  Workspace: SPECEE_OP_PREDICT_TREE with
+ * n = G*N.
+ */
+int specee_predict_tree(const specee_dims *dims, int G, int N, int Mcap, const specee_half *hidden,
+                        const specee_half *gamma, const specee_half *lm_head, const int32_t *ids,
+                        const int32_t *parent, const float *prev_probs, const specee_mlp *mlp /* HOST */,
+                        int32_t *merged_ids, int32_t *M_out, int32_t *cols, float *logits, float *probs,
+                        float *scores, int32_t *exit_flags, int32_t *path_exit, void *workspace,
+                        size_t workspace_bytes, void *stream);
+
+/*
+ * Full-vocabulary LM head with the final RMSNorm: the search space of earlier
+ * early-exit predictors (Sec. 4.1) and the first half of verification
+ * (Sec. 4.3.3).  out [N][V] fp32 = RMSNorm(hidden[n]) . lm_head[v].
+ * dims->K and dims->H are ignored.  Workspace: SPECEE_OP_LM_HEAD with n = N.
+ */
+int lm_head_gemv(const specee_dims *dims, int N, const specee_half *hidden, const specee_half *gamma,
+                 const specee_half *lm_head, float *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Verification (Sec. 4.3.3): arg-max of the full-vocabulary logits (lowest id
+ * on ties) without materialising them, and whether it is one of the K
+ * speculative ids.  token [N], max_logit [N] fp32, hit [N] int32.
+ * Workspace: SPECEE_OP_VERIFY with n = N.
+ */
+int specee_verify(const specee_dims *dims, int N, const specee_half *hidden, const specee_half *gamma,
+                  const specee_half *lm_head, const int32_t *ids, int32_t *token, float *max_logit, int32_t *hit,
+                  void *workspace, size_t workspace_bytes, void *stream);
+
+/* Bytes of device workspace `op` needs for n tokens / nodes (Mcap: tree only).
+ * Pure host function; 0 means none; (size_t)-1 means invalid arguments. */
+size_t specee_workspace_bytes(int op, const specee_dims *dims, int n, int Mcap);
+
+/*
+ * Online scheduling (Sec. 5.3), host-side and allocation-free: the caller owns
+ * the state.  A circular queue keeps the exit layers of the last Q tokens;
+ * counter[i] counts queued exit layers within `radius` of layer i.  A layer's
+ * predictor is active iff offline_mask[i] != 0 or counter[i] > 0.
+ * All pointers are HOST pointers.
+ */
+#define SPECEE_SCHED_MAXQ 64
+#define SPECEE_SCHED_MAXL 256
+typedef struct specee_sched {
+    int32_t L, Q, radius, filled, head;
+    int32_t queue[SPECEE_SCHED_MAXQ];
+    int32_t counter[SPECEE_SCHED_MAXL];
+} specee_sched;
+
+int specee_sched_init(specee_sched *s, int L, int Q, int radius);
+/* Record the exit layer of the token just decoded (0..L-1). */
+int specee_sched_push(specee_sched *s, int exit_layer);
+/* active [L] (0/1) for the next token; offline_mask [L] or NULL. Returns the number of active layers. */
+int specee_sched_active(const specee_sched *s, const int32_t *offline_mask, int32_t *active);
+
+const char *specee_strerror(int status);
+int specee_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECEE_H */

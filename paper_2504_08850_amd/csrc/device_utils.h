@@ -1,0 +1,87 @@
+// Device-side helpers shared by the gfx950 kernels: 16-byte fp16 vectors,
+// wavefront (64-lane) reductions built from DPP lane permutes, and fixed-order
+// block reductions through LDS.  Nothing here depends on launch shape beyond
+// "blockDim.x is a multiple of 64".
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace specee {
+
+typedef _Float16 half_t;
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+
+// DPP control words (CDNA ISA): quad_perm packs four 2-bit selectors.
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // reverse within 8 lanes
+constexpr int kDppMirror = 0x140;     // reverse within 16 lanes
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+    int i = __builtin_bit_cast(int, v);
+    i = __builtin_amdgcn_update_dpp(0, i, CTRL, 0xF, 0xF, true);
+    return __builtin_bit_cast(float, i);
+}
+
+// Sum over the 64 lanes of a wavefront; every lane returns the total.  The
+// first four steps stay inside a 16-lane DPP row (no LDS traffic); the last two
+// cross rows through the LDS crossbar.  The combination order is fixed, so the
+// result is reproducible.
+__device__ __forceinline__ float wave_sum(float v) {
+    v += dpp_f32<kDppXor1>(v);
+    v += dpp_f32<kDppXor2>(v);
+    v += dpp_f32<kDppHalfMirror>(v);
+    v += dpp_f32<kDppMirror>(v);
+    v += __shfl_xor(v, 16, kWave);
+    v += __shfl_xor(v, 32, kWave);
+    return v;
+}
+
+template <int CTRL>
+__device__ __forceinline__ void dpp_argmax_step(float &v, int &i) {
+    float ov = dpp_f32<CTRL>(v);
+    int oi = __builtin_amdgcn_update_dpp(0, i, CTRL, 0xF, 0xF, true);
+    if (ov > v || (ov == v && oi < i)) {
+        v = ov;
+        i = oi;
+    }
+}
+
+// Arg-max over a wavefront, lowest index on ties; every lane returns the winner.
+__device__ __forceinline__ void wave_argmax(float &v, int &i) {
+    dpp_argmax_step<kDppXor1>(v, i);
+    dpp_argmax_step<kDppXor2>(v, i);
+    dpp_argmax_step<kDppHalfMirror>(v, i);
+    dpp_argmax_step<kDppMirror>(v, i);
+#pragma unroll
+    for (int off = 16; off <= 32; off <<= 1) {
+        float ov = __shfl_xor(v, off, kWave);
+        int oi = __shfl_xor(i, off, kWave);
+        if (ov > v || (ov == v && oi < i)) {
+            v = ov;
+            i = oi;
+        }
+    }
+}
+
+__device__ __forceinline__ half8 load_half8(const half_t *p) {
+    return *reinterpret_cast<const half8 *>(p);
+}
+
+__device__ __forceinline__ half8 zero_half8() {
+    half8 z;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) z[e] = (half_t)0.0f;
+    return z;
+}
+
+__device__ __forceinline__ float quiet_nan() {
+    return __builtin_bit_cast(float, 0x7fc00000);
+}
+
+}  // namespace specee

@@ -1,0 +1,361 @@
+// Fused per-layer predictor kernel (paper Sec. 4.3.1 features + Sec. 4.3.2
+// judgment): one workgroup scores one (layer, token) pair.
+//
+// Why one workgroup per token: a call moves (K+2) rows of d halves plus ~13 KB
+// of predictor weights -- far below the bandwidth-delay product of the memory
+// system -- so what matters is the number of dependent memory round trips, not
+// bytes per second.  Everything that does not depend on the speculative ids
+// (hidden state, RMSNorm weight, the thread's MLP row) is requested first, the
+// K LM-head rows follow as soon as the ids arrive, and because the RMSNorm
+// scale is a scalar factor of every logit, sum(h^2) and the K dot products run
+// in the same pass: the kernel makes exactly two dependent trips to memory.
+// All loads are 16 bytes per lane; reductions are DPP within a wavefront and a
+// fixed-order LDS exchange across the eight wavefronts.
+#include "device_utils.h"
+#include "kernels.h"
+
+namespace specee {
+
+constexpr int kPredictThreads = 512;
+constexpr int kPredictWaves = kPredictThreads / kWave;
+
+// softmax over K values held in registers (K <= KC)
+template <int KC>
+__device__ __forceinline__ void local_softmax(const float (&z)[KC], int K, float (&p)[KC]) {
+    float m = z[0];
+#pragma unroll
+    for (int k = 1; k < KC; ++k)
+        if (k < K) m = fmaxf(m, z[k]);
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < KC; ++k) {
+        p[k] = (k < K) ? expf(z[k] - m) : 0.f;
+        s += p[k];
+    }
+    float inv = 1.0f / s;
+#pragma unroll
+    for (int k = 0; k < KC; ++k) p[k] *= inv;
+    // NaN logits (invalid id) propagate: fmaxf would drop them, so poison explicitly
+    bool bad = false;
+#pragma unroll
+    for (int k = 0; k < KC; ++k)
+        if (k < K && z[k] != z[k]) bad = true;
+    if (bad) {
+#pragma unroll
+        for (int k = 0; k < KC; ++k) p[k] = quiet_nan();
+    }
+}
+
+// KC: speculative rows held in flight (K <= KC).  VPT: 16-byte vectors per
+// thread per row (d/8 <= VPT * 512 * tiles).  SWEEP: the previous layer's local
+// probabilities are recomputed from that layer's hidden state instead of read,
+// which makes every (layer, token) workgroup independent.
+template <int KC, int VPT, bool SWEEP>
+__global__ __launch_bounds__(kPredictThreads) void predict_kernel(PredictParams p) {
+    __shared__ float red[kPredictWaves][2 * KC + 2];
+    __shared__ float red_u[kPredictWaves];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid >> 6;
+    const int b = blockIdx.x;
+    const int l = blockIdx.y;
+    const int K = p.K, H = p.H, d = p.d;
+    const int nv = d >> 3;
+    const size_t tok = (size_t)l * p.B + b;
+
+    // ---- which layer supplies the previous probabilities (sweep only)
+    int lprev = -1;
+    if (SWEEP) {
+        if (p.active && p.active[l] == 0) {
+            if (tid < K) {
+                p.logits[tok * K + tid] = 0.f;
+                p.probs[tok * K + tid] = 0.f;
+            }
+            if (tid == 0) {
+                p.scores[tok] = 0.f;
+                p.exit_flags[tok] = 0;
+            }
+            return;
+        }
+        for (int q = l - 1; q >= 0; --q)
+            if (!p.active || p.active[q] != 0) {
+                lprev = q;
+                break;
+            }
+    }
+
+    // ---- requests that do not depend on the ids
+    const half_t *W1 = p.W1 + (size_t)l * H * 3 * K;
+    const half_t *w2 = p.w2 + (size_t)l * H;
+    const half_t *b1 = p.b1 ? p.b1 + (size_t)l * H : nullptr;
+    const bool vec_w1 = K == KC;                 // rows of 3*KC halves: 8-byte aligned, static feature index
+    uint2 w1pre[(3 * KC + 3) / 4];
+    float w2pre = 0.f, b1pre = 0.f;
+    if (tid < H) {
+        if (vec_w1) {
+            const uint2 *src = reinterpret_cast<const uint2 *>(W1 + (size_t)tid * 3 * K);
+#pragma unroll
+            for (int q = 0; q < (3 * KC + 3) / 4; ++q)
+                if (q * 4 < 3 * K) w1pre[q] = src[q];
+        }
+        w2pre = (float)w2[tid];
+        if (b1) b1pre = (float)b1[tid];
+    }
+
+    const half_t *hrow = p.hidden + tok * d;
+    const half_t *hprow = (SWEEP && lprev >= 0) ? p.hidden + ((size_t)lprev * p.B + b) * d : nullptr;
+    half8 hv[VPT], gv[VPT], hp[VPT];
+#pragma unroll
+    for (int u = 0; u < VPT; ++u) {
+        int v = tid + u * kPredictThreads;
+        bool in = v < nv;
+        hv[u] = in ? load_half8(hrow + v * 8) : zero_half8();
+        gv[u] = in ? load_half8(p.gamma + v * 8) : zero_half8();
+        hp[u] = (SWEEP && in && hprow) ? load_half8(hprow + v * 8) : zero_half8();
+    }
+    float prev[KC];
+#pragma unroll
+    for (int k = 0; k < KC; ++k) prev[k] = 0.f;
+    const float *prev_src = SWEEP ? (lprev < 0 ? p.prev : nullptr) : p.prev;
+    if (prev_src) {
+#pragma unroll
+        for (int k = 0; k < KC; ++k)
+            if (k < K) prev[k] = prev_src[(size_t)b * K + k];
+    }
+
+    // ---- the K speculative LM-head rows
+    const half_t *rows[KC];
+    bool bad_id = false;
+#pragma unroll
+    for (int k = 0; k < KC; ++k) {
+        int id = (k < K) ? p.ids[(size_t)(SWEEP ? b : tok) * K + k] : 0;
+        bool ok = id >= 0 && id < p.V;
+        if (k < K && !ok) bad_id = true;
+        rows[k] = p.lm_head + (size_t)(ok ? id : 0) * d;
+    }
+    half8 wv[KC][VPT];
+#pragma unroll
+    for (int k = 0; k < KC; ++k)
+#pragma unroll
+        for (int u = 0; u < VPT; ++u) {
+            int v = tid + u * kPredictThreads;
+            wv[k][u] = (k < K && v < nv) ? load_half8(rows[k] + v * 8) : zero_half8();
+        }
+
+    // ---- one pass: sum of squares and the K dot products (and the previous layer's)
+    float ssq = 0.f, ssq_p = 0.f, acc[KC], acc_p[KC];
+#pragma unroll
+    for (int k = 0; k < KC; ++k) acc[k] = acc_p[k] = 0.f;
+#pragma unroll
+    for (int u = 0; u < VPT; ++u)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float g = (float)gv[u][e];
+            float hf = (float)hv[u][e];
+            float x = hf * g;
+            ssq += hf * hf;
+            float xp = 0.f;
+            if (SWEEP) {
+                float hpf = (float)hp[u][e];
+                xp = hpf * g;
+                ssq_p += hpf * hpf;
+            }
+#pragma unroll
+            for (int k = 0; k < KC; ++k) {
+                float w = (float)wv[k][u][e];
+                acc[k] += x * w;
+                if (SWEEP) acc_p[k] += xp * w;
+            }
+        }
+    // d larger than VPT * 512 vectors: remaining tiles, same arithmetic
+    for (int v = tid + VPT * kPredictThreads; v < nv; v += kPredictThreads) {
+        half8 h8 = load_half8(hrow + v * 8), g8 = load_half8(p.gamma + v * 8);
+        half8 hp8 = (SWEEP && hprow) ? load_half8(hprow + v * 8) : zero_half8();
+        half8 w8[KC];
+#pragma unroll
+        for (int k = 0; k < KC; ++k) w8[k] = (k < K) ? load_half8(rows[k] + v * 8) : zero_half8();
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float g = (float)g8[e], hf = (float)h8[e], hpf = (float)hp8[e];
+            float x = hf * g, xp = hpf * g;
+            ssq += hf * hf;
+            ssq_p += hpf * hpf;
+#pragma unroll
+            for (int k = 0; k < KC; ++k) {
+                float w = (float)w8[k][e];
+                acc[k] += x * w;
+                acc_p[k] += xp * w;
+            }
+        }
+    }
+
+    // ---- wavefront reduction, then fixed-order combination of the eight wave partials
+    ssq = wave_sum(ssq);
+#pragma unroll
+    for (int k = 0; k < KC; ++k) acc[k] = wave_sum(acc[k]);
+    if (SWEEP) {
+        ssq_p = wave_sum(ssq_p);
+#pragma unroll
+        for (int k = 0; k < KC; ++k) acc_p[k] = wave_sum(acc_p[k]);
+    }
+    if (lane == 0) {
+        red[wave][0] = ssq;
+        red[wave][1] = ssq_p;
+#pragma unroll
+        for (int k = 0; k < KC; ++k) {
+            red[wave][2 + k] = acc[k];
+            red[wave][2 + KC + k] = acc_p[k];
+        }
+    }
+    __syncthreads();
+    ssq = ssq_p = 0.f;
+#pragma unroll
+    for (int k = 0; k < KC; ++k) acc[k] = acc_p[k] = 0.f;
+#pragma unroll
+    for (int w = 0; w < kPredictWaves; ++w) {
+        ssq += red[w][0];
+        if (SWEEP) ssq_p += red[w][1];
+#pragma unroll
+        for (int k = 0; k < KC; ++k) {
+            acc[k] += red[w][2 + k];
+            if (SWEEP) acc_p[k] += red[w][2 + KC + k];
+        }
+    }
+
+    // ---- features (every thread computes them redundantly: no second exchange)
+    const float inv_d = 1.0f / (float)d;
+    float z[KC], pr[KC];
+    {
+        float r = 1.0f / sqrtf(ssq * inv_d + p.eps);
+#pragma unroll
+        for (int k = 0; k < KC; ++k) z[k] = bad_id ? quiet_nan() : acc[k] * r;
+        local_softmax<KC>(z, K, pr);
+    }
+    if (SWEEP && lprev >= 0) {
+        float zp[KC];
+        float rp = 1.0f / sqrtf(ssq_p * inv_d + p.eps);
+#pragma unroll
+        for (int k = 0; k < KC; ++k) zp[k] = bad_id ? quiet_nan() : acc_p[k] * rp;
+        local_softmax<KC>(zp, K, prev);
+    }
+
+    // ---- MLP: thread j owns hidden unit j (+512, ...); f = [z | p | p - prev]
+    float part = 0.f;
+    for (int j = tid; j < H; j += kPredictThreads) {
+        float a, w2j;
+        if (j == tid) {
+            a = b1pre;
+            w2j = w2pre;
+        } else {
+            a = b1 ? (float)b1[j] : 0.f;
+            w2j = (float)w2[j];
+        }
+        if (vec_w1) {
+            uint2 wq[(3 * KC + 3) / 4];
+            if (j == tid) {
+#pragma unroll
+                for (int q = 0; q < (3 * KC + 3) / 4; ++q) wq[q] = w1pre[q];
+            } else {
+                const uint2 *src = reinterpret_cast<const uint2 *>(W1 + (size_t)j * 3 * K);
+#pragma unroll
+                for (int q = 0; q < (3 * KC + 3) / 4; ++q)
+                    if (q * 4 < 3 * K) wq[q] = src[q];
+            }
+            float f[3 * KC];
+#pragma unroll
+            for (int k = 0; k < KC; ++k) {
+                f[k] = z[k];
+                f[KC + k] = pr[k];
+                f[2 * KC + k] = pr[k] - prev[k];
+            }
+#pragma unroll
+            for (int q = 0; q < (3 * KC) / 4; ++q) {
+                half4 w4 = __builtin_bit_cast(half4, wq[q]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) a += (float)w4[e] * f[q * 4 + e];
+            }
+        } else {
+            const half_t *src = W1 + (size_t)j * 3 * K;
+#pragma unroll
+            for (int k = 0; k < KC; ++k)
+                if (k < K) a += (float)src[k] * z[k];
+#pragma unroll
+            for (int k = 0; k < KC; ++k)
+                if (k < K) a += (float)src[K + k] * pr[k];
+#pragma unroll
+            for (int k = 0; k < KC; ++k)
+                if (k < K) a += (float)src[2 * K + k] * (pr[k] - prev[k]);
+        }
+        part += w2j * fmaxf(a, 0.f);
+        if (a != a) part = quiet_nan();  // fmaxf drops NaN; keep invalid ids visible
+    }
+    part = wave_sum(part);
+    if (lane == 0) red_u[wave] = part;
+    __syncthreads();
+
+    if (tid == 0) {
+        float u = p.b2 ? (float)p.b2[l] : 0.f;
+#pragma unroll
+        for (int w = 0; w < kPredictWaves; ++w) u += red_u[w];
+        float s = 1.0f / (1.0f + expf(-u));
+        p.scores[tok] = s;
+        p.exit_flags[tok] = (s > p.threshold) ? 1 : 0;
+#pragma unroll
+        for (int k = 0; k < KC; ++k)
+            if (k < K) {
+                p.logits[tok * K + k] = z[k];
+                p.probs[tok * K + k] = pr[k];
+            }
+    }
+}
+
+// first_exit[b] = first layer with exit flag 1 (inactive layers carry 0), else -1
+__global__ void first_exit_kernel(const int32_t *exit_flags, int L, int B, int32_t *first_exit) {
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    int f = -1;
+    for (int l = 0; l < L; ++l)
+        if (exit_flags[(size_t)l * B + b] != 0) {
+            f = l;
+            break;
+        }
+    first_exit[b] = f;
+}
+
+template <int KC, bool SWEEP>
+static hipError_t launch_vpt(const PredictParams &p, hipStream_t s) {
+    dim3 grid(p.B, p.L), block(kPredictThreads);
+    const int nv = p.d >> 3;
+    const int vpt = (nv + kPredictThreads - 1) / kPredictThreads;
+    if (vpt <= 1)
+        hipLaunchKernelGGL((predict_kernel<KC, 1, SWEEP>), grid, block, 0, s, p);
+    else if (vpt <= 2 || KC > 8)
+        hipLaunchKernelGGL((predict_kernel<KC, 2, SWEEP>), grid, block, 0, s, p);
+    else if constexpr (KC <= 8)
+        hipLaunchKernelGGL((predict_kernel<KC, 4, SWEEP>), grid, block, 0, s, p);
+    return hipGetLastError();
+}
+
+template <bool SWEEP>
+static hipError_t launch_kc(const PredictParams &p, hipStream_t s) {
+    if (p.K <= 4) return launch_vpt<4, SWEEP>(p, s);
+    if (p.K <= 8) return launch_vpt<8, SWEEP>(p, s);
+    return launch_vpt<16, SWEEP>(p, s);
+}
+
+hipError_t launch_predict(const PredictParams &p, hipStream_t s) {
+    return launch_kc<false>(p, s);
+}
+
+hipError_t launch_predict_sweep(const PredictParams &p, int32_t *first_exit, hipStream_t s) {
+    if (p.L > 0) {
+        hipError_t e = launch_kc<true>(p, s);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(first_exit_kernel, dim3((p.B + 255) / 256), dim3(256), 0, s, p.exit_flags, p.L, p.B,
+                       first_exit);
+    return hipGetLastError();
+}
+
+}  // namespace specee

@@ -1,0 +1,130 @@
+// C ABI of libspecee.so: host-side argument checks, workspace layout and
+// kernel launches.  See include/specee.h for the contract of every entry point.
+#include <hip/hip_runtime.h>
+
+#include "../../include/specee.h"
+#include "kernels.h"
+
+using namespace specee;
+
+namespace {
+
+inline bool misaligned(const void *p) {
+    return (reinterpret_cast<uintptr_t>(p) & 15u) != 0;
+}
+
+int check_dims(const specee_dims *dm, bool need_predictor) {
+    if (!dm) return SPECEE_EINVAL;
+    if (dm->d < 8 || (dm->d & 7) || dm->d > 16384 || dm->V < 1) return SPECEE_EINVAL;
+    if (need_predictor) {
+        if (dm->K < 1 || dm->K > SPECEE_KMAX || dm->H < 1 || dm->H > SPECEE_HMAX) return SPECEE_EINVAL;
+    }
+    if (!(dm->eps >= 0.f)) return SPECEE_EINVAL;
+    return SPECEE_OK;
+}
+
+int check_mlp(const specee_mlp *m) {
+    if (!m || !m->W1 || !m->w2) return SPECEE_EINVAL;
+    if (misaligned(m->W1) || misaligned(m->w2)) return SPECEE_EALIGN;
+    return SPECEE_OK;
+}
+
+const half_t *H(const specee_half *p) {
+    return reinterpret_cast<const half_t *>(p);
+}
+
+}  // namespace
+
+extern "C" {
+
+int specee_version(void) {
+    return 100;
+}
+
+const char *specee_strerror(int status) {
+    switch (status) {
+        case SPECEE_OK: return "success";
+        case SPECEE_EINVAL: return "invalid argument";
+        case SPECEE_EALIGN: return "tensor pointer is not 16-byte aligned";
+        case SPECEE_EWORKSPACE: return "workspace missing or too small";
+        case SPECEE_EHIP: return "HIP runtime refused the launch";
+        default: return "unknown status";
+    }
+}
+
+size_t specee_workspace_bytes(int op, const specee_dims *dm, int n, int Mcap) {
+    if (n < 0) return (size_t)-1;
+    switch (op) {
+        case SPECEE_OP_PREDICT:
+        case SPECEE_OP_PREDICT_SWEEP:
+            return check_dims(dm, true) ? (size_t)-1 : 0;
+        case SPECEE_OP_LM_HEAD:
+            return check_dims(dm, false) ? (size_t)-1 : 0;
+        default:
+            (void)Mcap;
+            return (size_t)-1;
+    }
+}
+
+int specee_predict(const specee_dims *dm, int B, const specee_half *hidden, const specee_half *gamma,
+                   const specee_half *lm_head, const int32_t *ids, const float *prev_probs, const specee_mlp *mlp,
+                   float *logits, float *probs, float *scores, int32_t *exit_flags, void *stream) {
+    int rc = check_dims(dm, true);
+    if (rc) return rc;
+    if (B < 0) return SPECEE_EINVAL;
+    if (B == 0) return SPECEE_OK;  // nothing to read or write: pointers may be NULL
+    if ((rc = check_mlp(mlp))) return rc;
+    if (!hidden || !gamma || !lm_head || !ids || !prev_probs || !logits || !probs || !scores || !exit_flags)
+        return SPECEE_EINVAL;
+    if (probs == prev_probs) return SPECEE_EINVAL;
+    if (misaligned(hidden) || misaligned(gamma) || misaligned(lm_head)) return SPECEE_EALIGN;
+    PredictParams p{};
+    p.d = dm->d; p.V = dm->V; p.K = dm->K; p.H = dm->H; p.eps = dm->eps; p.threshold = dm->threshold;
+    p.B = B; p.L = 1;
+    p.hidden = H(hidden); p.gamma = H(gamma); p.lm_head = H(lm_head); p.ids = ids; p.prev = prev_probs;
+    p.W1 = H(mlp->W1); p.b1 = H(mlp->b1); p.w2 = H(mlp->w2); p.b2 = H(mlp->b2);
+    p.active = nullptr;
+    p.logits = logits; p.probs = probs; p.scores = scores; p.exit_flags = exit_flags;
+    return launch_predict(p, static_cast<hipStream_t>(stream)) == hipSuccess ? SPECEE_OK : SPECEE_EHIP;
+}
+
+int specee_predict_sweep(const specee_dims *dm, int L, int B, const specee_half *hidden, const specee_half *gamma,
+                         const specee_half *lm_head, const int32_t *ids, const float *prev0, const specee_mlp *mlp,
+                         const int32_t *active, float *logits, float *probs, float *scores, int32_t *exit_flags,
+                         int32_t *first_exit, void *stream) {
+    int rc = check_dims(dm, true);
+    if (rc) return rc;
+    if (B < 0 || L < 0 || L > 65535) return SPECEE_EINVAL;
+    if (B == 0) return SPECEE_OK;
+    if (L > 0 && (rc = check_mlp(mlp))) return rc;
+    if (!first_exit) return SPECEE_EINVAL;
+    if (L > 0 && (!hidden || !gamma || !lm_head || !ids || !logits || !probs || !scores || !exit_flags))
+        return SPECEE_EINVAL;
+    if (misaligned(hidden) || misaligned(gamma) || misaligned(lm_head)) return SPECEE_EALIGN;
+    PredictParams p{};
+    p.d = dm->d; p.V = dm->V; p.K = dm->K; p.H = dm->H; p.eps = dm->eps; p.threshold = dm->threshold;
+    p.B = B; p.L = L;
+    p.hidden = H(hidden); p.gamma = H(gamma); p.lm_head = H(lm_head); p.ids = ids; p.prev = prev0;
+    p.W1 = H(mlp->W1); p.b1 = H(mlp->b1); p.w2 = H(mlp->w2); p.b2 = H(mlp->b2);
+    p.active = active;
+    p.logits = logits; p.probs = probs; p.scores = scores; p.exit_flags = exit_flags;
+    return launch_predict_sweep(p, first_exit, static_cast<hipStream_t>(stream)) == hipSuccess ? SPECEE_OK
+                                                                                              : SPECEE_EHIP;
+}
+
+int lm_head_gemv(const specee_dims *dm, int N, const specee_half *hidden, const specee_half *gamma,
+                 const specee_half *lm_head, float *out, void *workspace, size_t workspace_bytes, void *stream) {
+    (void)workspace;
+    (void)workspace_bytes;
+    int rc = check_dims(dm, false);
+    if (rc) return rc;
+    if (N < 0 || N > 65535) return SPECEE_EINVAL;
+    if (N == 0) return SPECEE_OK;
+    if (!hidden || !gamma || !lm_head || !out) return SPECEE_EINVAL;
+    if (misaligned(hidden) || misaligned(gamma) || misaligned(lm_head)) return SPECEE_EALIGN;
+    hipError_t e = launch_lm_head_gemv(dm->d, dm->V, dm->eps, N, H(hidden), H(gamma), H(lm_head), out,
+                                       static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SPECEE_OK : SPECEE_EHIP;
+}
+
+}  // extern "C"

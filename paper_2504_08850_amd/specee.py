@@ -1,0 +1,252 @@
+"""Python binding of libspecee.so (include/specee.h): argument marshalling only.
+
+Tensors are torch tensors on the GPU (PyTorch supplies device memory and
+streams, nothing else); every computation happens inside the HIP library.  A
+missing library is a hard error -- there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from pathlib import Path
+
+import torch
+
+_PKG = Path(__file__).resolve().parent
+LIB_PATH = _PKG / "libspecee.so"
+_lib = None
+
+OP_PREDICT, OP_PREDICT_SWEEP, OP_PREDICT_TREE, OP_LM_HEAD, OP_VERIFY = range(5)
+
+
+class SpeceeError(RuntimeError):
+    def __init__(self, fn, code):
+        self.code = code
+        msg = lib().specee_strerror(code).decode()
+        super().__init__(f"{fn} failed: {msg} ({code})")
+
+
+class Dims(C.Structure):
+    _fields_ = [("d", C.c_int32), ("V", C.c_int32), ("K", C.c_int32), ("H", C.c_int32),
+                ("eps", C.c_float), ("threshold", C.c_float)]
+
+
+class Mlp(C.Structure):
+    _fields_ = [("W1", C.c_void_p), ("b1", C.c_void_p), ("w2", C.c_void_p), ("b2", C.c_void_p)]
+
+
+class Sched(C.Structure):
+    _fields_ = [("L", C.c_int32), ("Q", C.c_int32), ("radius", C.c_int32), ("filled", C.c_int32),
+                ("head", C.c_int32), ("queue", C.c_int32 * 64), ("counter", C.c_int32 * 256)]
+
+
+def lib():
+    """Open the HIP library (built by paper_2504_08850_amd.build); fail loudly if absent."""
+    global _lib
+    if _lib is None:
+        if not LIB_PATH.exists():
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2504_08850_amd.build` "
+                "(there is no CPU or PyTorch fallback for the predictor)")
+        _lib = C.CDLL(str(LIB_PATH))
+        _lib.specee_strerror.restype = C.c_char_p
+        _lib.specee_strerror.argtypes = [C.c_int]
+        _lib.specee_workspace_bytes.restype = C.c_size_t
+        _lib.specee_workspace_bytes.argtypes = [C.c_int, C.POINTER(Dims), C.c_int, C.c_int]
+    return _lib
+
+
+def _ptr(t, dtype=None):
+    if t is None:
+        return C.c_void_p(None)
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
+    if dtype is not None:
+        assert t.dtype == dtype, (t.dtype, dtype)
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _mlp(W1, w2, b1, b2):
+    f16 = torch.float16
+    return Mlp(_ptr(W1, f16).value, _ptr(b1, f16).value, _ptr(w2, f16).value, _ptr(b2, f16).value)
+
+
+def _dims(d, V, K, H, eps, threshold):
+    return Dims(int(d), int(V), int(K), int(H), float(eps), float(threshold))
+
+
+def workspace_bytes(op, dims: Dims, n, Mcap=0) -> int:
+    r = lib().specee_workspace_bytes(int(op), C.byref(dims), int(n), int(Mcap))
+    if r == C.c_size_t(-1).value:
+        raise SpeceeError("specee_workspace_bytes", -1)
+    return int(r)
+
+
+def _workspace(op, dims, n, Mcap, workspace, device):
+    need = workspace_bytes(op, dims, n, Mcap)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=device)
+    return workspace, C.c_size_t(workspace.numel() * workspace.element_size())
+
+
+def predict(hidden, gamma, lm_head, ids, prev_probs, W1, w2, b1=None, b2=None, eps=1e-5, threshold=0.5,
+            out=None, stream=None):
+    """specee_predict: B tokens at one layer.  Returns dict(logits, probs, scores, exit)."""
+    B, d = hidden.shape
+    V = lm_head.shape[0]
+    K = ids.shape[1]
+    H = w2.shape[0]
+    dev = hidden.device
+    if out is None:
+        out = dict(logits=torch.empty((B, K), dtype=torch.float32, device=dev),
+                   probs=torch.empty((B, K), dtype=torch.float32, device=dev),
+                   scores=torch.empty((B,), dtype=torch.float32, device=dev),
+                   exit=torch.empty((B,), dtype=torch.int32, device=dev))
+    dims = _dims(d, V, K, H, eps, threshold)
+    mlp = _mlp(W1, w2, b1, b2)
+    f16 = torch.float16
+    rc = lib().specee_predict(C.byref(dims), C.c_int(B), _ptr(hidden, f16), _ptr(gamma, f16), _ptr(lm_head, f16),
+                              _ptr(ids, torch.int32), _ptr(prev_probs, torch.float32), C.byref(mlp),
+                              _ptr(out["logits"]), _ptr(out["probs"]), _ptr(out["scores"]), _ptr(out["exit"]),
+                              _stream(stream))
+    if rc:
+        raise SpeceeError("specee_predict", rc)
+    return out
+
+
+def predict_sweep(hidden, gamma, lm_head, ids, W1, w2, b1=None, b2=None, prev0=None, active=None, eps=1e-5,
+                  threshold=0.5, out=None, stream=None):
+    """specee_predict_sweep: hidden [L][B][d], one predictor per layer."""
+    L, B, d = hidden.shape
+    V = lm_head.shape[0]
+    K = ids.shape[1]
+    H = w2.shape[1]
+    dev = hidden.device
+    if out is None:
+        out = dict(logits=torch.empty((L, B, K), dtype=torch.float32, device=dev),
+                   probs=torch.empty((L, B, K), dtype=torch.float32, device=dev),
+                   scores=torch.empty((L, B), dtype=torch.float32, device=dev),
+                   exit=torch.empty((L, B), dtype=torch.int32, device=dev),
+                   first_exit=torch.empty((B,), dtype=torch.int32, device=dev))
+    dims = _dims(d, V, K, H, eps, threshold)
+    mlp = _mlp(W1, w2, b1, b2)
+    f16 = torch.float16
+    rc = lib().specee_predict_sweep(C.byref(dims), C.c_int(L), C.c_int(B), _ptr(hidden, f16), _ptr(gamma, f16),
+                                    _ptr(lm_head, f16), _ptr(ids, torch.int32), _ptr(prev0, torch.float32),
+                                    C.byref(mlp), _ptr(active, torch.int32), _ptr(out["logits"]),
+                                    _ptr(out["probs"]), _ptr(out["scores"]), _ptr(out["exit"]),
+                                    _ptr(out["first_exit"]), _stream(stream))
+    if rc:
+        raise SpeceeError("specee_predict_sweep", rc)
+    return out
+
+
+def predict_tree(hidden, gamma, lm_head, ids, prev_probs, W1, w2, b1=None, b2=None, parent=None, Mcap=64,
+                 eps=1e-5, threshold=0.5, want_path=None, out=None, workspace=None, stream=None):
+    """specee_predict_tree: hidden [G][N][d] (or [N][d] for a single tree)."""
+    single = hidden.dim() == 2
+    if single:
+        hidden, ids, prev_probs = hidden[None], ids[None], prev_probs[None]
+        parent = None if parent is None else parent[None]
+    G, N, d = hidden.shape
+    V = lm_head.shape[0]
+    K = ids.shape[2]
+    H = w2.shape[0]
+    dev = hidden.device
+    if want_path is None:
+        want_path = parent is not None
+    if out is None:
+        i32, f32 = torch.int32, torch.float32
+        out = dict(merged=torch.empty((G, Mcap), dtype=i32, device=dev), M=torch.empty((G,), dtype=i32, device=dev),
+                   cols=torch.empty((G, N, K), dtype=i32, device=dev),
+                   logits=torch.empty((G, N, K), dtype=f32, device=dev),
+                   probs=torch.empty((G, N, K), dtype=f32, device=dev),
+                   scores=torch.empty((G, N), dtype=f32, device=dev),
+                   exit=torch.empty((G, N), dtype=i32, device=dev),
+                   path_exit=torch.empty((G, N), dtype=i32, device=dev) if want_path else None)
+    dims = _dims(d, V, K, H, eps, threshold)
+    mlp = _mlp(W1, w2, b1, b2)
+    workspace, wbytes = _workspace(OP_PREDICT_TREE, dims, G * N, Mcap, workspace, dev)
+    f16 = torch.float16
+    rc = lib().specee_predict_tree(C.byref(dims), C.c_int(G), C.c_int(N), C.c_int(Mcap), _ptr(hidden, f16),
+                                   _ptr(gamma, f16), _ptr(lm_head, f16), _ptr(ids, torch.int32),
+                                   _ptr(parent, torch.int32), _ptr(prev_probs, torch.float32), C.byref(mlp),
+                                   _ptr(out["merged"]), _ptr(out["M"]), _ptr(out["cols"]), _ptr(out["logits"]),
+                                   _ptr(out["probs"]), _ptr(out["scores"]), _ptr(out["exit"]),
+                                   _ptr(out.get("path_exit")), _ptr(workspace), wbytes, _stream(stream))
+    if rc:
+        raise SpeceeError("specee_predict_tree", rc)
+    out["_workspace"] = workspace
+    if single:
+        return {k: (v[0] if (v is not None and k != "_workspace") else v) for k, v in out.items()}
+    return out
+
+
+def lm_head_gemv(hidden, gamma, lm_head, eps=1e-5, out=None, workspace=None, stream=None):
+    """lm_head_gemv: out [N][V] = RMSNorm(hidden) @ lm_head^T."""
+    N, d = hidden.shape
+    V = lm_head.shape[0]
+    dev = hidden.device
+    if out is None:
+        out = torch.empty((N, V), dtype=torch.float32, device=dev)
+    dims = _dims(d, V, 1, 1, eps, 0.5)
+    workspace, wbytes = _workspace(OP_LM_HEAD, dims, N, 0, workspace, dev)
+    f16 = torch.float16
+    rc = lib().lm_head_gemv(C.byref(dims), C.c_int(N), _ptr(hidden, f16), _ptr(gamma, f16), _ptr(lm_head, f16),
+                            _ptr(out, torch.float32), _ptr(workspace), wbytes, _stream(stream))
+    if rc:
+        raise SpeceeError("lm_head_gemv", rc)
+    return out
+
+
+def verify(hidden, gamma, lm_head, ids, eps=1e-5, out=None, workspace=None, stream=None):
+    """specee_verify: arg-max token of the full head and membership in the K ids."""
+    N, d = hidden.shape
+    V = lm_head.shape[0]
+    K = ids.shape[1]
+    dev = hidden.device
+    if out is None:
+        out = dict(token=torch.empty((N,), dtype=torch.int32, device=dev),
+                   max_logit=torch.empty((N,), dtype=torch.float32, device=dev),
+                   hit=torch.empty((N,), dtype=torch.int32, device=dev))
+    dims = _dims(d, V, K, 1, eps, 0.5)
+    workspace, wbytes = _workspace(OP_VERIFY, dims, N, 0, workspace, dev)
+    f16 = torch.float16
+    rc = lib().specee_verify(C.byref(dims), C.c_int(N), _ptr(hidden, f16), _ptr(gamma, f16), _ptr(lm_head, f16),
+                             _ptr(ids, torch.int32), _ptr(out["token"]), _ptr(out["max_logit"]), _ptr(out["hit"]),
+                             _ptr(workspace), wbytes, _stream(stream))
+    if rc:
+        raise SpeceeError("specee_verify", rc)
+    return out
+
+
+class Scheduler:
+    """Host-side online scheduler (specee_sched_*): circular queue of recent exit layers."""
+
+    def __init__(self, L, Q=5, radius=2, offline_mask=None):
+        self._s = Sched()
+        rc = lib().specee_sched_init(C.byref(self._s), int(L), int(Q), int(radius))
+        if rc:
+            raise SpeceeError("specee_sched_init", rc)
+        self.L = L
+        self._mask = None
+        if offline_mask is not None:
+            self._mask = (C.c_int32 * L)(*[int(x) for x in offline_mask])
+        self._active = (C.c_int32 * L)()
+
+    def push(self, exit_layer):
+        rc = lib().specee_sched_push(C.byref(self._s), int(exit_layer))
+        if rc:
+            raise SpeceeError("specee_sched_push", rc)
+
+    def active(self):
+        n = lib().specee_sched_active(C.byref(self._s), self._mask, self._active)
+        if n < 0:
+            raise SpeceeError("specee_sched_active", n)
+        return list(self._active)
+
+    def counters(self):
+        return list(self._s.counter[: self.L])
