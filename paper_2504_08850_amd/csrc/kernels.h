@@ -28,6 +28,48 @@ struct PredictParams {
 hipError_t launch_predict(const PredictParams &p, hipStream_t s);
 hipError_t launch_predict_sweep(const PredictParams &p, int32_t *first_exit, hipStream_t s);
 
+#define SPECEE_KMAX_INTERNAL 16
+
+// MFMA gather-contraction (gemm_kernels.hip)
+struct GemmParams {
+    int d, V, N;             // N hidden states per group
+    float eps;
+    const half_t *hidden;    // [G][N][d]
+    const half_t *gamma;     // [d]
+    const half_t *lm_head;   // [V][d]
+    const int32_t *rowlist;  // [G][Mcap] LM-head row of output column m, or null (row = m)
+    const int32_t *Mptr;     // [G] number of valid columns (device), or null (= Mcap)
+    int Mcap;
+    int dslice, S;           // k-range per workgroup (multiple of 64) and number of ranges
+    float *out;              // FINAL: [N][V] logits; else partial sums [G][S][Npad][Mpad]
+    float *ssq_part;         // [G][S][Npad] partial sums of h^2 (tree only)
+    int Mpad, Npad;
+};
+
+struct TreeFinishParams {
+    int d, V, K, H, N, S, Mcap, Mpad, Npad;
+    float eps, threshold;
+    const float *partial;    // [G][S][Npad][Mpad]
+    const float *ssq_part;   // [G][S][Npad]
+    const int32_t *ids;      // [G][N][K]
+    const int32_t *cols;     // [G][N][K]
+    const int32_t *M_out;    // [G]
+    const float *prev;       // [G][N][K]
+    const half_t *W1, *b1, *w2, *b2;
+    float *logits, *probs, *scores;
+    int32_t *exit_flags;
+};
+
+hipError_t launch_merge(const int32_t *ids, int n, int G, int Mcap, int32_t *merged, int32_t *M_out, int32_t *cols,
+                        hipStream_t st);
+hipError_t launch_tree_gemm(const GemmParams &p, int G, hipStream_t st);
+hipError_t launch_tree_finish(const TreeFinishParams &p, int G, hipStream_t st);
+hipError_t launch_path(const int32_t *exit_flags, const int32_t *parent, int N, int G, int32_t *path_exit,
+                       hipStream_t st);
+// Full-vocabulary head for several hidden states on the matrix cores
+hipError_t launch_lm_head_gemm(int d, int V, float eps, int N, const half_t *hidden, const half_t *gamma,
+                               const half_t *lm_head, float *out, hipStream_t st);
+
 // Full-vocabulary head, one hidden state per grid.y: out[n][v] = RMSNorm(h_n) . W[v]
 hipError_t launch_lm_head_gemv(int d, int V, float eps, int N, const half_t *hidden, const half_t *gamma,
                                const half_t *lm_head, float *out, hipStream_t s);

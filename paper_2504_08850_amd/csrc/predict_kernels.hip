@@ -13,38 +13,12 @@
 // fixed-order LDS exchange across the eight wavefronts.
 #include "device_utils.h"
 #include "kernels.h"
+#include "predictor_tail.h"
 
 namespace specee {
 
 constexpr int kPredictThreads = 512;
 constexpr int kPredictWaves = kPredictThreads / kWave;
-
-// softmax over K values held in registers (K <= KC)
-template <int KC>
-__device__ __forceinline__ void local_softmax(const float (&z)[KC], int K, float (&p)[KC]) {
-    float m = z[0];
-#pragma unroll
-    for (int k = 1; k < KC; ++k)
-        if (k < K) m = fmaxf(m, z[k]);
-    float s = 0.f;
-#pragma unroll
-    for (int k = 0; k < KC; ++k) {
-        p[k] = (k < K) ? expf(z[k] - m) : 0.f;
-        s += p[k];
-    }
-    float inv = 1.0f / s;
-#pragma unroll
-    for (int k = 0; k < KC; ++k) p[k] *= inv;
-    // NaN logits (invalid id) propagate: fmaxf would drop them, so poison explicitly
-    bool bad = false;
-#pragma unroll
-    for (int k = 0; k < KC; ++k)
-        if (k < K && z[k] != z[k]) bad = true;
-    if (bad) {
-#pragma unroll
-        for (int k = 0; k < KC; ++k) p[k] = quiet_nan();
-    }
-}
 
 // KC: speculative rows held in flight (K <= KC).  VPT: 16-byte vectors per
 // thread per row (d/8 <= VPT * 512 * tiles).  SWEEP: the previous layer's local
@@ -89,19 +63,8 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(PredictParams 
     const half_t *W1 = p.W1 + (size_t)l * H * 3 * K;
     const half_t *w2 = p.w2 + (size_t)l * H;
     const half_t *b1 = p.b1 ? p.b1 + (size_t)l * H : nullptr;
-    const bool vec_w1 = K == KC;                 // rows of 3*KC halves: 8-byte aligned, static feature index
-    uint2 w1pre[(3 * KC + 3) / 4];
-    float w2pre = 0.f, b1pre = 0.f;
-    if (tid < H) {
-        if (vec_w1) {
-            const uint2 *src = reinterpret_cast<const uint2 *>(W1 + (size_t)tid * 3 * K);
-#pragma unroll
-            for (int q = 0; q < (3 * KC + 3) / 4; ++q)
-                if (q * 4 < 3 * K) w1pre[q] = src[q];
-        }
-        w2pre = (float)w2[tid];
-        if (b1) b1pre = (float)b1[tid];
-    }
+    MlpRow<KC> row0;
+    mlp_row_load<KC>(row0, W1, b1, w2, K, H, tid);
 
     const half_t *hrow = p.hidden + tok * d;
     const half_t *hprow = (SWEEP && lprev >= 0) ? p.hidden + ((size_t)lprev * p.B + b) * d : nullptr;
@@ -241,55 +204,7 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(PredictParams 
     }
 
     // ---- MLP: thread j owns hidden unit j (+512, ...); f = [z | p | p - prev]
-    float part = 0.f;
-    for (int j = tid; j < H; j += kPredictThreads) {
-        float a, w2j;
-        if (j == tid) {
-            a = b1pre;
-            w2j = w2pre;
-        } else {
-            a = b1 ? (float)b1[j] : 0.f;
-            w2j = (float)w2[j];
-        }
-        if (vec_w1) {
-            uint2 wq[(3 * KC + 3) / 4];
-            if (j == tid) {
-#pragma unroll
-                for (int q = 0; q < (3 * KC + 3) / 4; ++q) wq[q] = w1pre[q];
-            } else {
-                const uint2 *src = reinterpret_cast<const uint2 *>(W1 + (size_t)j * 3 * K);
-#pragma unroll
-                for (int q = 0; q < (3 * KC + 3) / 4; ++q)
-                    if (q * 4 < 3 * K) wq[q] = src[q];
-            }
-            float f[3 * KC];
-#pragma unroll
-            for (int k = 0; k < KC; ++k) {
-                f[k] = z[k];
-                f[KC + k] = pr[k];
-                f[2 * KC + k] = pr[k] - prev[k];
-            }
-#pragma unroll
-            for (int q = 0; q < (3 * KC) / 4; ++q) {
-                half4 w4 = __builtin_bit_cast(half4, wq[q]);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) a += (float)w4[e] * f[q * 4 + e];
-            }
-        } else {
-            const half_t *src = W1 + (size_t)j * 3 * K;
-#pragma unroll
-            for (int k = 0; k < KC; ++k)
-                if (k < K) a += (float)src[k] * z[k];
-#pragma unroll
-            for (int k = 0; k < KC; ++k)
-                if (k < K) a += (float)src[K + k] * pr[k];
-#pragma unroll
-            for (int k = 0; k < KC; ++k)
-                if (k < K) a += (float)src[2 * K + k] * (pr[k] - prev[k]);
-        }
-        part += w2j * fmaxf(a, 0.f);
-        if (a != a) part = quiet_nan();  // fmaxf drops NaN; keep invalid ids visible
-    }
+    float part = mlp_partial<KC, kPredictThreads>(row0, W1, b1, w2, K, H, tid, z, pr, prev);
     part = wave_sum(part);
     if (lane == 0) red_u[wave] = part;
     __syncthreads();
@@ -298,7 +213,7 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(PredictParams 
         float u = p.b2 ? (float)p.b2[l] : 0.f;
 #pragma unroll
         for (int w = 0; w < kPredictWaves; ++w) u += red_u[w];
-        float s = 1.0f / (1.0f + expf(-u));
+        float s = sigmoidf(u);
         p.scores[tok] = s;
         p.exit_flags[tok] = (s > p.threshold) ? 1 : 0;
 #pragma unroll

@@ -33,6 +33,36 @@ const half_t *H(const specee_half *p) {
     return reinterpret_cast<const half_t *>(p);
 }
 
+// d-slices of the tree contraction: about 256 elements each, at most 128 slices, multiples of 64
+struct TreeSplit {
+    int S, dslice;
+};
+TreeSplit tree_split(int d) {
+    int S = (d + 255) / 256;
+    if (S > 128) S = 128;
+    int dslice = (((d + S - 1) / S + 63) / 64) * 64;
+    S = (d + dslice - 1) / dslice;
+    return {S, dslice};
+}
+
+inline size_t align256(size_t b) {
+    return (b + 255) & ~(size_t)255;
+}
+
+struct TreeLayout {
+    int Mpad;
+    size_t partial_off, ssq_off, total;
+};
+TreeLayout tree_layout(int d, int n_total, int Mcap) {
+    TreeSplit ts = tree_split(d);
+    TreeLayout L;
+    L.Mpad = ((Mcap + 15) / 16) * 16;
+    L.partial_off = 0;
+    L.ssq_off = align256((size_t)ts.S * n_total * L.Mpad * sizeof(float));
+    L.total = L.ssq_off + align256((size_t)ts.S * n_total * sizeof(float));
+    return L;
+}
+
 }  // namespace
 
 extern "C" {
@@ -60,8 +90,10 @@ size_t specee_workspace_bytes(int op, const specee_dims *dm, int n, int Mcap) {
             return check_dims(dm, true) ? (size_t)-1 : 0;
         case SPECEE_OP_LM_HEAD:
             return check_dims(dm, false) ? (size_t)-1 : 0;
+        case SPECEE_OP_PREDICT_TREE:
+            if (check_dims(dm, true) || Mcap < 1 || Mcap > 4096) return (size_t)-1;
+            return tree_layout(dm->d, n, Mcap).total;
         default:
-            (void)Mcap;
             return (size_t)-1;
     }
 }
@@ -122,9 +154,62 @@ int lm_head_gemv(const specee_dims *dm, int N, const specee_half *hidden, const 
     if (N == 0) return SPECEE_OK;
     if (!hidden || !gamma || !lm_head || !out) return SPECEE_EINVAL;
     if (misaligned(hidden) || misaligned(gamma) || misaligned(lm_head)) return SPECEE_EALIGN;
-    hipError_t e = launch_lm_head_gemv(dm->d, dm->V, dm->eps, N, H(hidden), H(gamma), H(lm_head), out,
-                                       static_cast<hipStream_t>(stream));
+    if (misaligned(out)) return SPECEE_EALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // one or two hidden states: stream the head once per state on the vector units;
+    // more: one pass over the head on the matrix cores
+    hipError_t e = (N <= 2) ? launch_lm_head_gemv(dm->d, dm->V, dm->eps, N, H(hidden), H(gamma), H(lm_head), out, st)
+                            : launch_lm_head_gemm(dm->d, dm->V, dm->eps, N, H(hidden), H(gamma), H(lm_head), out, st);
     return e == hipSuccess ? SPECEE_OK : SPECEE_EHIP;
+}
+
+int specee_predict_tree(const specee_dims *dm, int G, int N, int Mcap, const specee_half *hidden,
+                        const specee_half *gamma, const specee_half *lm_head, const int32_t *ids,
+                        const int32_t *parent, const float *prev_probs, const specee_mlp *mlp, int32_t *merged_ids,
+                        int32_t *M_out, int32_t *cols, float *logits, float *probs, float *scores,
+                        int32_t *exit_flags, int32_t *path_exit, void *workspace, size_t workspace_bytes,
+                        void *stream) {
+    int rc = check_dims(dm, true);
+    if (rc) return rc;
+    if (G < 0 || N < 1 || Mcap < 1 || Mcap > 4096 || (long long)N * dm->K > 4096) return SPECEE_EINVAL;
+    if ((long long)G * N > (1 << 24) || G > 65535) return SPECEE_EINVAL;
+    if (G == 0) return SPECEE_OK;
+    if ((rc = check_mlp(mlp))) return rc;
+    if (!hidden || !gamma || !lm_head || !ids || !prev_probs || !merged_ids || !M_out || !cols || !logits ||
+        !probs || !scores || !exit_flags)
+        return SPECEE_EINVAL;
+    if (path_exit && !parent) return SPECEE_EINVAL;
+    if (probs == prev_probs) return SPECEE_EINVAL;
+    if (misaligned(hidden) || misaligned(gamma) || misaligned(lm_head) || misaligned(workspace)) return SPECEE_EALIGN;
+    const TreeSplit ts = tree_split(dm->d);
+    const TreeLayout lay = tree_layout(dm->d, G * N, Mcap);
+    if (!workspace || workspace_bytes < lay.total) return SPECEE_EWORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    float *partial = reinterpret_cast<float *>(ws + lay.partial_off);
+    float *ssq_part = reinterpret_cast<float *>(ws + lay.ssq_off);
+
+    if (launch_merge(ids, N * dm->K, G, Mcap, merged_ids, M_out, cols, st) != hipSuccess) return SPECEE_EHIP;
+
+    GemmParams gp{};
+    gp.d = dm->d; gp.V = dm->V; gp.N = N; gp.eps = dm->eps;
+    gp.hidden = H(hidden); gp.gamma = H(gamma); gp.lm_head = H(lm_head);
+    gp.rowlist = merged_ids; gp.Mptr = M_out; gp.Mcap = Mcap;
+    gp.dslice = ts.dslice; gp.S = ts.S;
+    gp.out = partial; gp.ssq_part = ssq_part; gp.Mpad = lay.Mpad; gp.Npad = N;
+    if (launch_tree_gemm(gp, G, st) != hipSuccess) return SPECEE_EHIP;
+
+    TreeFinishParams fp{};
+    fp.d = dm->d; fp.V = dm->V; fp.K = dm->K; fp.H = dm->H; fp.N = N; fp.S = ts.S; fp.Mcap = Mcap;
+    fp.Mpad = lay.Mpad; fp.Npad = N; fp.eps = dm->eps; fp.threshold = dm->threshold;
+    fp.partial = partial; fp.ssq_part = ssq_part; fp.ids = ids; fp.cols = cols; fp.M_out = M_out;
+    fp.prev = prev_probs;
+    fp.W1 = H(mlp->W1); fp.b1 = H(mlp->b1); fp.w2 = H(mlp->w2); fp.b2 = H(mlp->b2);
+    fp.logits = logits; fp.probs = probs; fp.scores = scores; fp.exit_flags = exit_flags;
+    if (launch_tree_finish(fp, G, st) != hipSuccess) return SPECEE_EHIP;
+
+    if (path_exit && launch_path(exit_flags, parent, N, G, path_exit, st) != hipSuccess) return SPECEE_EHIP;
+    return SPECEE_OK;
 }
 
 }  // extern "C"

@@ -1,0 +1,259 @@
+"""GPU parity: specee_predict_tree (merged mapping) and the multi-state full-vocabulary head
+against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2504_08850_amd import synth
+
+from parity import check_scored, close, dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def sp():
+    from paper_2504_08850_amd import specee
+    specee.lib()
+    assert torch.cuda.is_available()
+    return specee
+
+
+_LM = {}
+
+
+def lm_for(c):
+    key = (c.V, c.d)
+    if key not in _LM:
+        _LM.clear()      # keep at most one large head resident
+        h = synth.lm_head(c.V, c.d, synth.lm_seed(c))
+        _LM[key] = (h, dev(h))
+    return _LM[key]
+
+
+def run_tree(sp, t, lm_d, Mcap, parent="auto", **kw):
+    par = t.get("parent") if isinstance(parent, str) else parent
+    out = sp.predict_tree(dev(t["hidden"]), dev(t["gamma"]), lm_d, dev(t["ids"]), dev(t["prev_probs"]),
+                          dev(t["W1"]), dev(t["w2"]), dev(t["b1"]), dev(t["b2"]), parent=dev(par), Mcap=Mcap, **kw)
+    torch.cuda.synchronize()
+    return {k: host(v) for k, v in out.items() if k != "_workspace"}
+
+
+def check_tree(got, ref, thr, what):
+    # integer outputs: bit-exact
+    assert np.array_equal(got["M"], ref["M"]), what + " M"
+    assert np.array_equal(got["merged"], ref["merged"]), what + " merged ids"
+    assert np.array_equal(got["cols"], ref["cols"]), what + " cols"
+    e = check_scored(got, ref, thr, what)
+    if ref.get("path_exit") is not None:
+        decided = np.abs(ref["scores"] - thr) > 1e-4
+        if decided.all():
+            assert np.array_equal(got["path_exit"], ref["path_exit"]), what + " path_exit"
+    return e
+
+
+def ref_tree(oracle, t, Mcap, **kw):
+    return oracle.predict_tree(t["hidden"], t["gamma"], t["lm_head"], t["ids"], t["prev_probs"], t["W1"], t["w2"],
+                               t["b1"], t["b2"], parent=t.get("parent"), Mcap=Mcap, **kw)
+
+
+@pytest.mark.parametrize("name,bias", [("T3", False), ("T4", True)])
+def test_tree_small(sp, oracle, name, bias):
+    t = synth.make(name, bias=bias)
+    c = t["cfg"]
+    ref = ref_tree(oracle, t, c.Mcap)
+    got = run_tree(sp, t, dev(t["lm_head"]), c.Mcap)
+    e = check_tree(got, ref, c.threshold, name)
+    print(name, "M", ref["M"], "worst", e)
+
+
+def test_tree_equals_independent_predict_calls_on_gpu(sp):
+    """Merged mapping == N independent per-node predictors (two different GPU code paths)."""
+    t = synth.make("T3")
+    c = t["cfg"]
+    lm_d = dev(t["lm_head"])
+    tree = run_tree(sp, t, lm_d, c.Mcap)
+    ind = sp.predict(dev(t["hidden"]), dev(t["gamma"]), lm_d, dev(t["ids"]), dev(t["prev_probs"]), dev(t["W1"]),
+                     dev(t["w2"]))
+    torch.cuda.synchronize()
+    close(tree["logits"], host(ind["logits"]), 1.0, "tree vs independent logits")
+    close(tree["scores"], host(ind["scores"]), 1e-3, "tree vs independent scores")
+
+
+def make_tree(seed, d, V, K, H, N, ids=None, bias=False):
+    rng = np.random.default_rng(seed)
+    t = dict(
+        hidden=rng.standard_normal((N, d)).astype(np.float16),
+        gamma=(1 + 0.05 * rng.standard_normal(d)).astype(np.float16),
+        lm_head=(0.05 * rng.standard_normal((V, d))).astype(np.float16),
+        ids=ids if ids is not None else rng.integers(0, V, size=(N, K)).astype(np.int32),
+        prev_probs=rng.dirichlet(np.ones(K), size=N).astype(np.float32),
+        W1=(0.1 * rng.standard_normal((H, 3 * K))).astype(np.float16),
+        w2=(0.1 * rng.standard_normal(H)).astype(np.float16),
+        b1=(0.1 * rng.standard_normal(H)).astype(np.float16) if bias else None,
+        b2=(0.1 * rng.standard_normal(1)).astype(np.float16) if bias else None,
+        parent=np.array([-1] + [int(rng.integers(0, n)) for n in range(1, N)], np.int32))
+    return t
+
+
+def test_tree_all_nodes_share_ids_and_all_distinct(sp, oracle):
+    same = np.tile(np.array([[17, 3, 250, 99]], np.int32), (20, 1))
+    t = make_tree(1, 512, 300, 4, 64, 20, ids=same)
+    ref = ref_tree(oracle, t, 16)
+    assert ref["M"] == 4
+    check_tree(run_tree(sp, t, dev(t["lm_head"]), 16), ref, 0.5, "shared ids")
+    distinct = np.random.default_rng(2).permutation(300)[:80].reshape(20, 4).astype(np.int32)
+    t = make_tree(3, 512, 300, 4, 64, 20, ids=distinct)
+    ref = ref_tree(oracle, t, 80)
+    assert ref["M"] == 80
+    check_tree(run_tree(sp, t, dev(t["lm_head"]), 80), ref, 0.5, "distinct ids")
+
+
+@pytest.mark.parametrize("d,V,K,H,N,Mcap", [
+    (8, 9, 1, 1, 1, 1),              # smallest legal tree
+    (64, 40, 2, 8, 100, 40),         # more than 64 nodes: two node blocks, duplicate ids inside a node allowed
+    (520, 777, 8, 512, 21, 168),     # ragged d (not a multiple of 64)
+    (4096, 2000, 4, 512, 60, 64),    # C3 shape on a small vocabulary, random (non-pooled) ids capped by V
+    (1024, 5000, 16, 300, 50, 800),  # K = KMAX, several row groups
+    (2048, 64, 3, 2048, 17, 51),     # K odd, H = HMAX
+])
+def test_tree_shapes(sp, oracle, d, V, K, H, N, Mcap):
+    t = make_tree(d + N, d, V, K, H, N, bias=(K % 2 == 1))
+    if len(np.unique(t["ids"])) > Mcap:
+        pool = np.random.default_rng(0).permutation(V)[:Mcap]
+        t["ids"] = pool[np.random.default_rng(1).integers(0, Mcap, size=(N, K))].astype(np.int32)
+    ref = ref_tree(oracle, t, Mcap)
+    check_tree(run_tree(sp, t, dev(t["lm_head"]), Mcap), ref, 0.5, f"tree d={d} K={K} N={N}")
+
+
+def test_tree_batch_of_independent_trees(sp, oracle):
+    ts = [synth.make("T4", seed=s) for s in range(3)]
+    c = ts[0]["cfg"]
+    stack = lambda k: np.stack([t[k] for t in ts])
+    tb = dict(ts[0], hidden=stack("hidden"), ids=stack("ids"), prev_probs=stack("prev_probs"), parent=stack("parent"))
+    ref = ref_tree(oracle, tb, c.Mcap)
+    got = run_tree(sp, tb, dev(tb["lm_head"]), c.Mcap)
+    check_tree(got, ref, c.threshold, "batched trees")
+    assert len(set(ref["M"].tolist())) > 1       # trees really differ in merged size
+
+
+def test_tree_without_parent_and_with_malformed_parent(sp, oracle):
+    t = synth.make("T4")
+    c = t["cfg"]
+    lm_d = dev(t["lm_head"])
+    got = run_tree(sp, t, lm_d, c.Mcap, parent=None)
+    assert got["path_exit"] is None
+    ref = ref_tree(oracle, dict(t, parent=None), c.Mcap)
+    check_tree(got, ref, c.threshold, "no parent")
+    bad = t["parent"].copy()
+    bad[5] = 9                                    # points forward: the path is refused, nothing loops
+    got = run_tree(sp, t, lm_d, c.Mcap, parent=bad)
+    assert got["path_exit"][5] == 0
+
+
+def test_tree_merged_set_overflow_and_invalid_ids(sp, oracle):
+    t = synth.make("T4")
+    c = t["cfg"]
+    lm_d = dev(t["lm_head"])
+    true_M = len(np.unique(t["ids"]))
+    got = run_tree(sp, t, lm_d, true_M - 1)
+    assert got["M"] == true_M                     # the true size is reported
+    assert np.all(np.isnan(got["scores"])) and got["exit"].sum() == 0 and got["path_exit"].sum() == 0
+    t2 = dict(t, ids=t["ids"].copy())
+    t2["ids"][4, 2] = c.V + 5
+    t2["ids"][9, 0] = -1
+    got = run_tree(sp, t2, lm_d, c.Mcap)
+    u = np.unique(t2["ids"])
+    assert got["M"] == len(u) and np.array_equal(got["merged"][:len(u)], u)
+    good = np.ones(c.N, bool); good[[4, 9]] = False
+    assert np.all(np.isnan(got["scores"][~good])) and np.all(got["exit"][~good] == 0)
+    ref = ref_tree(oracle, t, c.Mcap)
+    close(got["scores"][good], ref["scores"][good], 1e-3, "valid nodes beside invalid ones")
+
+
+def test_tree_argument_errors(sp):
+    t = synth.make("T4")
+    c = t["cfg"]
+    lm_d = dev(t["lm_head"])
+    with pytest.raises(sp.SpeceeError) as ei:
+        run_tree(sp, t, lm_d, c.Mcap, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert ei.value.code == -3
+    with pytest.raises(sp.SpeceeError) as ei:
+        run_tree(sp, t, lm_d, 5000)
+    assert ei.value.code == -1
+
+
+def test_tree_is_deterministic(sp):
+    t = synth.make("T3")
+    lm_d = dev(t["lm_head"])
+    a = run_tree(sp, t, lm_d, 96)
+    b = run_tree(sp, t, lm_d, 96)
+    for k in a:
+        if a[k] is not None:
+            assert np.array_equal(a[k], b[k]), k
+
+
+def test_tree_c3_llama7b_60_nodes(sp, oracle):
+    c = synth.CONFIGS["C3"]
+    lm_h, lm_d = lm_for(c)
+    for seed in range(3):
+        t = synth.make("C3", seed=seed, lm=lm_h)
+        oracle.set_threads(8)
+        ref = ref_tree(oracle, t, c.Mcap)
+        oracle.set_threads(1)
+        got = run_tree(sp, t, lm_d, c.Mcap)
+        e = check_tree(got, ref, c.threshold, f"C3 seed {seed}")
+        print("C3 seed", seed, "M", int(ref["M"]), "exits", int(ref["exit"].sum()), "paths",
+              int(ref["path_exit"].sum()), "worst", e)
+        assert 0 < ref["exit"].sum() < c.N and ref["M"] <= 64
+
+
+# ---------------------------------------------------------------- multi-state full head (matrix cores)
+@pytest.mark.parametrize("d,V,N", [(64, 37, 3), (1032, 1001, 5), (4096, 515, 16), (520, 4100, 64), (2048, 300, 70)])
+def test_lm_head_multi_state_small(sp, oracle, d, V, N):
+    rng = np.random.default_rng(d + V + N)
+    h = rng.standard_normal((N, d)).astype(np.float16)
+    g = (1 + 0.05 * rng.standard_normal(d)).astype(np.float16)
+    W = (0.05 * rng.standard_normal((V, d))).astype(np.float16)
+    ref = oracle.lm_head_gemv(h, g, W)
+    got = host(sp.lm_head_gemv(dev(h), dev(g), dev(W)))
+    close(got, ref, 1.0, f"lm_head gemm d={d} V={V} N={N}")
+
+
+def test_lm_head_16_states_llama13b_sampled_rows(sp, oracle):
+    c = synth.CONFIGS["C4"]
+    lm_h, lm_d = lm_for(c)
+    t = synth.make("C4", lm=lm_h)
+    h = t["hidden"][0]
+    got = host(sp.lm_head_gemv(dev(h), dev(t["gamma"]), lm_d))
+    rows = np.unique(np.concatenate([np.random.default_rng(0).integers(0, c.V, 2048), [0, c.V - 1],
+                                     t["ids"].ravel()])).astype(np.int32)
+    oracle.set_threads(8)
+    ref = oracle.lm_head_rows(h, t["gamma"], lm_h, rows)
+    oracle.set_threads(1)
+    close(got[:, rows], ref, 1.0, "lm_head 32000x5120 N=16 sampled rows")
+
+
+def test_c5_large_vocab_tree_and_full_head(sp, oracle):
+    """d=8192, V=128256, K=8, 64-node tree; plus lm_head_gemv on the same hidden states (sampled rows)."""
+    c = synth.CONFIGS["C5"]
+    lm_h, lm_d = lm_for(c)
+    t = synth.make("C5", lm=lm_h)
+    oracle.set_threads(8)
+    ref = ref_tree(oracle, t, c.Mcap)
+    got = run_tree(sp, t, lm_d, c.Mcap)
+    e = check_tree(got, ref, c.threshold, "C5")
+    print("C5 M", int(ref["M"]), "exits", int(ref["exit"].sum()), "worst", e)
+    assert ref["M"] <= 256 and 0 < ref["exit"].sum() < c.N
+    full = host(sp.lm_head_gemv(dev(t["hidden"]), dev(t["gamma"]), lm_d))
+    rows = np.unique(np.concatenate([np.random.default_rng(1).integers(0, c.V, 1024), [0, c.V - 1],
+                                     ref["merged"][:int(ref["M"])]])).astype(np.int32)
+    ref_rows = oracle.lm_head_rows(t["hidden"], t["gamma"], lm_h, rows)
+    w = close(full[:, rows], ref_rows, 1.0, "lm_head 128256x8192 N=64 sampled rows")
+    one = host(sp.lm_head_gemv(dev(t["hidden"][:1]), dev(t["gamma"]), lm_d))
+    close(one[:, rows], ref_rows[:1], 1.0, "lm_head 128256x8192 N=1 sampled rows")
+    oracle.set_threads(1)
+    # the tree's logits are the full head's logits at the ids
+    idx = t["ids"]
+    close(got["logits"], np.take_along_axis(full, idx, axis=1), 1.0, "tree logits vs full head")
+    print("C5 lm_head worst", w)
