@@ -1,0 +1,437 @@
+#!/usr/bin/env python3
+"""Benchmark of the SpecEE speculative early-exit predictor on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--only NAME] [--no-cpu]
+
+One *step* is the full per-token hot path at the Llama2-7B shape with K=4 (the
+"32-layer exit sweep for one token" workload): 32 dependent specee_predict calls,
+one per decoder layer with that layer's predictor, each consuming the local
+probabilities the previous call produced.  The calls are captured once into a HIP
+graph per input set and the timed region replays graphs, rotating over input sets
+(different hidden states and speculative ids) so that the LM-head rows of a step
+are not in cache from the step before.  All inputs are resident in HBM before the
+timed region; nothing is copied from or to the host inside it.
+
+The single JSON line also carries, under "extra", the latency of the other
+workloads (single step, token trees, full-vocabulary head and the speed-up over
+it) and a throughput mode (many independent problems per launch) with its own
+fraction of the HBM roofline; "cpu_baseline" times the CPU oracle on the same
+workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
+H = 512
+
+# HBM bytes per launch of the dominant kernels, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs scaled by the same counters on specee_calib_copy (see profiles/); None = not measured.
+MEASURED_TRAFFIC = {}
+_traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json.txt")
+if os.path.exists(_traffic_file):
+    try:
+        MEASURED_TRAFFIC = json.loads(open(_traffic_file).read().split("---JSON---")[1])
+    except Exception:  # noqa: BLE001 - a malformed summary must not break the benchmark
+        MEASURED_TRAFFIC = {}
+
+
+def predict_bytes(d, K, B=1, Hh=H, distinct_rows=None):
+    """Algorithmic bytes of one predictor launch: hidden states + RMSNorm weight + distinct
+    LM-head rows + predictor weights + ids/prev/outputs."""
+    rows = B * K if distinct_rows is None else distinct_rows
+    return B * d * 2 + d * 2 + rows * d * 2 + (3 * K * Hh + Hh) * 2 + B * (K * 4 + K * 4 + 2 * K * 4 + 8)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--sets", type=int, default=64, help="rotating input sets")
+    ap.add_argument("--only", default="", help="comma-separated sections: sweep,single,batch,tree,lmhead,c4,c5,copy")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-extra", action="store_true", help="only the headline step")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (--gpus 1); the predictor shards by token with no "
+              "communication, see DESIGN.md", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2504_08850_amd import specee as sp
+    from paper_2504_08850_amd import synth
+
+    sp.lib()
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    def up(a):
+        return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+    def ev_time(fn, iters, warm):
+        """milliseconds per call of fn, HIP events on the stream the kernels run on"""
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    def capture(fn):
+        """Capture fn's launches into a HIP graph; returns the graph."""
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            fn()
+        torch.cuda.current_stream().wait_stream(s)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            fn()
+        torch.cuda.synchronize()
+        return g
+
+    only = set(x for x in args.only.split(",") if x)
+
+    def want(*names):
+        return not only or bool(only & set(names))
+    extra = {}
+    c2 = synth.CONFIGS["C2"]
+    d, V, K, L = c2.d, c2.V, c2.K, c2.L
+    t_setup = time.time()
+    lm_h = synth.lm_head(V, d, synth.lm_seed(c2))
+    lm = up(lm_h)
+    base = synth.make("C2", lm=lm_h)
+    gamma = up(base["gamma"])
+    W1, w2 = up(base["W1"]), up(base["w2"])           # one predictor per layer, shared by all tokens
+
+    # ------------------------------------------------------------------ headline: C2 sweep, 32 dependent calls
+    R = args.sets
+    result = None
+    if want("sweep"):
+        sets = []
+        for r in range(R):
+            hid = up(synth.hidden_drift(L, 1, d, 50_000 + r))
+            ids = up(synth.ids_uniform_distinct(1, K, V, 60_000 + r))
+            out = dict(logits=torch.empty((L, 1, K), device=dev), probs=torch.empty((L, 1, K), device=dev),
+                       scores=torch.empty((L, 1), device=dev), exit=torch.empty((L, 1), dtype=torch.int32, device=dev))
+            zero = torch.zeros((1, K), device=dev)
+            sets.append((hid, ids, out, zero))
+
+        def sweep_calls(r):
+            hid, ids, out, zero = sets[r]
+            for l in range(L):
+                o = dict(logits=out["logits"][l], probs=out["probs"][l], scores=out["scores"][l], exit=out["exit"][l])
+                sp.predict(hid[l], gamma, lm, ids, zero if l == 0 else out["probs"][l - 1], W1[l], w2[l], out=o)
+
+        graphs = [capture(lambda r=r: sweep_calls(r)) for r in range(R)]
+        for w in range(args.warmup):
+            graphs[w % R].replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for k in range(args.steps):
+            graphs[k % R].replay()
+        e1.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        ms_per_step = e0.elapsed_time(e1) / args.steps
+        us_per_call = ms_per_step * 1e3 / L
+        alg = predict_bytes(d, K)
+        achieved = alg / (us_per_call * 1e-6) / 1e9
+        result = {
+            "metric": "predictor evals/s (Llama2-7B shape, K=4; per-layer speculative early-exit predictor)",
+            "value": L / (ms_per_step * 1e-3),
+            "unit": "evals/s",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": ms_per_step,
+            "us_per_call": us_per_call,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "f32 (fp16 inputs widened, fp32 accumulation)", "data": "synthetic",
+            "config": {"workload": "C2: 32-layer exit sweep for one token, d=4096 V=32000 K=4, MLP 12->512->1, "
+                                   "32 dependent specee_predict launches per step (HIP graph replay), "
+                                   f"{R} rotating input sets", "batch": 1, "layers": L},
+            "roofline": {"bound": "hbm", "kernel": "predict_kernel<4,1,false>", "achieved": achieved,
+                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                         "algorithmic_bytes_per_launch": alg,
+                         "traffic": MEASURED_TRAFFIC.get("predict_c2"),
+                         "note": "one call moves 62 KB, far below the ~8 MB bandwidth-delay product of HBM: this "
+                                 "mode is bound by two dependent memory round trips plus launch, not by bandwidth; "
+                                 "see extra.throughput for the bandwidth-bound mode"},
+            "wall_ms_timed_region": wall_ms,
+        }
+        # the same sweep as ONE launch of specee_predict_sweep (all layers' hidden states known up front)
+        if not args.no_extra:
+            hid0, ids0, _, _ = sets[0]
+            so = sp.predict_sweep(hid0, gamma, lm, ids0, W1, w2)
+            gs = [capture(lambda r=r: sp.predict_sweep(sets[r][0], gamma, lm, sets[r][1], W1, w2, out=so))
+                  for r in range(min(R, 16))]
+            it = [0]
+
+            def rot():
+                gs[it[0] % len(gs)].replay()
+                it[0] += 1
+            ms = ev_time(rot, 400, 40)
+            extra["c2_one_launch_sweep"] = {"us_per_sweep": ms * 1e3, "evals_per_s": L / (ms * 1e-3)}
+
+    # ------------------------------------------------------------------ C1: isolated single call, cold vs warm
+    if want("single") and not args.no_extra:
+        t1 = synth.make("C1", lm=lm_h)
+        R1 = 256
+        hid = up(synth.hidden(R1, d, 123))
+        ids = up(synth.ids_uniform_distinct(R1, K, V, 124))
+        prev = up(synth.prob_rows(R1, K, 125))
+        w1_1, w2_1 = up(t1["W1"]), up(t1["w2"])
+        outs = sp.predict(hid[:1], gamma, lm, ids[:1], prev[:1], w1_1, w2_1)
+
+        def cold_calls():
+            for r in range(R1):
+                sp.predict(hid[r:r + 1], gamma, lm, ids[r:r + 1], prev[r:r + 1], w1_1, w2_1, out=outs)
+
+        def warm_calls():
+            for r in range(R1):
+                sp.predict(hid[:1], gamma, lm, ids[:1], prev[:1], w1_1, w2_1, out=outs)
+        gc, gw = capture(cold_calls), capture(warm_calls)
+        us_cold = ev_time(gc.replay, 20, 3) * 1e3 / R1
+        us_warm = ev_time(gw.replay, 20, 3) * 1e3 / R1
+        extra["c1_single_call"] = {"us_per_call_rotated_ids": us_cold, "us_per_call_same_inputs": us_warm,
+                                   "algorithmic_bytes": predict_bytes(d, K)}
+
+    # ------------------------------------------------------------------ full-vocabulary head, N=1 (what the predictor replaces)
+    lm_us = None
+    if want("lmhead") and not args.no_extra:
+        hid = up(synth.hidden(8, d, 321))
+        out_full = torch.empty((1, V), device=dev)
+        it = [0]
+
+        def full():
+            sp.lm_head_gemv(hid[it[0] % 8:it[0] % 8 + 1], gamma, lm, out=out_full)
+            it[0] += 1
+        g = capture(lambda: [full() for _ in range(8)])
+        lm_us = ev_time(g.replay, 30, 5) * 1e3 / 8
+        byts = V * d * 2 + d * 4 + V * 4
+        extra["lm_head_gemv_32000x4096"] = {
+            "us_per_call": lm_us, "achieved_GBps": byts / lm_us / 1e3, "frac_of_8TBps": byts / lm_us / 1e3 / HBM_PEAK_GBS,
+            "algorithmic_bytes": byts, "traffic": MEASURED_TRAFFIC.get("lm_head_gemv_7b"),
+            "note": "262 MB head is re-read every call; the 256 MB Infinity Cache can hold part of it"}
+        vids = up(synth.ids_uniform_distinct(1, K, V, 5))
+        vout = sp.verify(hid[:1], gamma, lm, vids)
+        vws = torch.empty(sp.workspace_bytes(sp.OP_VERIFY, sp.Dims(d, V, K, 1, 1e-5, 0.5), 1), dtype=torch.uint8,
+                          device=dev)
+        gv = capture(lambda: [sp.verify(hid[i:i + 1], gamma, lm, vids, out=vout, workspace=vws) for i in range(8)])
+        v_us = ev_time(gv.replay, 30, 5) * 1e3 / 8
+        extra["specee_verify_32000x4096"] = {"us_per_call": v_us, "achieved_GBps": V * d * 2 / v_us / 1e3}
+        if result is not None:
+            extra["speedup_vs_full_vocab_head"] = {
+                "predictor_us": result["us_per_call"], "lm_head_gemv_us": lm_us,
+                "ratio": lm_us / result["us_per_call"]}
+
+    # ------------------------------------------------------------------ throughput mode: many independent tokens per launch
+    if want("batch") and not args.no_extra:
+        tp = {}
+        t1 = synth.make("C1", lm=lm_h)
+        w1_1, w2_1 = up(t1["W1"]), up(t1["w2"])
+        for B in (16, 256, 4096, 16384):
+            rng = np.random.default_rng(B)
+            hid = up(rng.standard_normal((B, d), dtype=np.float32).astype(np.float16))
+            ids_h = rng.integers(0, V, size=(B, K)).astype(np.int32)
+            ids = up(ids_h)
+            prev = up(synth.prob_rows(B, K, 9))
+            o = sp.predict(hid, gamma, lm, ids, prev, w1_1, w2_1)
+            reps = 8
+            g = capture(lambda: [sp.predict(hid, gamma, lm, ids, prev, w1_1, w2_1, out=o) for _ in range(reps)])
+            us = ev_time(g.replay, 20, 3) * 1e3 / reps
+            byts = predict_bytes(d, K, B, distinct_rows=len(np.unique(ids_h)))
+            tp[f"B={B}"] = {"us_per_launch": us, "evals_per_s": B / us * 1e6, "algorithmic_bytes": byts,
+                            "achieved_GBps": byts / us / 1e3, "frac_of_8TBps": byts / us / 1e3 / HBM_PEAK_GBS}
+        tp["traffic_B4096"] = MEASURED_TRAFFIC.get("predict_B4096")
+        extra["throughput_predict_7b"] = tp
+
+    # ------------------------------------------------------------------ C3 tree (latency) and batches of trees (throughput)
+    if want("tree") and not args.no_extra:
+        c3 = synth.CONFIGS["C3"]
+        trees = [synth.make("C3", seed=s, lm=lm_h) for s in range(32)]
+        tw1, tw2 = up(trees[0]["W1"]), up(trees[0]["w2"])
+        dev_trees = [(up(t["hidden"]), up(t["ids"]), up(t["prev_probs"]), up(t["parent"])) for t in trees]
+        Ms = [len(np.unique(t["ids"])) for t in trees]
+        o = sp.predict_tree(dev_trees[0][0], gamma, lm, dev_trees[0][1], dev_trees[0][2], tw1, tw2,
+                            parent=dev_trees[0][3], Mcap=c3.Mcap)
+        ws = o["_workspace"]
+        # preallocate outputs once so the graph holds no allocations
+        outs = [sp.predict_tree(hh, gamma, lm, ii, pp, tw1, tw2, parent=par, Mcap=c3.Mcap, workspace=ws)
+                for (hh, ii, pp, par) in dev_trees]
+
+        def tree_calls_prealloc():
+            for (hh, ii, pp, par), oo in zip(dev_trees, outs):
+                oo2 = {k: (v[None] if v is not None else None) for k, v in oo.items() if k != "_workspace"}
+                sp.predict_tree(hh[None], gamma, lm, ii[None], pp[None], tw1, tw2, parent=par[None], Mcap=c3.Mcap,
+                                out=oo2, workspace=ws)
+        g = capture(tree_calls_prealloc)
+        us = ev_time(g.replay, 20, 3) * 1e3 / len(dev_trees)
+        byts = int(np.mean([c3.N * d * 2 + m * d * 2 for m in Ms])) + d * 2 + (3 * K * H + H) * 2
+        extra["c3_tree_N60"] = {"us_per_call": us, "mean_M": float(np.mean(Ms)), "algorithmic_bytes": byts,
+                                "achieved_GBps": byts / us / 1e3, "node_evals_per_s": c3.N / us * 1e6}
+        # throughput: G trees per launch
+        for G in (64, 256):
+            ii = torch.stack([dev_trees[i % 32][1] for i in range(G)])
+            pp = torch.stack([dev_trees[i % 32][2] for i in range(G)])
+            par = torch.stack([dev_trees[i % 32][3] for i in range(G)])
+            # different hidden states per tree so nothing is shared between trees but the LM head
+            hh = up(synth.hidden(c3.N, d, 999, lead=(G,)))
+            og = sp.predict_tree(hh, gamma, lm, ii, pp, tw1, tw2, parent=par, Mcap=c3.Mcap)
+            wsg = og.pop("_workspace")
+            g = capture(lambda: sp.predict_tree(hh, gamma, lm, ii, pp, tw1, tw2, parent=par, Mcap=c3.Mcap, out=og,
+                                                workspace=wsg))
+            us = ev_time(g.replay, 20, 3) * 1e3
+            bytsG = sum(c3.N * d * 2 + Ms[i % 32] * d * 2 for i in range(G)) + d * 2 + (3 * K * H + H) * 2
+            extra[f"c3_tree_batch_G{G}"] = {"us_per_launch": us, "node_evals_per_s": G * c3.N / us * 1e6,
+                                            "algorithmic_bytes": bytsG, "achieved_GBps": bytsG / us / 1e3,
+                                            "frac_of_8TBps": bytsG / us / 1e3 / HBM_PEAK_GBS}
+
+    # ------------------------------------------------------------------ C4: 13B shape, 16 sequences x 40 layers
+    if want("c4") and not args.no_extra:
+        del lm
+        torch.cuda.empty_cache()
+        c4 = synth.CONFIGS["C4"]
+        lm4_h = synth.lm_head(c4.V, c4.d, synth.lm_seed(c4))
+        lm4 = up(lm4_h)
+        t4 = synth.make("C4", lm=lm4_h)
+        T4 = {k: up(v) for k, v in t4.items() if k not in ("cfg", "lm_head")}
+        # per-layer batched call (decode-time use): 40 dependent launches of B=16
+        o4 = dict(logits=torch.empty((c4.L, c4.B, c4.K), device=dev), probs=torch.empty((c4.L, c4.B, c4.K), device=dev),
+                  scores=torch.empty((c4.L, c4.B), device=dev),
+                  exit=torch.empty((c4.L, c4.B), dtype=torch.int32, device=dev))
+        zero = torch.zeros((c4.B, c4.K), device=dev)
+
+        def c4_calls():
+            for l in range(c4.L):
+                o = {k: v[l] for k, v in o4.items()}
+                sp.predict(T4["hidden"][l], T4["gamma"], lm4, T4["ids"], zero if l == 0 else o4["probs"][l - 1],
+                           T4["W1"][l], T4["w2"][l], out=o)
+        g = capture(c4_calls)
+        ms = ev_time(g.replay, 50, 5)
+        nrows = len(np.unique(t4["ids"]))
+        byts_layer = predict_bytes(c4.d, c4.K, c4.B, distinct_rows=nrows)
+        extra["c4_13b_16seq_per_layer_calls"] = {
+            "us_per_layer_call": ms * 1e3 / c4.L, "ms_all_40_layers": ms, "evals_per_s": c4.L * c4.B / (ms * 1e-3),
+            "algorithmic_bytes_per_layer": byts_layer, "achieved_GBps": byts_layer / (ms * 1e3 / c4.L) / 1e3}
+        so = sp.predict_sweep(T4["hidden"], T4["gamma"], lm4, T4["ids"], T4["W1"], T4["w2"])
+        g = capture(lambda: sp.predict_sweep(T4["hidden"], T4["gamma"], lm4, T4["ids"], T4["W1"], T4["w2"], out=so))
+        us = ev_time(g.replay, 100, 10) * 1e3
+        byts = c4.L * c4.B * c4.d * 2 + nrows * c4.d * 2 + c4.d * 2 + c4.L * (3 * c4.K * H + H) * 2
+        extra["c4_13b_one_launch_sweep"] = {"us_per_launch": us, "evals_per_s": c4.L * c4.B / us * 1e6,
+                                            "algorithmic_bytes": byts, "achieved_GBps": byts / us / 1e3,
+                                            "frac_of_8TBps": byts / us / 1e3 / HBM_PEAK_GBS}
+        del lm4, T4
+        torch.cuda.empty_cache()
+        lm = None
+
+    # ------------------------------------------------------------------ C5: d=8192, V=128256, K=8, 64-node tree + full head
+    if want("c5") and not args.no_extra:
+        lm = None
+        torch.cuda.empty_cache()
+        c5 = synth.CONFIGS["C5"]
+        lm5_h = synth.lm_head(c5.V, c5.d, synth.lm_seed(c5))
+        lm5 = up(lm5_h)
+        ts = [synth.make("C5", seed=s, lm=lm5_h) for s in range(8)]
+        g5 = up(ts[0]["gamma"])
+        tw1, tw2 = up(ts[0]["W1"]), up(ts[0]["w2"])
+        dts = [(up(t["hidden"]), up(t["ids"]), up(t["prev_probs"]), up(t["parent"])) for t in ts]
+        Ms = [len(np.unique(t["ids"])) for t in ts]
+        outs = [sp.predict_tree(hh, g5, lm5, ii, pp, tw1, tw2, parent=par, Mcap=c5.Mcap) for (hh, ii, pp, par) in dts]
+        ws = outs[0]["_workspace"]
+
+        def c5_calls():
+            for (hh, ii, pp, par), oo in zip(dts, outs):
+                oo2 = {k: (v[None] if v is not None else None) for k, v in oo.items() if k != "_workspace"}
+                sp.predict_tree(hh[None], g5, lm5, ii[None], pp[None], tw1, tw2, parent=par[None], Mcap=c5.Mcap,
+                                out=oo2, workspace=ws)
+        g = capture(c5_calls)
+        us_tree = ev_time(g.replay, 20, 3) * 1e3 / len(dts)
+        byts = int(np.mean([c5.N * c5.d * 2 + m * c5.d * 2 for m in Ms])) + c5.d * 2 + (3 * c5.K * H + H) * 2
+        extra["c5_tree_N64_V128256"] = {"us_per_call": us_tree, "mean_M": float(np.mean(Ms)),
+                                        "algorithmic_bytes": byts, "achieved_GBps": byts / us_tree / 1e3}
+        full = torch.empty((c5.N, c5.V), device=dev)
+        g = capture(lambda: sp.lm_head_gemv(dts[0][0], g5, lm5, out=full))
+        us64 = ev_time(g.replay, 10, 2) * 1e3
+        b64 = c5.V * c5.d * 2 + c5.N * c5.d * 2 + c5.N * c5.V * 4
+        extra["lm_head_gemv_128256x8192_N64"] = {"us_per_call": us64, "algorithmic_bytes": b64,
+                                                 "achieved_GBps": b64 / us64 / 1e3,
+                                                 "frac_of_8TBps": b64 / us64 / 1e3 / HBM_PEAK_GBS,
+                                                 "mfma_TFLOPs": 2 * 2.0 * c5.N * c5.V * c5.d / us64 / 1e6,
+                                                 "traffic": MEASURED_TRAFFIC.get("lm_head_gemm_c5")}
+        one = torch.empty((1, c5.V), device=dev)
+        g = capture(lambda: sp.lm_head_gemv(dts[0][0][:1], g5, lm5, out=one))
+        us1 = ev_time(g.replay, 10, 2) * 1e3
+        b1 = c5.V * c5.d * 2 + c5.d * 4 + c5.V * 4
+        extra["lm_head_gemv_128256x8192_N1"] = {"us_per_call": us1, "algorithmic_bytes": b1,
+                                                "achieved_GBps": b1 / us1 / 1e3,
+                                                "frac_of_8TBps": b1 / us1 / 1e3 / HBM_PEAK_GBS}
+        extra["c5_tree_N64_V128256"]["speedup_vs_full_head_N64"] = us64 / us_tree
+        del lm5
+        torch.cuda.empty_cache()
+
+    # ------------------------------------------------------------------ counter calibration: plain copy of known size
+    if "copy" in only:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            sp.calib_copy(dst, src)
+        torch.cuda.synchronize()
+        ms = ev_time(lambda: sp.calib_copy(dst, src), 20, 2)
+        extra["calib_copy_256MiB"] = {"ms": ms, "GBps_read_plus_write": 2 * src.numel() / ms / 1e6}
+
+    # ------------------------------------------------------------------ CPU oracle on the same workload
+    cpu = None
+    if not args.no_cpu and want("sweep"):
+        from oracle import specee_oracle as orc
+        orc.build()
+        orc.set_threads(1)
+        hid = synth.hidden_drift(L, 1, d, 50_000)
+        ids = synth.ids_uniform_distinct(1, K, V, 60_000)
+        t0 = time.perf_counter()
+        orc.predict_sweep(hid, base["gamma"], lm_h, ids, base["W1"], base["w2"])
+        one = time.perf_counter() - t0
+        reps = int(max(3, min(20000, 12.0 / max(one, 1e-6))))
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            orc.predict_sweep(hid, base["gamma"], lm_h, ids, base["W1"], base["w2"])
+        dt = time.perf_counter() - t0
+        cpu = {"value": reps * L / dt, "unit": "evals/s", "cores": orc.get_threads(), "kind": "oracle",
+               "sample": f"{reps} repetitions of the same 32-layer sweep (one token) in {dt:.1f} s, "
+                         "plain C float64 oracle, single thread",
+               "us_per_call": dt / (reps * L) * 1e6}
+        # context: the oracle's full-vocabulary head on a sample of rows
+        rows = np.arange(0, V, 8, dtype=np.int32)
+        t0 = time.perf_counter()
+        orc.lm_head_rows(hid[0], base["gamma"], lm_h, rows)
+        dt = time.perf_counter() - t0
+        cpu["lm_head_gemv_us_extrapolated_from_4000_rows"] = dt * 8 * 1e6
+
+    if result is None:
+        result = {"metric": "section run", "value": None, "unit": "", "n_gpus": 1, "steps": args.steps,
+                  "warmup": args.warmup, "config": {"workload": ",".join(sorted(only))}}
+    result["extra"] = extra
+    result["cpu_baseline"] = cpu
+    result["setup_s"] = time.time() - t_setup
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

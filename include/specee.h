@@ -185,6 +185,14 @@ int specee_sched_push(specee_sched *s, int exit_layer);
 /* active [L] (0/1) for the next token; offline_mask [L] or NULL. Returns the number of active layers. */
 int specee_sched_active(const specee_sched *s, const int32_t *offline_mask, int32_t *active);
 
+/*
+ * Measurement aid, not part of the method: copies `bytes` (multiple of 16,
+ * 16-byte aligned device pointers) with a plain streaming kernel, so that
+ * per-dispatch hardware byte counters can be calibrated against a transfer of
+ * known size.
+ */
+int specee_calib_copy(void *dst, const void *src, size_t bytes, void *stream);
+
 const char *specee_strerror(int status);
 int specee_version(void);
 

@@ -28,6 +28,7 @@
 // (double buffered, one barrier per 64-element step).
 #include "device_utils.h"
 #include "kernels.h"
+#include "merge_block.h"
 
 namespace specee {
 
@@ -37,11 +38,27 @@ constexpr int kKC = 64;           // k elements per LDS stage (128 bytes of ever
 constexpr int kNB = 64;           // hidden states per workgroup (4 n-tiles of 16)
 constexpr int kLdsRow = kKC + 8;  // halves per LDS row: 144 bytes, keeps 16-byte reads spread over banks
 
-template <int TPW, bool FINAL>
+// MODE 0: un-normalised partial sums per d-slice (tree); 1: normalised logits stored (full head);
+// 2: normalised logits reduced to one arg-max candidate per hidden state and workgroup (verification).
+// FUSED (tree only, N*K <= 1024): every workgroup merges the tree's ids itself in LDS before the
+// contraction, which removes a kernel launch and a dependent round trip from the latency path;
+// workgroup (0,0) of each tree publishes merged ids, their count and the columns.
+constexpr int kGemmFusedMax = kMergePerThread * kGemmThreads;
+constexpr int kStageHalves = 2 * kNB * kLdsRow;  // one operand (hi or lo), both buffers
+
+// PD: prefetch distance in 64-element stages.  Streaming use keeps PD stages of global loads in
+// flight per wavefront; the latency-bound tree use picks PD >= the number of stages of a d-slice, so
+// every load of the workgroup is issued before the first one is consumed.
+template <int TPW, int MODE, bool FUSED, int PD>
 __global__ __launch_bounds__(kGemmThreads) void gather_gemm_kernel(GemmParams p) {
-    __shared__ __attribute__((aligned(16))) half_t lds_hi[2][kNB][kLdsRow];
-    __shared__ __attribute__((aligned(16))) half_t lds_lo[2][kNB][kLdsRow];
+    __shared__ __attribute__((aligned(16))) half_t smem[2 * kStageHalves];
     __shared__ float lds_ssq[kNB];
+    static_assert(sizeof(half_t) * 2 * kStageHalves >= sizeof(int32_t) * merge_lds_ints(kGemmFusedMax),
+                  "merge scratch must fit in the staging buffers");
+    typedef half_t (*stage_t)[kNB][kLdsRow];
+    stage_t lds_hi = reinterpret_cast<stage_t>(smem);
+    stage_t lds_lo = reinterpret_cast<stage_t>(smem + kStageHalves);
+    constexpr bool FINAL = MODE != 0;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, q = lane >> 4;
@@ -50,15 +67,52 @@ __global__ __launch_bounds__(kGemmThreads) void gather_gemm_kernel(GemmParams p)
     const int n0 = nb * kNB;
     const int s = blockIdx.y;
     const int d = p.d;
-
-    int M = p.Mptr ? p.Mptr[g] : p.Mcap;
-    if (M > p.Mcap) M = p.Mcap;
-    const int m0 = blockIdx.x * (16 * TPW * kGemmWaves);
-    if (m0 >= M) return;  // uniform over the workgroup
-
     const int k_begin = s * p.dslice;
     const int k_end = min(d, k_begin + p.dslice);
     const int nchunks = (k_end - k_begin + kKC - 1) / kKC;
+
+    // ---- B side: this thread stages vector column vc of hidden states r0 and r0+32
+    const int vc = tid & 7, r0 = tid >> 3;  // 8 vectors per 64-element stage, 32 rows per pass, 2 passes
+    const half_t *hbase = p.hidden + ((size_t)g * p.N + n0) * d;
+    half8 h_buf[PD][2], g_buf[PD];
+    auto issue_b = [&](int kc, int slot) {
+        const int ko = k_begin + kc * kKC + vc * 8;
+        const bool in = kc < nchunks && ko < k_end;
+        g_buf[slot] = in ? load_half8(p.gamma + ko) : zero_half8();
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int r = r0 + 32 * i;
+            h_buf[slot][i] = (in && n0 + r < p.N) ? load_half8(hbase + (size_t)r * d + ko) : zero_half8();
+        }
+    };
+    // the hidden states do not depend on the merged set: request them before merging
+#pragma unroll
+    for (int u = 0; u < PD; ++u) issue_b(u, u);
+
+    int M;
+    int32_t *uniq = nullptr;
+    if (FUSED) {
+        const int n_ids = p.N * p.K;
+        int col_of[kMergePerThread];
+        const int Mtrue = merge_block(p.ids + (size_t)g * n_ids, n_ids, reinterpret_cast<int32_t *>(smem), uniq,
+                                      col_of);
+        if (blockIdx.x == 0 && blockIdx.y == 0 && nb == 0) {
+            if (tid == 0) p.M_out[g] = Mtrue;
+            for (int m = tid; m < p.Mcap; m += kGemmThreads)
+                p.merged_out[(size_t)g * p.Mcap + m] = m < Mtrue ? uniq[m] : -1;
+#pragma unroll
+            for (int e = 0; e < kMergePerThread; ++e) {
+                int i = tid + e * kGemmThreads;
+                if (i < n_ids) p.cols_out[(size_t)g * n_ids + i] = col_of[e];
+            }
+        }
+        M = Mtrue;
+    } else {
+        M = p.Mptr ? p.Mptr[g] : p.Mcap;
+    }
+    if (M > p.Mcap) M = p.Mcap;
+    const int m0 = blockIdx.x * (16 * TPW * kGemmWaves);
+    if (m0 >= M) return;  // uniform over the workgroup
 
     // ---- A side: this lane's rows
     const half_t *rowptr[TPW];
@@ -69,34 +123,27 @@ __global__ __launch_bounds__(kGemmThreads) void gather_gemm_kernel(GemmParams p)
         rowok[tp] = m < M;
         int row = 0;
         if (rowok[tp]) {
-            row = p.rowlist ? p.rowlist[(size_t)g * p.Mcap + m] : m;
+            row = FUSED ? uniq[m] : (p.rowlist ? p.rowlist[(size_t)g * p.Mcap + m] : m);
             if (row < 0 || row >= p.V) row = 0;  // invalid id: finish kernel reports NaN, never read out of bounds
         }
         rowptr[tp] = p.lm_head + (size_t)row * d;
     }
-    // ---- B side: this thread stages vector column vc of hidden states r0, r0+16, r0+32, r0+48
-    const int vc = tid & 7, r0 = tid >> 3;  // 8 vectors per 64-element stage, 32 rows per pass, 2 passes
-    const half_t *hbase = p.hidden + ((size_t)g * p.N + n0) * d;
+    if (FUSED) __syncthreads();  // the merge scratch becomes the staging buffers
 
-    half8 a_next[TPW][2], h_next[2], g_next;
-    auto issue_loads = [&](int kc) {
+    half8 a_buf[PD][TPW][2];
+    auto issue_a = [&](int kc, int slot) {
         const int k0 = k_begin + kc * kKC;
 #pragma unroll
         for (int tp = 0; tp < TPW; ++tp)
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
-                int ko = k0 + q * 16 + j * 8;
-                a_next[tp][j] = (rowok[tp] && ko < k_end) ? load_half8(rowptr[tp] + ko) : zero_half8();
+                const int ko = k0 + q * 16 + j * 8;
+                a_buf[slot][tp][j] =
+                    (kc < nchunks && rowok[tp] && ko < k_end) ? load_half8(rowptr[tp] + ko) : zero_half8();
             }
-        int ko = k0 + vc * 8;
-        bool in = ko < k_end;
-        g_next = in ? load_half8(p.gamma + ko) : zero_half8();
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            int r = r0 + 32 * i;
-            h_next[i] = (in && n0 + r < p.N) ? load_half8(hbase + (size_t)r * d + ko) : zero_half8();
-        }
     };
+#pragma unroll
+    for (int u = 0; u < PD; ++u) issue_a(u, u);
 
     floatx4 acc[TPW][4];
 #pragma unroll
@@ -105,46 +152,56 @@ __global__ __launch_bounds__(kGemmThreads) void gather_gemm_kernel(GemmParams p)
         for (int nt = 0; nt < 4; ++nt) acc[tp][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
     float ssq[2] = {0.f, 0.f};
 
-    issue_loads(0);
     int buf = 0;
-    for (int kc = 0; kc < nchunks; ++kc) {
-        // split x = h*gamma into hi + lo and publish this stage
+    for (int kc0 = 0; kc0 < nchunks; kc0 += PD) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            half8 hi, lo;
+        for (int u = 0; u < PD; ++u) {
+            const int kc = kc0 + u;
+            if (kc < nchunks) {  // uniform over the workgroup
+                // split x = h*gamma into hi + lo and publish this stage
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                float hf = (float)h_next[i][e];
-                float x = hf * (float)g_next[e];
-                half_t xh = (half_t)x;
-                hi[e] = xh;
-                lo[e] = (half_t)(x - (float)xh);
-                ssq[i] += hf * hf;
-            }
-            int r = r0 + 32 * i;
-            *reinterpret_cast<half8 *>(&lds_hi[buf][r][vc * 8]) = hi;
-            *reinterpret_cast<half8 *>(&lds_lo[buf][r][vc * 8]) = lo;
-        }
-        half8 a_cur[TPW][2];
+                for (int i = 0; i < 2; ++i) {
+                    half8 hi, lo;
 #pragma unroll
-        for (int tp = 0; tp < TPW; ++tp)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) a_cur[tp][j] = a_next[tp][j];
-        __syncthreads();
-        if (kc + 1 < nchunks) issue_loads(kc + 1);
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int nt = 0; nt < 4; ++nt) {
-                half8 bh = *reinterpret_cast<const half8 *>(&lds_hi[buf][nt * 16 + c][q * 16 + j * 8]);
-                half8 bl = *reinterpret_cast<const half8 *>(&lds_lo[buf][nt * 16 + c][q * 16 + j * 8]);
-#pragma unroll
-                for (int tp = 0; tp < TPW; ++tp) {
-                    acc[tp][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_cur[tp][j], bh, acc[tp][nt], 0, 0, 0);
-                    acc[tp][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_cur[tp][j], bl, acc[tp][nt], 0, 0, 0);
+                    for (int e = 0; e < 8; ++e) {
+                        float hf = (float)h_buf[u][i][e];
+                        float x = hf * (float)g_buf[u][e];
+                        half_t xh = (half_t)x;
+                        hi[e] = xh;
+                        lo[e] = (half_t)(x - (float)xh);
+                        ssq[i] += hf * hf;
+                    }
+                    const int r = r0 + 32 * i;
+                    *reinterpret_cast<half8 *>(&lds_hi[buf][r][vc * 8]) = hi;
+                    *reinterpret_cast<half8 *>(&lds_lo[buf][r][vc * 8]) = lo;
                 }
+                half8 a_cur[TPW][2];
+#pragma unroll
+                for (int tp = 0; tp < TPW; ++tp)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) a_cur[tp][j] = a_buf[u][tp][j];
+                __syncthreads();
+                if (kc + PD < nchunks) {
+                    issue_a(kc + PD, u);
+                    issue_b(kc + PD, u);
+                }
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int nt = 0; nt < 4; ++nt) {
+                        half8 bh = *reinterpret_cast<const half8 *>(&lds_hi[buf][nt * 16 + c][q * 16 + j * 8]);
+                        half8 bl = *reinterpret_cast<const half8 *>(&lds_lo[buf][nt * 16 + c][q * 16 + j * 8]);
+#pragma unroll
+                        for (int tp = 0; tp < TPW; ++tp) {
+                            acc[tp][nt] =
+                                __builtin_amdgcn_mfma_f32_16x16x32_f16(a_cur[tp][j], bh, acc[tp][nt], 0, 0, 0);
+                            acc[tp][nt] =
+                                __builtin_amdgcn_mfma_f32_16x16x32_f16(a_cur[tp][j], bl, acc[tp][nt], 0, 0, 0);
+                        }
+                    }
+                buf ^= 1;
             }
-        buf ^= 1;
+        }
     }
 
     // ---- sum of squares of each hidden state over this k-range: 8 consecutive lanes share a row
@@ -170,7 +227,55 @@ __global__ __launch_bounds__(kGemmThreads) void gather_gemm_kernel(GemmParams p)
         }
     }
 
-    // ---- epilogue: lane holds Z[m0t + 4q .. +3][n0 + nt*16 + c]
+    // ---- epilogue: lane holds Z[mt + 4q .. +3][n0 + nt*16 + c]
+    if (MODE == 2) {
+        __shared__ float cand_v[kGemmWaves][kNB];
+        __shared__ int cand_i[kGemmWaves][kNB];
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+            float scale = 1.0f / sqrtf(lds_ssq[nt * 16 + c] / (float)d + p.eps);
+            float bv = -INFINITY;
+            int bi = 0x7fffffff;
+#pragma unroll
+            for (int tp = 0; tp < TPW; ++tp) {
+                const int m = m0 + (wave * TPW + tp) * 16 + q * 4;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float v = acc[tp][nt][r] * scale;
+                    if (m + r < M && v > bv) {  // rows ascend: strict '>' keeps the lowest row on ties
+                        bv = v;
+                        bi = m + r;
+                    }
+                }
+            }
+#pragma unroll
+            for (int off = 16; off <= 32; off <<= 1) {  // the four q-groups of column c
+                float ov = __shfl_xor(bv, off, kWave);
+                int oi = __shfl_xor(bi, off, kWave);
+                if (ov > bv || (ov == bv && oi < bi)) {
+                    bv = ov;
+                    bi = oi;
+                }
+            }
+            if (q == 0) {
+                cand_v[wave][nt * 16 + c] = bv;
+                cand_i[wave][nt * 16 + c] = bi;
+            }
+        }
+        __syncthreads();
+        if (tid < kNB && n0 + tid < p.N) {
+            float bv = cand_v[0][tid];
+            int bi = cand_i[0][tid];
+            for (int w = 1; w < kGemmWaves; ++w)
+                if (cand_v[w][tid] > bv || (cand_v[w][tid] == bv && cand_i[w][tid] < bi)) {
+                    bv = cand_v[w][tid];
+                    bi = cand_i[w][tid];
+                }
+            p.best_val[(size_t)(n0 + tid) * gridDim.x + blockIdx.x] = bv;
+            p.best_idx[(size_t)(n0 + tid) * gridDim.x + blockIdx.x] = bi;
+        }
+        return;
+    }
 #pragma unroll
     for (int nt = 0; nt < 4; ++nt) {
         const int n = n0 + nt * 16 + c;
@@ -200,35 +305,73 @@ __global__ __launch_bounds__(kGemmThreads) void gather_gemm_kernel(GemmParams p)
     }
 }
 
-template <bool FINAL>
-static hipError_t launch_tpw(const GemmParams &p, int tpw, int G, hipStream_t st) {
-    const int rows_per_wg = 16 * tpw * kGemmWaves;
+constexpr int kTreePD = 4;    // a 256-element d-slice is requested in one go
+
+template <int MODE, int TPW, int PD>
+static void launch_one(const GemmParams &p, int G, hipStream_t st) {
+    const int rows_per_wg = 16 * TPW * kGemmWaves;
     dim3 grid((p.Mcap + rows_per_wg - 1) / rows_per_wg, p.S, G * ((p.N + kNB - 1) / kNB));
-    dim3 block(kGemmThreads);
-    switch (tpw) {
-        case 1: hipLaunchKernelGGL((gather_gemm_kernel<1, FINAL>), grid, block, 0, st, p); break;
-        case 2: hipLaunchKernelGGL((gather_gemm_kernel<2, FINAL>), grid, block, 0, st, p); break;
-        default: hipLaunchKernelGGL((gather_gemm_kernel<4, FINAL>), grid, block, 0, st, p); break;
-    }
+    hipLaunchKernelGGL((gather_gemm_kernel<TPW, MODE, false, PD>), grid, dim3(kGemmThreads), 0, st, p);
+}
+
+// Streaming configurations measured on MI355X (fp16 head, N = 16..64 hidden states):
+//   256 rows per workgroup, one stage ahead   -- best when that still gives >= 400 workgroups
+//   128 rows per workgroup, four stages ahead -- best for smaller vocabularies
+template <int MODE>
+static hipError_t launch_stream(const GemmParams &p, int tpw, hipStream_t st) {
+    if (tpw == 4)
+        launch_one<MODE, 4, 1>(p, 1, st);
+    else
+        launch_one<MODE, 2, 4>(p, 1, st);
     return hipGetLastError();
 }
 
-hipError_t launch_tree_gemm(const GemmParams &p, int G, hipStream_t st) {
-    return launch_tpw<false>(p, 1, G, st);
+bool tree_gemm_can_fuse_merge(int n_ids) {
+    return n_ids <= kGemmFusedMax;
 }
 
-hipError_t launch_lm_head_gemm(int d, int V, float eps, int N, const half_t *hidden, const half_t *gamma,
-                               const half_t *lm_head, float *out, hipStream_t st) {
+hipError_t launch_tree_gemm(const GemmParams &p, int G, hipStream_t st) {
+    const int rows_per_wg = 16 * kGemmWaves;
+    dim3 grid((p.Mcap + rows_per_wg - 1) / rows_per_wg, p.S, G * ((p.N + kNB - 1) / kNB));
+    if (p.ids)
+        hipLaunchKernelGGL((gather_gemm_kernel<1, 0, true, kTreePD>), grid, dim3(kGemmThreads), 0, st, p);
+    else
+        hipLaunchKernelGGL((gather_gemm_kernel<1, 0, false, kTreePD>), grid, dim3(kGemmThreads), 0, st, p);
+    return hipGetLastError();
+}
+
+static int lm_head_tpw(int V) {
+    return (V + 255) / 256 >= 400 ? 4 : 2;
+}
+
+int lm_head_gemm_workgroups(int V) {
+    int rows = 64 * lm_head_tpw(V);
+    return (V + rows - 1) / rows;
+}
+
+static GemmParams full_head_params(int d, int V, float eps, int N, const half_t *hidden, const half_t *gamma,
+                                   const half_t *lm_head) {
     GemmParams p{};
     p.d = d; p.V = V; p.N = N; p.eps = eps;
     p.hidden = hidden; p.gamma = gamma; p.lm_head = lm_head;
     p.rowlist = nullptr; p.Mptr = nullptr; p.Mcap = V;
     p.dslice = ((d + kKC - 1) / kKC) * kKC; p.S = 1;
-    p.out = out; p.ssq_part = nullptr; p.Mpad = 0; p.Npad = 0;
-    // enough workgroups to cover 256 CUs about twice, otherwise the widest tile (most reuse of the staged x)
-    int tpw = 4;
-    while (tpw > 1 && (V + 64 * tpw - 1) / (64 * tpw) < 400) tpw >>= 1;
-    return launch_tpw<true>(p, tpw, 1, st);
+    return p;
+}
+
+hipError_t launch_lm_head_gemm(int d, int V, float eps, int N, const half_t *hidden, const half_t *gamma,
+                               const half_t *lm_head, float *out, hipStream_t st) {
+    GemmParams p = full_head_params(d, V, eps, N, hidden, gamma, lm_head);
+    p.out = out;
+    return launch_stream<1>(p, lm_head_tpw(V), st);
+}
+
+hipError_t launch_lm_head_argmax_gemm(int d, int V, float eps, int N, const half_t *hidden, const half_t *gamma,
+                                      const half_t *lm_head, float *best_val, int32_t *best_idx, hipStream_t st) {
+    GemmParams p = full_head_params(d, V, eps, N, hidden, gamma, lm_head);
+    p.best_val = best_val;
+    p.best_idx = best_idx;
+    return launch_stream<2>(p, lm_head_tpw(V), st);
 }
 
 }  // namespace specee

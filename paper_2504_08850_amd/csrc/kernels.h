@@ -44,6 +44,13 @@ struct GemmParams {
     float *out;              // FINAL: [N][V] logits; else partial sums [G][S][Npad][Mpad]
     float *ssq_part;         // [G][S][Npad] partial sums of h^2 (tree only)
     int Mpad, Npad;
+    float *best_val;         // arg-max mode: [N][gridDim.x] candidates
+    int32_t *best_idx;
+    // fused merge (tree, N*K <= 1024): the kernel merges ids itself and workgroup (0,0) of each tree
+    // publishes the results
+    const int32_t *ids;      // [G][N][K] or null (rowlist / Mptr are then inputs)
+    int K;
+    int32_t *merged_out, *M_out, *cols_out;
 };
 
 struct TreeFinishParams {
@@ -58,14 +65,15 @@ struct TreeFinishParams {
     const half_t *W1, *b1, *w2, *b2;
     float *logits, *probs, *scores;
     int32_t *exit_flags;
+    const int32_t *parent;   // [G][N] or null
+    int32_t *path_exit;      // [G][N] or null
 };
 
 hipError_t launch_merge(const int32_t *ids, int n, int G, int Mcap, int32_t *merged, int32_t *M_out, int32_t *cols,
                         hipStream_t st);
+bool tree_gemm_can_fuse_merge(int n_ids);
 hipError_t launch_tree_gemm(const GemmParams &p, int G, hipStream_t st);
 hipError_t launch_tree_finish(const TreeFinishParams &p, int G, hipStream_t st);
-hipError_t launch_path(const int32_t *exit_flags, const int32_t *parent, int N, int G, int32_t *path_exit,
-                       hipStream_t st);
 // Full-vocabulary head for several hidden states on the matrix cores
 hipError_t launch_lm_head_gemm(int d, int V, float eps, int N, const half_t *hidden, const half_t *gamma,
                                const half_t *lm_head, float *out, hipStream_t st);
@@ -73,5 +81,15 @@ hipError_t launch_lm_head_gemm(int d, int V, float eps, int N, const half_t *hid
 // Full-vocabulary head, one hidden state per grid.y: out[n][v] = RMSNorm(h_n) . W[v]
 hipError_t launch_lm_head_gemv(int d, int V, float eps, int N, const half_t *hidden, const half_t *gamma,
                                const half_t *lm_head, float *out, hipStream_t s);
+
+// Verification: arg-max candidates per workgroup, then the combining tail
+int lm_head_gemv_workgroups(int V);
+int lm_head_gemm_workgroups(int V);
+hipError_t launch_lm_head_argmax_gemv(int d, int V, float eps, int N, const half_t *hidden, const half_t *gamma,
+                                      const half_t *lm_head, float *best_val, int32_t *best_idx, hipStream_t s);
+hipError_t launch_lm_head_argmax_gemm(int d, int V, float eps, int N, const half_t *hidden, const half_t *gamma,
+                                      const half_t *lm_head, float *best_val, int32_t *best_idx, hipStream_t s);
+hipError_t launch_verify_finish(const float *best_val, const int32_t *best_idx, int P, int N, const int32_t *ids,
+                                int K, int32_t *token, float *max_logit, int32_t *hit, hipStream_t s);
 
 }  // namespace specee

@@ -31,9 +31,14 @@ __device__ __forceinline__ float dot8(half8 w, floatx4 xa, floatx4 xb, float acc
     return acc;
 }
 
+// ARGMAX: instead of storing the V logits, keep the best (value, row) of this
+// workgroup's rows (lowest row on ties) and store one candidate per workgroup:
+// best_val / best_idx [N][gridDim.x].
+template <bool ARGMAX>
 __global__ __launch_bounds__(kGemvThreads) void lm_head_gemv_kernel(int d, int V, float eps, const half_t *hidden,
                                                                     const half_t *gamma, const half_t *lm_head,
-                                                                    float *out, int rows_per_wg) {
+                                                                    float *out, int rows_per_wg, float *best_val,
+                                                                    int32_t *best_idx) {
     extern __shared__ float4 lds_x[];  // [2][nv]: plane 0 = elements 0..3 of each vector, plane 1 = 4..7
     __shared__ float red[kGemvWaves];
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
@@ -69,6 +74,8 @@ __global__ __launch_bounds__(kGemvThreads) void lm_head_gemv_kernel(int d, int V
     const int row_begin = blockIdx.x * rows_per_wg;
     const int row_end = min(V, row_begin + rows_per_wg);
     float *o = out + (size_t)n * V;
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
     for (int row = row_begin + wave * kGemvRows; row < row_end; row += kGemvWaves * kGemvRows) {
         const bool two = row + 1 < row_end;
         const half_t *w0 = lm_head + (size_t)row * d;
@@ -95,10 +102,78 @@ __global__ __launch_bounds__(kGemvThreads) void lm_head_gemv_kernel(int d, int V
         }
         acc0 = wave_sum(acc0);
         acc1 = wave_sum(acc1);
-        if (lane == 0) {
+        if (ARGMAX) {
+            float v0 = acc0 * r, v1 = acc1 * r;
+            if (v0 > bv) {
+                bv = v0;
+                bi = row;
+            }
+            if (two && v1 > bv) {
+                bv = v1;
+                bi = row + 1;
+            }
+        } else if (lane == 0) {
             o[row] = acc0 * r;
             if (two) o[row + 1] = acc1 * r;
         }
+    }
+    if (ARGMAX) {
+        // rows ascend within a wave, so strict '>' already kept the lowest row; combine the waves in LDS
+        __shared__ float wv[kGemvWaves];
+        __shared__ int wi[kGemvWaves];
+        if (lane == 0) {
+            wv[wave] = bv;
+            wi[wave] = bi;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            for (int w = 1; w < kGemvWaves; ++w)
+                if (wv[w] > bv || (wv[w] == bv && wi[w] < bi)) {
+                    bv = wv[w];
+                    bi = wi[w];
+                }
+            best_val[(size_t)n * gridDim.x + blockIdx.x] = bv;
+            best_idx[(size_t)n * gridDim.x + blockIdx.x] = bi;
+        }
+    }
+}
+
+// Verification tail (paper Sec. 4.3.3): combine P candidates per hidden state
+// into the arg-max token (lowest id on ties) and test membership in the K ids.
+__global__ __launch_bounds__(256) void verify_finish_kernel(const float *best_val, const int32_t *best_idx, int P,
+                                                            const int32_t *ids, int K, int32_t *token,
+                                                            float *max_logit, int32_t *hit) {
+    __shared__ float wv[4];
+    __shared__ int wi[4];
+    const int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int i = tid; i < P; i += 256) {
+        float v = best_val[(size_t)n * P + i];
+        int ix = best_idx[(size_t)n * P + i];
+        if (v > bv || (v == bv && ix < bi)) {
+            bv = v;
+            bi = ix;
+        }
+    }
+    wave_argmax(bv, bi);
+    if (lane == 0) {
+        wv[wave] = bv;
+        wi[wave] = bi;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < 4; ++w)
+            if (wv[w] > bv || (wv[w] == bv && wi[w] < bi)) {
+                bv = wv[w];
+                bi = wi[w];
+            }
+        int h = 0;
+        for (int k = 0; k < K; ++k)
+            if (ids[(size_t)n * K + k] == bi) h = 1;
+        token[n] = bi;
+        max_logit[n] = bv;
+        hit[n] = h;
     }
 }
 
@@ -111,8 +186,35 @@ hipError_t launch_lm_head_gemv(int d, int V, float eps, int N, const half_t *hid
     rows_per_wg = ((rows_per_wg + quantum - 1) / quantum) * quantum;
     wgs = (V + rows_per_wg - 1) / rows_per_wg;
     size_t lds = (size_t)d * sizeof(float);
-    hipLaunchKernelGGL(lm_head_gemv_kernel, dim3(wgs, N), dim3(kGemvThreads), lds, s, d, V, eps, hidden, gamma,
-                       lm_head, out, rows_per_wg);
+    hipLaunchKernelGGL(lm_head_gemv_kernel<false>, dim3(wgs, N), dim3(kGemvThreads), lds, s, d, V, eps, hidden,
+                       gamma, lm_head, out, rows_per_wg, nullptr, nullptr);
+    return hipGetLastError();
+}
+
+int lm_head_gemv_workgroups(int V) {
+    int wgs = 512;
+    int rows_per_wg = (V + wgs - 1) / wgs;
+    const int quantum = kGemvWaves * kGemvRows;
+    rows_per_wg = ((rows_per_wg + quantum - 1) / quantum) * quantum;
+    return (V + rows_per_wg - 1) / rows_per_wg;
+}
+
+hipError_t launch_lm_head_argmax_gemv(int d, int V, float eps, int N, const half_t *hidden, const half_t *gamma,
+                                      const half_t *lm_head, float *best_val, int32_t *best_idx, hipStream_t s) {
+    int wgs = lm_head_gemv_workgroups(V);
+    int rows_per_wg = (V + wgs - 1) / wgs;
+    const int quantum = kGemvWaves * kGemvRows;
+    rows_per_wg = ((rows_per_wg + quantum - 1) / quantum) * quantum;
+    size_t lds = (size_t)d * sizeof(float);
+    hipLaunchKernelGGL(lm_head_gemv_kernel<true>, dim3(wgs, N), dim3(kGemvThreads), lds, s, d, V, eps, hidden,
+                       gamma, lm_head, nullptr, rows_per_wg, best_val, best_idx);
+    return hipGetLastError();
+}
+
+hipError_t launch_verify_finish(const float *best_val, const int32_t *best_idx, int P, int N, const int32_t *ids,
+                                int K, int32_t *token, float *max_logit, int32_t *hit, hipStream_t s) {
+    hipLaunchKernelGGL(verify_finish_kernel, dim3(N), dim3(256), 0, s, best_val, best_idx, P, ids, K, token,
+                       max_logit, hit);
     return hipGetLastError();
 }
 

@@ -1,0 +1,151 @@
+// Workgroup-level merge of a token tree's speculative ids (paper Sec. 6.2, the
+// merged mapping): sorted distinct ids, their count, and the column of every
+// (node, slot) in that set.  Pure integer work in LDS.
+//
+// The ids of a tree overlap heavily (that is the point of merging), so sorting
+// all N*K of them is wasted work.  Instead:
+//   1. de-duplicate through an open-addressing hash table in LDS (one LDS
+//      compare-and-swap per element; the table stores element indices so every
+//      int32 value is a legal key);
+//   2. compact the M representatives with a ballot/popcount scan;
+//   3. rank each distinct key among the M distinct keys by counting
+//      (M^2 / threads comparisons, keys read four at a time as LDS broadcasts);
+//   4. every element looks up the rank of its representative.
+// Which duplicate wins the table slot is timing dependent, but every output is
+// a function of the key values only, so results are deterministic.
+#pragma once
+#include "device_utils.h"
+
+namespace specee {
+
+constexpr int kMergePerThread = 4;  // elements a thread may own: n <= 4 * blockDim.x
+
+// LDS the caller provides, in ints (n4 = n rounded up to a multiple of 4).
+__host__ __device__ constexpr int merge_lds_ints(int n) {
+    return 3 * ((n + 3) & ~3) + 72;
+}
+
+// All threads of the workgroup must call.  On return (after the final barrier
+// inside) uniq[0..M) holds the sorted distinct ids and `col_of[e]` (for the
+// e-th element owned by this thread: i = tid + e * blockDim.x) its column.
+// Returns M.  `lds` is clobbered; uniq points into it.
+__device__ inline int merge_block(const int32_t *ids, int n, int32_t *lds, int32_t *&uniq,
+                                  int (&col_of)[kMergePerThread]) {
+    const int tid = threadIdx.x, T = blockDim.x;
+    const int lane = tid & 63, wave = tid >> 6, nwaves = T >> 6;
+    const int n4 = (n + 3) & ~3;
+    const unsigned TS = 2u * (unsigned)n4;  // table slots: load factor <= 1/2
+    int32_t *key = lds;                     // [n4]  keys by element; later distinct keys, later their ranks
+    int32_t *table = lds + n4;              // [2*n4] hash table of element indices
+    int32_t *cidx = table;                  // [n4]  (after the table is dead) compact index of a representative
+    int32_t *wtot = lds + 3 * n4;           // [<= 64] ballot totals
+    uniq = table + n4;                      // [n4]  (after the table is dead) sorted distinct keys
+
+    for (int i = tid; i < n4; i += T) key[i] = i < n ? ids[i] : 0x7fffffff;
+    for (unsigned t = tid; t < TS; t += T) table[t] = -1;
+    __syncthreads();
+
+    // 1. insert: the first element to claim a slot represents its key
+    int kreg[kMergePerThread], rep[kMergePerThread];
+#pragma unroll
+    for (int e = 0; e < kMergePerThread; ++e) {
+        const int i = tid + e * T;
+        rep[e] = -1;
+        kreg[e] = 0;
+        if (i < n) {
+            const int k = key[i];
+            kreg[e] = k;
+            unsigned h = (unsigned)(((unsigned long long)((unsigned)k * 2654435761u) * TS) >> 32);
+            for (unsigned probe = 0; probe < TS; ++probe) {  // the table is larger than n: always ends early
+                const int old = atomicCAS(&table[h], -1, i);
+                if (old == -1) {
+                    rep[e] = i;
+                    break;
+                }
+                if (key[old] == k) {
+                    rep[e] = old;
+                    break;
+                }
+                h = h + 1 == TS ? 0 : h + 1;
+            }
+        }
+    }
+    __syncthreads();
+
+    // 2. compact the representatives (order by element index)
+    int incl[kMergePerThread];
+    bool isrep[kMergePerThread];
+#pragma unroll
+    for (int e = 0; e < kMergePerThread; ++e) {
+        const int i = tid + e * T;
+        isrep[e] = i < n && rep[e] == i;
+        const unsigned long long mask = __ballot(isrep[e]);
+        incl[e] = __popcll(mask & (~0ull >> (63 - lane)));
+        if (lane == 0) wtot[e * nwaves + wave] = __popcll(mask);
+    }
+    __syncthreads();
+    int M = 0;
+    {
+        const int chunks = kMergePerThread;
+        for (int w = 0; w < chunks * nwaves; ++w) M += wtot[w];
+    }
+#pragma unroll
+    for (int e = 0; e < kMergePerThread; ++e) {
+        const int i = tid + e * T;
+        if (isrep[e]) {
+            int before = 0;
+            for (int w = 0; w < e * nwaves + wave; ++w) before += wtot[w];
+            const int ci = before + incl[e] - 1;
+            key[ci] = kreg[e];  // key[] is dead: every thread holds its keys in registers
+            cidx[i] = ci;       // the table is dead after the barrier above
+        }
+    }
+    const int M4 = (M + 3) & ~3;
+    __syncthreads();
+    for (int a = M + tid; a < M4; a += T) key[a] = 0x7fffffff;  // pad for the 4-wide reads
+    __syncthreads();
+
+    // 3. rank of every distinct key among the distinct keys
+    int rnk[kMergePerThread], kd[kMergePerThread];
+#pragma unroll
+    for (int e = 0; e < kMergePerThread; ++e) {
+        const int a = tid + e * T;
+        rnk[e] = 0;
+        kd[e] = 0;
+        if (a < M) {
+            const int k = key[a];
+            int r0 = 0, r1 = 0, r2 = 0, r3 = 0;
+#pragma unroll 4
+            for (int b = 0; b < M4; b += 4) {
+                const int4 kb = *reinterpret_cast<const int4 *>(key + b);
+                r0 += kb.x < k;
+                r1 += kb.y < k;
+                r2 += kb.z < k;
+                r3 += kb.w < k;
+            }
+            rnk[e] = (r0 + r1) + (r2 + r3);
+            kd[e] = k;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < kMergePerThread; ++e) {
+        const int a = tid + e * T;
+        if (a < M) {
+            uniq[rnk[e]] = kd[e];
+            key[a] = rnk[e];  // distinct keys are dead: reuse as rank by compact index
+        }
+    }
+    __syncthreads();
+
+    // 4. column of every element = rank of its representative's key
+#pragma unroll
+    for (int e = 0; e < kMergePerThread; ++e) {
+        const int i = tid + e * T;
+        col_of[e] = (i < n && rep[e] >= 0) ? key[cidx[rep[e]]] : 0;
+    }
+    __syncthreads();
+    return M;
+}
+
+}  // namespace specee

@@ -33,13 +33,23 @@ const half_t *H(const specee_half *p) {
     return reinterpret_cast<const half_t *>(p);
 }
 
-// d-slices of the tree contraction: about 256 elements each, at most 128 slices, multiples of 64
+// d-slices of the tree contraction.  A single tree is latency-bound: slices of ~256 elements spread
+// it over many CUs.  With many trees per call the grid is already full, and fewer, longer slices
+// mean fewer partial sums to write and re-read.  Slices are multiples of 64; at most 128 of them.
 struct TreeSplit {
     int S, dslice;
 };
-TreeSplit tree_split(int d) {
-    int S = (d + 255) / 256;
-    if (S > 128) S = 128;
+int tree_max_slices(int d) {
+    int max_S = (d + 255) / 256;
+    return max_S > 128 ? 128 : max_S;
+}
+TreeSplit tree_split(int d, int n_total, int N, int Mcap) {
+    const int max_S = tree_max_slices(d);
+    const int G = N > 0 ? (n_total + N - 1) / N : 1;
+    const long long wgs_per_slice = (long long)G * ((Mcap + 63) / 64) * ((N + 63) / 64);
+    int S = (int)((768 + wgs_per_slice - 1) / wgs_per_slice);
+    if (S > max_S) S = max_S;
+    if (S < 1) S = 1;
     int dslice = (((d + S - 1) / S + 63) / 64) * 64;
     S = (d + dslice - 1) / dslice;
     return {S, dslice};
@@ -53,8 +63,8 @@ struct TreeLayout {
     int Mpad;
     size_t partial_off, ssq_off, total;
 };
-TreeLayout tree_layout(int d, int n_total, int Mcap) {
-    TreeSplit ts = tree_split(d);
+TreeLayout tree_layout(int S, int n_total, int Mcap) {
+    struct { int S; } ts = {S};
     TreeLayout L;
     L.Mpad = ((Mcap + 15) / 16) * 16;
     L.partial_off = 0;
@@ -90,9 +100,15 @@ size_t specee_workspace_bytes(int op, const specee_dims *dm, int n, int Mcap) {
             return check_dims(dm, true) ? (size_t)-1 : 0;
         case SPECEE_OP_LM_HEAD:
             return check_dims(dm, false) ? (size_t)-1 : 0;
+        case SPECEE_OP_VERIFY: {
+            if (check_dims(dm, false)) return (size_t)-1;
+            int P = n <= 2 ? lm_head_gemv_workgroups(dm->V) : lm_head_gemm_workgroups(dm->V);
+            return 2 * align256((size_t)n * P * sizeof(float));
+        }
         case SPECEE_OP_PREDICT_TREE:
             if (check_dims(dm, true) || Mcap < 1 || Mcap > 4096) return (size_t)-1;
-            return tree_layout(dm->d, n, Mcap).total;
+            // the split depends on how n divides into trees: size for the finest one
+            return tree_layout(tree_max_slices(dm->d), n, Mcap).total;
         default:
             return (size_t)-1;
     }
@@ -181,15 +197,19 @@ int specee_predict_tree(const specee_dims *dm, int G, int N, int Mcap, const spe
     if (path_exit && !parent) return SPECEE_EINVAL;
     if (probs == prev_probs) return SPECEE_EINVAL;
     if (misaligned(hidden) || misaligned(gamma) || misaligned(lm_head) || misaligned(workspace)) return SPECEE_EALIGN;
-    const TreeSplit ts = tree_split(dm->d);
-    const TreeLayout lay = tree_layout(dm->d, G * N, Mcap);
-    if (!workspace || workspace_bytes < lay.total) return SPECEE_EWORKSPACE;
+    const TreeSplit ts = tree_split(dm->d, G * N, N, Mcap);
+    const TreeLayout lay = tree_layout(ts.S, G * N, Mcap);
+    const size_t need = tree_layout(tree_max_slices(dm->d), G * N, Mcap).total;
+    if (!workspace || workspace_bytes < need) return SPECEE_EWORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace);
     float *partial = reinterpret_cast<float *>(ws + lay.partial_off);
     float *ssq_part = reinterpret_cast<float *>(ws + lay.ssq_off);
 
-    if (launch_merge(ids, N * dm->K, G, Mcap, merged_ids, M_out, cols, st) != hipSuccess) return SPECEE_EHIP;
+    // few trees: merge inside the contraction kernel (one launch less on the latency path);
+    // many trees: merge once per tree in its own small kernel instead of once per workgroup
+    const bool fuse = tree_gemm_can_fuse_merge(N * dm->K) && (long long)G * ts.S <= 64;
+    if (!fuse && launch_merge(ids, N * dm->K, G, Mcap, merged_ids, M_out, cols, st) != hipSuccess) return SPECEE_EHIP;
 
     GemmParams gp{};
     gp.d = dm->d; gp.V = dm->V; gp.N = N; gp.eps = dm->eps;
@@ -197,6 +217,8 @@ int specee_predict_tree(const specee_dims *dm, int G, int N, int Mcap, const spe
     gp.rowlist = merged_ids; gp.Mptr = M_out; gp.Mcap = Mcap;
     gp.dslice = ts.dslice; gp.S = ts.S;
     gp.out = partial; gp.ssq_part = ssq_part; gp.Mpad = lay.Mpad; gp.Npad = N;
+    gp.ids = fuse ? ids : nullptr; gp.K = dm->K;
+    gp.merged_out = merged_ids; gp.M_out = M_out; gp.cols_out = cols;
     if (launch_tree_gemm(gp, G, st) != hipSuccess) return SPECEE_EHIP;
 
     TreeFinishParams fp{};
@@ -206,10 +228,34 @@ int specee_predict_tree(const specee_dims *dm, int G, int N, int Mcap, const spe
     fp.prev = prev_probs;
     fp.W1 = H(mlp->W1); fp.b1 = H(mlp->b1); fp.w2 = H(mlp->w2); fp.b2 = H(mlp->b2);
     fp.logits = logits; fp.probs = probs; fp.scores = scores; fp.exit_flags = exit_flags;
+    fp.parent = parent; fp.path_exit = path_exit;
     if (launch_tree_finish(fp, G, st) != hipSuccess) return SPECEE_EHIP;
-
-    if (path_exit && launch_path(exit_flags, parent, N, G, path_exit, st) != hipSuccess) return SPECEE_EHIP;
     return SPECEE_OK;
+}
+
+int specee_verify(const specee_dims *dm, int N, const specee_half *hidden, const specee_half *gamma,
+                  const specee_half *lm_head, const int32_t *ids, int32_t *token, float *max_logit, int32_t *hit,
+                  void *workspace, size_t workspace_bytes, void *stream) {
+    int rc = check_dims(dm, false);
+    if (rc) return rc;
+    if (N < 0 || N > 65535 || dm->K < 1 || dm->K > SPECEE_KMAX) return SPECEE_EINVAL;
+    if (N == 0) return SPECEE_OK;
+    if (!hidden || !gamma || !lm_head || !ids || !token || !max_logit || !hit) return SPECEE_EINVAL;
+    if (misaligned(hidden) || misaligned(gamma) || misaligned(lm_head) || misaligned(workspace)) return SPECEE_EALIGN;
+    const bool vec = N <= 2;
+    const int P = vec ? lm_head_gemv_workgroups(dm->V) : lm_head_gemm_workgroups(dm->V);
+    const size_t half_ws = align256((size_t)N * P * sizeof(float));
+    if (!workspace || workspace_bytes < 2 * half_ws) return SPECEE_EWORKSPACE;
+    float *best_val = static_cast<float *>(workspace);
+    int32_t *best_idx = reinterpret_cast<int32_t *>(static_cast<char *>(workspace) + half_ws);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = vec ? launch_lm_head_argmax_gemv(dm->d, dm->V, dm->eps, N, H(hidden), H(gamma), H(lm_head),
+                                                    best_val, best_idx, st)
+                       : launch_lm_head_argmax_gemm(dm->d, dm->V, dm->eps, N, H(hidden), H(gamma), H(lm_head),
+                                                    best_val, best_idx, st);
+    if (e != hipSuccess) return SPECEE_EHIP;
+    e = launch_verify_finish(best_val, best_idx, P, N, ids, dm->K, token, max_logit, hit, st);
+    return e == hipSuccess ? SPECEE_OK : SPECEE_EHIP;
 }
 
 }  // extern "C"

@@ -1,149 +1,139 @@
 // Token-tree side kernels of the merged mapping (paper Sec. 6.2):
-//   merge_kernel   sorted distinct set of a tree's N*K speculative ids and the
-//                  column of every (node, slot) in it -- pure integer work, one
-//                  workgroup per tree, bitonic sort + scan + binary search in LDS;
-//   finish_kernel  per node: fixed-order sum of the d-slice partials of its K
-//                  columns, RMSNorm scale, then the same feature/MLP tail as the
-//                  single-token predictor;
-//   path_kernel    a token path exits only if every token on it exits (the
-//                  rearmost exit decides): AND of exit flags up to the root.
+//   merge_kernel        sorted distinct set of a tree's N*K speculative ids and
+//                       the column of every (node, slot) in it (integer work,
+//                       one workgroup per tree; the contraction kernel can run
+//                       the same merge in its own prologue instead);
+//   tree_finish_kernel  one wavefront per node: sums the d-slice partials of its
+//                       K columns in fixed order, applies the RMSNorm scale and
+//                       runs the same feature/MLP tail as the single-token
+//                       predictor, eight hidden units per lane in registers;
+//   path_kernel         the path rule: a token path exits only if every token
+//                       on it exits (the rearmost exit decides), i.e. the AND of
+//                       exit flags up to the root.
 #include "device_utils.h"
 #include "kernels.h"
+#include "merge_block.h"
 #include "predictor_tail.h"
 
 namespace specee {
 
 constexpr int kMergeThreads = 1024;
-constexpr int kMergeMax = 4096;           // N*K limit
-constexpr int kPadKey = 0x7fffffff;       // sorts after every valid or invalid id
 
-__global__ __launch_bounds__(kMergeThreads) void merge_kernel(const int32_t *ids, int n, int P, int Mcap,
-                                                              int32_t *merged, int32_t *M_out, int32_t *cols) {
-    __shared__ int32_t key[kMergeMax];
-    __shared__ int32_t pos[kMergeMax];
-    __shared__ int32_t uniq[kMergeMax];
-    const int tid = threadIdx.x;
-    const int g = blockIdx.x;
-    const int32_t *gids = ids + (size_t)g * n;
-
-    for (int i = tid; i < P; i += kMergeThreads) key[i] = i < n ? gids[i] : kPadKey;
-    __syncthreads();
-    // bitonic sort, ascending (signed compare: negative, i.e. invalid, ids sort first)
-    for (int k = 2; k <= P; k <<= 1)
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int t = tid; t < (P >> 1); t += kMergeThreads) {
-                int lo = ((t & ~(j - 1)) << 1) | (t & (j - 1));
-                int hi = lo | j;
-                bool up = (lo & k) == 0;
-                int32_t a = key[lo], b = key[hi];
-                if ((a > b) == up) {
-                    key[lo] = b;
-                    key[hi] = a;
-                }
-            }
-            __syncthreads();
-        }
-    // head-of-run flags and their inclusive scan (Hillis-Steele over P entries)
-    for (int i = tid; i < P; i += kMergeThreads)
-        pos[i] = (i < n && (i == 0 || key[i] != key[i - 1])) ? 1 : 0;
-    __syncthreads();
-    for (int off = 1; off < P; off <<= 1) {
-        int32_t v[kMergeMax / kMergeThreads];
-        int cnt = 0;
-        for (int i = tid; i < P; i += kMergeThreads) v[cnt++] = pos[i] + (i >= off ? pos[i - off] : 0);
-        __syncthreads();
-        cnt = 0;
-        for (int i = tid; i < P; i += kMergeThreads) pos[i] = v[cnt++];
-        __syncthreads();
-    }
-    const int M = n > 0 ? pos[n - 1] : 0;
-    for (int i = tid; i < n; i += kMergeThreads)
-        if (i == 0 || key[i] != key[i - 1]) uniq[pos[i] - 1] = key[i];
-    __syncthreads();
+__global__ __launch_bounds__(kMergeThreads) void merge_kernel(const int32_t *ids, int n, int Mcap, int32_t *merged,
+                                                              int32_t *M_out, int32_t *cols) {
+    extern __shared__ __attribute__((aligned(16))) int32_t merge_lds[];
+    const int g = blockIdx.x, tid = threadIdx.x;
+    int32_t *uniq;
+    int col_of[kMergePerThread];
+    const int M = merge_block(ids + (size_t)g * n, n, merge_lds, uniq, col_of);
     if (tid == 0) M_out[g] = M;
     for (int m = tid; m < Mcap; m += kMergeThreads) merged[(size_t)g * Mcap + m] = m < M ? uniq[m] : -1;
-    // column of every id: binary search in the distinct set
-    for (int i = tid; i < n; i += kMergeThreads) {
-        int32_t id = gids[i];
-        int lo = 0, hi = M - 1;
-        while (lo < hi) {
-            int mid = (lo + hi) >> 1;
-            if (uniq[mid] < id) lo = mid + 1;
-            else hi = mid;
-        }
-        cols[(size_t)g * n + i] = lo;
+#pragma unroll
+    for (int e = 0; e < kMergePerThread; ++e) {
+        int i = tid + e * kMergeThreads;
+        if (i < n) cols[(size_t)g * n + i] = col_of[e];
     }
 }
 
-constexpr int kFinishThreads = 512;
-constexpr int kFinishWaves = kFinishThreads / kWave;
-constexpr int kFinishSMax = 128;  // d-slices
+constexpr int kFinishThreads = 256;
+constexpr int kFinishWaves = kFinishThreads / kWave;  // nodes per workgroup: one per wavefront
+constexpr int kFinishUnits = 8;                       // hidden units per lane held in registers (H <= 512)
 
 template <int KC>
 __global__ __launch_bounds__(kFinishThreads) void tree_finish_kernel(TreeFinishParams p) {
-    __shared__ float part[SPECEE_KMAX_INTERNAL * kFinishSMax];
-    __shared__ float ssqp[kFinishSMax];
-    __shared__ float zs[KC + 1];
-    __shared__ float red_u[kFinishWaves];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int n = blockIdx.x, g = blockIdx.y;
-    const int K = p.K, H = p.H, S = p.S;
-    const size_t gn = (size_t)g * p.N + n;
+    const int g = blockIdx.y;
+    const int n = blockIdx.x * kFinishWaves + wave;
+    const int K = p.K, H = p.H, S = p.S, N = p.N;
+    if (n >= N) return;  // no barriers below: wavefronts are independent
+    const bool regs = (K == KC) && (H <= kFinishUnits * kWave) && KC <= 8;
 
-    MlpRow<KC> row0;
-    mlp_row_load<KC>(row0, p.W1, p.b1, p.w2, K, H, tid);
+    MlpRow<KC> rows[KC <= 8 ? kFinishUnits : 1];
+    if (regs) {
+#pragma unroll
+        for (int u = 0; u < kFinishUnits; ++u) mlp_row_load<KC>(rows[u], p.W1, p.b1, p.w2, K, H, lane + u * kWave);
+    }
+    const size_t gn = (size_t)g * N + n;
+    // independent requests first: merged size, this node's ids, columns and previous probabilities
+    const int M = p.M_out[g];
+    const float b2 = p.b2 ? (float)p.b2[0] : 0.f;
+    int id = 0, col = 0;
+    if (lane < K) {
+        id = p.ids[gn * K + lane];
+        col = p.cols[gn * K + lane];
+    }
     float prev[KC];
 #pragma unroll
-    for (int k = 0; k < KC; ++k) prev[k] = k < K ? p.prev[gn * K + k] : 0.f;
+    for (int k = 0; k < KC; ++k) prev[k] = (k < K) ? p.prev[gn * K + k] : 0.f;
 
-    const int M = p.M_out[g];
-    const bool overflow = M > p.Mcap;
-    bool bad = overflow;
-#pragma unroll
-    for (int k = 0; k < KC; ++k)
-        if (k < K) {
-            int id = p.ids[gn * K + k];
-            if (id < 0 || id >= p.V) bad = true;
-        }
-    // gather this node's K columns from every d-slice partial
-    for (int t = tid; t < K * S; t += kFinishThreads) {
-        int k = t / S, s = t - k * S;
-        int col = p.cols[gn * K + k];
+    // lanes 0..K-1: one logit each; lane K: the sum of squares.  Slices are summed in ascending
+    // order, sixteen loads in flight at a time.
+    float a = 0.f;
+    bool bad = M > p.Mcap;
+    const float *src = nullptr;
+    size_t stride = 0;
+    if (lane < K) {
+        if (id < 0 || id >= p.V) bad = true;
         col = (col >= 0 && col < p.Mpad) ? col : 0;
-        part[k * S + s] = p.partial[(((size_t)g * S + s) * p.Npad + n) * p.Mpad + col];
+        src = p.partial + ((size_t)g * S * p.Npad + n) * p.Mpad + col;
+        stride = (size_t)p.Npad * p.Mpad;
+    } else if (lane == K) {
+        src = p.ssq_part + (size_t)g * S * p.Npad + n;
+        stride = (size_t)p.Npad;
     }
-    for (int s = tid; s < S; s += kFinishThreads) ssqp[s] = p.ssq_part[((size_t)g * S + s) * p.Npad + n];
-    __syncthreads();
-    if (tid <= K) {  // threads 0..K-1: one logit each, ascending slice order; thread K: sum of squares
-        float a = 0.f;
-        const float *src = tid < K ? part + tid * S : ssqp;
-        for (int s = 0; s < S; ++s) a += src[s];
-        zs[tid < K ? tid : KC] = a;
+    if (src) {
+        int s = 0;
+        for (; s + 16 <= S; s += 16) {
+            float v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) v[u] = src[(size_t)(s + u) * stride];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) a += v[u];
+        }
+        for (; s + 4 <= S; s += 4) {
+            float v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = src[(size_t)(s + u) * stride];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) a += v[u];
+        }
+        for (; s < S; ++s) a += src[(size_t)s * stride];
     }
-    __syncthreads();
-    const float r = 1.0f / sqrtf(zs[KC] / (float)p.d + p.eps);
+    bad = __any(bad);
+    const float r = 1.0f / sqrtf(__shfl(a, K, kWave) / (float)p.d + p.eps);
     float z[KC], pr[KC];
 #pragma unroll
-    for (int k = 0; k < KC; ++k) z[k] = (k < K) ? (bad ? quiet_nan() : zs[k] * r) : 0.f;
+    for (int k = 0; k < KC; ++k) {
+        float v = __shfl(a, k < K ? k : 0, kWave);
+        z[k] = (k < K) ? (bad ? quiet_nan() : v * r) : 0.f;
+    }
     local_softmax<KC>(z, K, pr);
 
-    float partu = mlp_partial<KC, kFinishThreads>(row0, p.W1, p.b1, p.w2, K, H, tid, z, pr, prev);
-    partu = wave_sum(partu);
-    if (lane == 0) red_u[wave] = partu;
-    __syncthreads();
-    if (tid == 0) {
-        float u = p.b2 ? (float)p.b2[0] : 0.f;
+    float part = 0.f;
+    if (regs) {
 #pragma unroll
-        for (int w = 0; w < kFinishWaves; ++w) u += red_u[w];
-        float sc = sigmoidf(u);
+        for (int u = 0; u < kFinishUnits; ++u)
+            if (lane + u * kWave < H) part += mlp_unit<KC>(rows[u], p.W1, K, lane + u * kWave, z, pr, prev);
+    } else {
+        for (int j = lane; j < H; j += kWave) {
+            MlpRow<KC> row;
+            mlp_row_load<KC>(row, p.W1, p.b1, p.w2, K, H, j);
+            part += mlp_unit<KC>(row, p.W1, K, j, z, pr, prev);
+        }
+    }
+    part = wave_sum(part);
+    const float sc = sigmoidf(b2 + part);
+    if (lane == 0) {
         p.scores[gn] = sc;
         p.exit_flags[gn] = (sc > p.threshold) ? 1 : 0;
+    }
+    if (lane < K) {
+        p.logits[gn * K + lane] = bad ? quiet_nan() : a * r;
+        float mine = 0.f;
 #pragma unroll
         for (int k = 0; k < KC; ++k)
-            if (k < K) {
-                p.logits[gn * K + k] = z[k];
-                p.probs[gn * K + k] = pr[k];
-            }
+            if (k == lane) mine = pr[k];
+        p.probs[gn * K + lane] = mine;
     }
 }
 
@@ -169,28 +159,24 @@ __global__ void path_kernel(const int32_t *exit_flags, const int32_t *parent, in
 
 hipError_t launch_merge(const int32_t *ids, int n, int G, int Mcap, int32_t *merged, int32_t *M_out, int32_t *cols,
                         hipStream_t st) {
-    int P = 64;
-    while (P < n) P <<= 1;
-    hipLaunchKernelGGL(merge_kernel, dim3(G), dim3(kMergeThreads), 0, st, ids, n, P, Mcap, merged, M_out, cols);
+    size_t lds = (size_t)merge_lds_ints(n) * sizeof(int32_t);
+    hipLaunchKernelGGL(merge_kernel, dim3(G), dim3(kMergeThreads), lds, st, ids, n, Mcap, merged, M_out, cols);
     return hipGetLastError();
 }
 
 hipError_t launch_tree_finish(const TreeFinishParams &p, int G, hipStream_t st) {
-    dim3 grid(p.N, G), block(kFinishThreads);
+    dim3 grid((p.N + kFinishWaves - 1) / kFinishWaves, G), block(kFinishThreads);
     if (p.K <= 4)
         hipLaunchKernelGGL((tree_finish_kernel<4>), grid, block, 0, st, p);
     else if (p.K <= 8)
         hipLaunchKernelGGL((tree_finish_kernel<8>), grid, block, 0, st, p);
     else
         hipLaunchKernelGGL((tree_finish_kernel<16>), grid, block, 0, st, p);
-    return hipGetLastError();
-}
-
-hipError_t launch_path(const int32_t *exit_flags, const int32_t *parent, int N, int G, int32_t *path_exit,
-                       hipStream_t st) {
-    int total = N * G;
-    hipLaunchKernelGGL(path_kernel, dim3((total + 255) / 256), dim3(256), 0, st, exit_flags, parent, N, total,
-                       path_exit);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || !p.path_exit) return e;
+    const int total = p.N * G;
+    hipLaunchKernelGGL(path_kernel, dim3((total + 255) / 256), dim3(256), 0, st, p.exit_flags, p.parent, p.N, total,
+                       p.path_exit);
     return hipGetLastError();
 }
 

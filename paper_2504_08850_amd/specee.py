@@ -223,6 +223,16 @@ def verify(hidden, gamma, lm_head, ids, eps=1e-5, out=None, workspace=None, stre
     return out
 
 
+def calib_copy(dst, src, stream=None):
+    """specee_calib_copy: plain device copy of known size (counter calibration)."""
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    rc = lib().specee_calib_copy(_ptr(dst), _ptr(src), C.c_size_t(nbytes), _stream(stream))
+    if rc:
+        raise SpeceeError("specee_calib_copy", rc)
+    return dst
+
+
 class Scheduler:
     """Host-side online scheduler (specee_sched_*): circular queue of recent exit layers."""
 
