@@ -94,7 +94,7 @@ __global__ __launch_bounds__(kGemmThreads) void gather_gemm_kernel(GemmParams p)
     if (FUSED) {
         const int n_ids = p.N * p.K;
         int col_of[kMergePerThread];
-        const int Mtrue = merge_block(p.ids + (size_t)g * n_ids, n_ids, reinterpret_cast<int32_t *>(smem), uniq,
+        const int Mtrue = merge_block<kGemmThreads>(p.ids + (size_t)g * n_ids, n_ids, reinterpret_cast<int32_t *>(smem), uniq,
                                       col_of);
         if (blockIdx.x == 0 && blockIdx.y == 0 && nb == 0) {
             if (tid == 0) p.M_out[g] = Mtrue;

@@ -29,10 +29,15 @@ __host__ __device__ constexpr int merge_lds_ints(int n) {
 // inside) uniq[0..M) holds the sorted distinct ids and `col_of[e]` (for the
 // e-th element owned by this thread: i = tid + e * blockDim.x) its column.
 // Returns M.  `lds` is clobbered; uniq points into it.
+// T = blockDim.x (compile time, so the short serial loops over per-wave totals unroll into
+// independent LDS reads).
+template <int T>
 __device__ inline int merge_block(const int32_t *ids, int n, int32_t *lds, int32_t *&uniq,
                                   int (&col_of)[kMergePerThread]) {
-    const int tid = threadIdx.x, T = blockDim.x;
-    const int lane = tid & 63, wave = tid >> 6, nwaves = T >> 6;
+    const int tid = threadIdx.x;
+    constexpr int nwaves = T >> 6;
+    constexpr int kTotals = kMergePerThread * nwaves;
+    const int lane = tid & 63, wave = tid >> 6;
     const int n4 = (n + 3) & ~3;
     const unsigned TS = 2u * (unsigned)n4;  // table slots: load factor <= 1/2
     int32_t *key = lds;                     // [n4]  keys by element; later distinct keys, later their ranks
@@ -41,20 +46,23 @@ __device__ inline int merge_block(const int32_t *ids, int n, int32_t *lds, int32
     int32_t *wtot = lds + 3 * n4;           // [<= 64] ballot totals
     uniq = table + n4;                      // [n4]  (after the table is dead) sorted distinct keys
 
-    for (int i = tid; i < n4; i += T) key[i] = i < n ? ids[i] : 0x7fffffff;
-    for (unsigned t = tid; t < TS; t += T) table[t] = -1;
-    __syncthreads();
-
-    // 1. insert: the first element to claim a slot represents its key
     int kreg[kMergePerThread], rep[kMergePerThread];
 #pragma unroll
     for (int e = 0; e < kMergePerThread; ++e) {
         const int i = tid + e * T;
+        kreg[e] = i < n ? ids[i] : 0x7fffffff;
+        if (i < n4) key[i] = kreg[e];
+    }
+    for (unsigned t = tid; t < TS; t += T) table[t] = -1;
+    __syncthreads();
+
+    // 1. insert: the first element to claim a slot represents its key
+#pragma unroll
+    for (int e = 0; e < kMergePerThread; ++e) {
+        const int i = tid + e * T;
         rep[e] = -1;
-        kreg[e] = 0;
         if (i < n) {
-            const int k = key[i];
-            kreg[e] = k;
+            const int k = kreg[e];
             unsigned h = (unsigned)(((unsigned long long)((unsigned)k * 2654435761u) * TS) >> 32);
             for (unsigned probe = 0; probe < TS; ++probe) {  // the table is larger than n: always ends early
                 const int old = atomicCAS(&table[h], -1, i);
@@ -85,17 +93,32 @@ __device__ inline int merge_block(const int32_t *ids, int n, int32_t *lds, int32
     }
     __syncthreads();
     int M = 0;
+    int before[kMergePerThread];
     {
-        const int chunks = kMergePerThread;
-        for (int w = 0; w < chunks * nwaves; ++w) M += wtot[w];
+        int tot[kTotals];
+#pragma unroll
+        for (int w = 0; w < kTotals; w += 4) {
+            const int4 t4 = *reinterpret_cast<const int4 *>(wtot + w);
+            tot[w] = t4.x;
+            tot[w + 1] = t4.y;
+            tot[w + 2] = t4.z;
+            tot[w + 3] = t4.w;
+        }
+#pragma unroll
+        for (int e = 0; e < kMergePerThread; ++e) before[e] = 0;
+#pragma unroll
+        for (int w = 0; w < kTotals; ++w) {
+#pragma unroll
+            for (int e = 0; e < kMergePerThread; ++e)
+                if (w < e * nwaves + wave) before[e] += tot[w];
+            M += tot[w];
+        }
     }
 #pragma unroll
     for (int e = 0; e < kMergePerThread; ++e) {
         const int i = tid + e * T;
         if (isrep[e]) {
-            int before = 0;
-            for (int w = 0; w < e * nwaves + wave; ++w) before += wtot[w];
-            const int ci = before + incl[e] - 1;
+            const int ci = before[e] + incl[e] - 1;
             key[ci] = kreg[e];  // key[] is dead: every thread holds its keys in registers
             cidx[i] = ci;       // the table is dead after the barrier above
         }

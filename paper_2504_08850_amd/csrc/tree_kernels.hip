@@ -25,7 +25,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(const int32_t *ids
     const int g = blockIdx.x, tid = threadIdx.x;
     int32_t *uniq;
     int col_of[kMergePerThread];
-    const int M = merge_block(ids + (size_t)g * n, n, merge_lds, uniq, col_of);
+    const int M = merge_block<kMergeThreads>(ids + (size_t)g * n, n, merge_lds, uniq, col_of);
     if (tid == 0) M_out[g] = M;
     for (int m = tid; m < Mcap; m += kMergeThreads) merged[(size_t)g * Mcap + m] = m < M ? uniq[m] : -1;
 #pragma unroll
@@ -35,105 +35,180 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(const int32_t *ids
     }
 }
 
-constexpr int kFinishThreads = 256;
-constexpr int kFinishWaves = kFinishThreads / kWave;  // nodes per workgroup: one per wavefront
-constexpr int kFinishUnits = 8;                       // hidden units per lane held in registers (H <= 512)
+constexpr int kFinishUnits = 8;  // hidden units per lane held in registers (H <= 512)
 
-template <int KC>
-__global__ __launch_bounds__(kFinishThreads) void tree_finish_kernel(TreeFinishParams p) {
+// Sum over the S d-slices of one partial value, ascending slice order, sixteen loads in flight.
+__device__ __forceinline__ float sum_slices(const float *src, size_t stride, int S) {
+    float a = 0.f;
+    int s = 0;
+    for (; s + 16 <= S; s += 16) {
+        float v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = src[(size_t)(s + u) * stride];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) a += v[u];
+    }
+    for (; s + 4 <= S; s += 4) {
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = src[(size_t)(s + u) * stride];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) a += v[u];
+    }
+    for (; s < S; ++s) a += src[(size_t)s * stride];
+    return a;
+}
+
+// WHOLE = false: 256 threads, one node per wavefront, a few nodes per workgroup -- the latency
+// shape (many CUs busy; the path rule runs in its own kernel).
+// WHOLE = true: 512 threads, one workgroup per tree -- the throughput shape.  All threads first
+// gather and sum every node's partials into LDS in one sweep (two dependent memory trips for the
+// whole tree), then the wavefronts take nodes in turn with the predictor rows held in registers,
+// and the path rule runs on the exit flags in LDS.
+template <int KC, bool WHOLE>
+__global__ __launch_bounds__(WHOLE ? 512 : 256) void tree_finish_kernel(TreeFinishParams p, int nodes_per_wg) {
+    extern __shared__ float finish_lds[];  // WHOLE: zsum [N][K+1] | prev [N][K] | exit [N]
+    constexpr int THREADS = WHOLE ? 512 : 256;
+    constexpr int kWaves = THREADS / kWave;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = blockIdx.y;
-    const int n = blockIdx.x * kFinishWaves + wave;
     const int K = p.K, H = p.H, S = p.S, N = p.N;
-    if (n >= N) return;  // no barriers below: wavefronts are independent
+    const int n_begin = blockIdx.x * nodes_per_wg;
+    const int n_end = min(N, n_begin + nodes_per_wg);
     const bool regs = (K == KC) && (H <= kFinishUnits * kWave) && KC <= 8;
+    float *zsum = finish_lds;
+    float *prevl = zsum + (size_t)N * (K + 1);
+    int32_t *exit_lds = reinterpret_cast<int32_t *>(prevl + (size_t)N * K);
 
     MlpRow<KC> rows[KC <= 8 ? kFinishUnits : 1];
     if (regs) {
 #pragma unroll
         for (int u = 0; u < kFinishUnits; ++u) mlp_row_load<KC>(rows[u], p.W1, p.b1, p.w2, K, H, lane + u * kWave);
     }
-    const size_t gn = (size_t)g * N + n;
-    // independent requests first: merged size, this node's ids, columns and previous probabilities
     const int M = p.M_out[g];
     const float b2 = p.b2 ? (float)p.b2[0] : 0.f;
-    int id = 0, col = 0;
-    if (lane < K) {
-        id = p.ids[gn * K + lane];
-        col = p.cols[gn * K + lane];
-    }
-    float prev[KC];
-#pragma unroll
-    for (int k = 0; k < KC; ++k) prev[k] = (k < K) ? p.prev[gn * K + k] : 0.f;
+    const size_t pstride = (size_t)p.Npad * p.Mpad;
 
-    // lanes 0..K-1: one logit each; lane K: the sum of squares.  Slices are summed in ascending
-    // order, sixteen loads in flight at a time.
-    float a = 0.f;
-    bool bad = M > p.Mcap;
-    const float *src = nullptr;
-    size_t stride = 0;
-    if (lane < K) {
-        if (id < 0 || id >= p.V) bad = true;
-        col = (col >= 0 && col < p.Mpad) ? col : 0;
-        src = p.partial + ((size_t)g * S * p.Npad + n) * p.Mpad + col;
-        stride = (size_t)p.Npad * p.Mpad;
-    } else if (lane == K) {
-        src = p.ssq_part + (size_t)g * S * p.Npad + n;
-        stride = (size_t)p.Npad;
-    }
-    if (src) {
-        int s = 0;
-        for (; s + 16 <= S; s += 16) {
-            float v[16];
-#pragma unroll
-            for (int u = 0; u < 16; ++u) v[u] = src[(size_t)(s + u) * stride];
-#pragma unroll
-            for (int u = 0; u < 16; ++u) a += v[u];
+    if (WHOLE) {
+        const int total = N * (K + 1);
+        for (int idx = tid; idx < total; idx += THREADS) {
+            const int n = idx / (K + 1), k = idx - n * (K + 1);
+            const size_t gn = (size_t)g * N + n;
+            float v;
+            if (k < K) {
+                const int id = p.ids[gn * K + k];
+                int col = p.cols[gn * K + k];
+                prevl[n * K + k] = p.prev[gn * K + k];
+                col = (col >= 0 && col < p.Mpad) ? col : 0;
+                v = sum_slices(p.partial + ((size_t)g * S * p.Npad + n) * p.Mpad + col, pstride, S);
+                if (id < 0 || id >= p.V || M > p.Mcap) v = quiet_nan();
+            } else {
+                v = sum_slices(p.ssq_part + (size_t)g * S * p.Npad + n, (size_t)p.Npad, S);
+            }
+            zsum[idx] = v;
         }
-        for (; s + 4 <= S; s += 4) {
-            float v[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) v[u] = src[(size_t)(s + u) * stride];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) a += v[u];
-        }
-        for (; s < S; ++s) a += src[(size_t)s * stride];
+        __syncthreads();
     }
-    bad = __any(bad);
-    const float r = 1.0f / sqrtf(__shfl(a, K, kWave) / (float)p.d + p.eps);
-    float z[KC], pr[KC];
-#pragma unroll
-    for (int k = 0; k < KC; ++k) {
-        float v = __shfl(a, k < K ? k : 0, kWave);
-        z[k] = (k < K) ? (bad ? quiet_nan() : v * r) : 0.f;
-    }
-    local_softmax<KC>(z, K, pr);
 
-    float part = 0.f;
-    if (regs) {
+    for (int n = n_begin + wave; n < n_end; n += kWaves) {
+        const size_t gn = (size_t)g * N + n;
+        float z[KC], pr[KC], prev[KC];
+        if (WHOLE) {
+            const float r = 1.0f / sqrtf(zsum[n * (K + 1) + K] / (float)p.d + p.eps);
 #pragma unroll
-        for (int u = 0; u < kFinishUnits; ++u)
-            if (lane + u * kWave < H) part += mlp_unit<KC>(rows[u], p.W1, K, lane + u * kWave, z, pr, prev);
-    } else {
-        for (int j = lane; j < H; j += kWave) {
-            MlpRow<KC> row;
-            mlp_row_load<KC>(row, p.W1, p.b1, p.w2, K, H, j);
-            part += mlp_unit<KC>(row, p.W1, K, j, z, pr, prev);
+            for (int k = 0; k < KC; ++k) {
+                z[k] = (k < K) ? zsum[n * (K + 1) + k] * r : 0.f;
+                prev[k] = (k < K) ? prevl[n * K + k] : 0.f;
+            }
+        } else {
+            // independent requests first: this node's ids, columns and previous probabilities
+            int id = 0, col = 0;
+            if (lane < K) {
+                id = p.ids[gn * K + lane];
+                col = p.cols[gn * K + lane];
+            }
+#pragma unroll
+            for (int k = 0; k < KC; ++k) prev[k] = (k < K) ? p.prev[gn * K + k] : 0.f;
+            // lanes 0..K-1: one logit each; lane K: the sum of squares
+            float a = 0.f;
+            bool bad = M > p.Mcap;
+            if (lane < K) {
+                if (id < 0 || id >= p.V) bad = true;
+                col = (col >= 0 && col < p.Mpad) ? col : 0;
+                a = sum_slices(p.partial + ((size_t)g * S * p.Npad + n) * p.Mpad + col, pstride, S);
+            } else if (lane == K) {
+                a = sum_slices(p.ssq_part + (size_t)g * S * p.Npad + n, (size_t)p.Npad, S);
+            }
+            bad = __any(bad);
+            const float r = 1.0f / sqrtf(__shfl(a, K, kWave) / (float)p.d + p.eps);
+#pragma unroll
+            for (int k = 0; k < KC; ++k) {
+                float v = __shfl(a, k < K ? k : 0, kWave);
+                z[k] = (k < K) ? (bad ? quiet_nan() : v * r) : 0.f;
+            }
         }
-    }
-    part = wave_sum(part);
-    const float sc = sigmoidf(b2 + part);
-    if (lane == 0) {
-        p.scores[gn] = sc;
-        p.exit_flags[gn] = (sc > p.threshold) ? 1 : 0;
-    }
-    if (lane < K) {
-        p.logits[gn * K + lane] = bad ? quiet_nan() : a * r;
-        float mine = 0.f;
+        local_softmax<KC>(z, K, pr);
+        // a NaN logit (invalid id / overflowing merged set) poisons the whole node
+        bool poisoned = false;
 #pragma unroll
         for (int k = 0; k < KC; ++k)
-            if (k == lane) mine = pr[k];
-        p.probs[gn * K + lane] = mine;
+            if (k < K && z[k] != z[k]) poisoned = true;
+
+        float part = 0.f;
+        if (regs) {
+            // keep the rows packed as fp16 across nodes: without this the compiler widens all of them to
+            // fp32 outside the node loop and runs out of registers
+#pragma unroll
+            for (int u = 0; u < kFinishUnits; ++u)
+#pragma unroll
+                for (int q = 0; q < (3 * KC) / 4; ++q)
+                    asm volatile("" : "+v"(rows[u].w1[q].x), "+v"(rows[u].w1[q].y));
+#pragma unroll
+            for (int u = 0; u < kFinishUnits; ++u)
+                if (lane + u * kWave < H) part += mlp_unit<KC>(rows[u], p.W1, K, lane + u * kWave, z, pr, prev);
+        } else {
+            for (int j = lane; j < H; j += kWave) {
+                MlpRow<KC> row;
+                mlp_row_load<KC>(row, p.W1, p.b1, p.w2, K, H, j);
+                part += mlp_unit<KC>(row, p.W1, K, j, z, pr, prev);
+            }
+        }
+        part = wave_sum(part);
+        const float sc = sigmoidf(b2 + part);
+        const int ex = (sc > p.threshold) ? 1 : 0;
+        if (lane == 0) {
+            p.scores[gn] = sc;
+            p.exit_flags[gn] = ex;
+            if (WHOLE) exit_lds[n] = ex;
+        }
+        if (lane < K) {
+            float zl = 0.f, pl = 0.f;
+#pragma unroll
+            for (int k = 0; k < KC; ++k)
+                if (k == lane) {
+                    zl = z[k];
+                    pl = pr[k];
+                }
+            p.logits[gn * K + lane] = poisoned ? quiet_nan() : zl;
+            p.probs[gn * K + lane] = pl;
+        }
+    }
+    if (WHOLE && p.path_exit) {  // whole tree in this workgroup: the path rule from LDS
+        __syncthreads();
+        const int32_t *par = p.parent + (size_t)g * N;
+        for (int n = tid; n < N; n += THREADS) {
+            int cur = n, ok = 1;
+            for (int step = 0; step < N && cur >= 0; ++step) {  // parents precede children: at most N steps
+                ok &= exit_lds[cur];
+                int up = par[cur];
+                if (up >= cur) {  // malformed tree: refuse the path rather than loop
+                    ok = 0;
+                    break;
+                }
+                cur = up;
+            }
+            p.path_exit[(size_t)g * N + n] = ok;
+        }
     }
 }
 
@@ -164,20 +239,30 @@ hipError_t launch_merge(const int32_t *ids, int n, int G, int Mcap, int32_t *mer
     return hipGetLastError();
 }
 
-hipError_t launch_tree_finish(const TreeFinishParams &p, int G, hipStream_t st) {
-    dim3 grid((p.N + kFinishWaves - 1) / kFinishWaves, G), block(kFinishThreads);
-    if (p.K <= 4)
-        hipLaunchKernelGGL((tree_finish_kernel<4>), grid, block, 0, st, p);
-    else if (p.K <= 8)
-        hipLaunchKernelGGL((tree_finish_kernel<8>), grid, block, 0, st, p);
-    else
-        hipLaunchKernelGGL((tree_finish_kernel<16>), grid, block, 0, st, p);
+template <int KC>
+static hipError_t launch_finish_kc(const TreeFinishParams &p, int G, hipStream_t st) {
+    // enough trees to fill the GPU with one workgroup each: predictor weights are fetched once per tree,
+    // the path rule needs no second kernel
+    const size_t whole_lds = ((size_t)p.N * (p.K + 1) + (size_t)p.N * p.K + p.N) * sizeof(float);
+    if (G >= 32 && whole_lds <= 60 * 1024) {
+        hipLaunchKernelGGL((tree_finish_kernel<KC, true>), dim3(1, G), dim3(512), whole_lds, st, p, p.N);
+        return hipGetLastError();
+    }
+    const int per_wg = 4;  // one node per wavefront
+    hipLaunchKernelGGL((tree_finish_kernel<KC, false>), dim3((p.N + per_wg - 1) / per_wg, G), dim3(256), 0, st, p,
+                       per_wg);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || !p.path_exit) return e;
     const int total = p.N * G;
     hipLaunchKernelGGL(path_kernel, dim3((total + 255) / 256), dim3(256), 0, st, p.exit_flags, p.parent, p.N, total,
                        p.path_exit);
     return hipGetLastError();
+}
+
+hipError_t launch_tree_finish(const TreeFinishParams &p, int G, hipStream_t st) {
+    if (p.K <= 4) return launch_finish_kc<4>(p, G, st);
+    if (p.K <= 8) return launch_finish_kc<8>(p, G, st);
+    return launch_finish_kc<16>(p, G, st);
 }
 
 }  // namespace specee
