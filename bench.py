@@ -40,7 +40,8 @@ MEASURED_TRAFFIC = {}
 _traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json.txt")
 if os.path.exists(_traffic_file):
     try:
-        MEASURED_TRAFFIC = json.loads(open(_traffic_file).read().split("---JSON---")[1])
+        MEASURED_TRAFFIC = {k: v["fetch_bytes"] + v["write_bytes"] for k, v in
+                            json.loads(open(_traffic_file).read().split("---JSON---")[1]).items()}
     except Exception:  # noqa: BLE001 - a malformed summary must not break the benchmark
         MEASURED_TRAFFIC = {}
 
@@ -292,20 +293,22 @@ def main():
         byts = int(np.mean([c3.N * d * 2 + m * d * 2 for m in Ms])) + d * 2 + (3 * K * H + H) * 2
         extra["c3_tree_N60"] = {"us_per_call": us, "mean_M": float(np.mean(Ms)), "algorithmic_bytes": byts,
                                 "achieved_GBps": byts / us / 1e3, "node_evals_per_s": c3.N / us * 1e6}
-        # throughput: G trees per launch
+        # throughput: G different trees per launch (own hidden states, own id pools)
         for G in (64, 256):
-            ii = torch.stack([dev_trees[i % 32][1] for i in range(G)])
-            pp = torch.stack([dev_trees[i % 32][2] for i in range(G)])
-            par = torch.stack([dev_trees[i % 32][3] for i in range(G)])
-            # different hidden states per tree so nothing is shared between trees but the LM head
-            hh = up(synth.hidden(c3.N, d, 999, lead=(G,)))
+            tg = [synth.make("C3", seed=1000 + i, lm=lm_h) for i in range(G)]
+            hh = up(np.stack([t["hidden"] for t in tg]))
+            ii_h = np.stack([t["ids"] for t in tg])
+            ii, pp = up(ii_h), up(np.stack([t["prev_probs"] for t in tg]))
+            par = up(np.stack([t["parent"] for t in tg]))
             og = sp.predict_tree(hh, gamma, lm, ii, pp, tw1, tw2, parent=par, Mcap=c3.Mcap)
             wsg = og.pop("_workspace")
             g = capture(lambda: sp.predict_tree(hh, gamma, lm, ii, pp, tw1, tw2, parent=par, Mcap=c3.Mcap, out=og,
                                                 workspace=wsg))
             us = ev_time(g.replay, 20, 3) * 1e3
-            bytsG = sum(c3.N * d * 2 + Ms[i % 32] * d * 2 for i in range(G)) + d * 2 + (3 * K * H + H) * 2
+            # hidden states of every tree + every LM-head row the batch touches, once
+            bytsG = G * c3.N * d * 2 + len(np.unique(ii_h)) * d * 2 + d * 2 + (3 * K * H + H) * 2
             extra[f"c3_tree_batch_G{G}"] = {"us_per_launch": us, "node_evals_per_s": G * c3.N / us * 1e6,
+                                            "distinct_rows_in_batch": int(len(np.unique(ii_h))),
                                             "algorithmic_bytes": bytsG, "achieved_GBps": bytsG / us / 1e3,
                                             "frac_of_8TBps": bytsG / us / 1e3 / HBM_PEAK_GBS}
 
