@@ -29,6 +29,7 @@
 #include "device_utils.h"
 #include "kernels.h"
 #include "merge_block.h"
+#include "tree_finish.h"
 
 namespace specee {
 
@@ -39,7 +40,10 @@ constexpr int kNB = 64;           // hidden states per workgroup (4 n-tiles of 1
 constexpr int kLdsRow = kKC + 8;  // halves per LDS row: 144 bytes, keeps 16-byte reads spread over banks
 
 // MODE 0: un-normalised partial sums per d-slice (tree); 1: normalised logits stored (full head);
-// 2: normalised logits reduced to one arg-max candidate per hidden state and workgroup (verification).
+// 2: normalised logits reduced to one arg-max candidate per hidden state and workgroup (verification);
+// 3: whole tree in one workgroup (needs FUSED, one d-slice, N <= 64, Mcap <= 64*TPW): the logits stay
+//    in LDS and the same workgroup scores every node and applies the path rule -- nothing but the
+//    inputs is read from memory and nothing but the outputs is written.
 // FUSED (tree only, N*K <= 1024): every workgroup merges the tree's ids itself in LDS before the
 // contraction, which removes a kernel launch and a dependent round trip from the latency path;
 // workgroup (0,0) of each tree publishes merged ids, their count and the columns.
@@ -49,10 +53,16 @@ constexpr int kStageHalves = 2 * kNB * kLdsRow;  // one operand (hi or lo), both
 // PD: prefetch distance in 64-element stages.  Streaming use keeps PD stages of global loads in
 // flight per wavefront; the latency-bound tree use picks PD >= the number of stages of a d-slice, so
 // every load of the workgroup is issued before the first one is consumed.
-template <int TPW, int MODE, bool FUSED, int PD>
-__global__ __launch_bounds__(kGemmThreads) void gather_gemm_kernel(GemmParams p) {
+template <int TPW, int MODE, bool FUSED, int PD, int KC = 4>
+__global__ __launch_bounds__(kGemmThreads) void gather_gemm_kernel(GemmParams p, TreeFinishParams f) {
     __shared__ __attribute__((aligned(16))) half_t smem[2 * kStageHalves];
     __shared__ float lds_ssq[kNB];
+    __shared__ int32_t cols_lds[MODE == 3 ? kGemmFusedMax : 1];
+    __shared__ float prev_lds[MODE == 3 ? kGemmFusedMax : 1];
+    __shared__ int32_t exit_lds[MODE == 3 ? kNB : 1];
+    static_assert(MODE != 3 || FUSED, "the whole-tree mode merges in its prologue");
+    static_assert(sizeof(half_t) * 2 * kStageHalves >= sizeof(float) * kNB * 64 * (MODE == 3 ? TPW : 1),
+                  "the logits of a whole tree must fit in the staging buffers");
     static_assert(sizeof(half_t) * 2 * kStageHalves >= sizeof(int32_t) * merge_lds_ints(kGemmFusedMax),
                   "merge scratch must fit in the staging buffers");
     typedef half_t (*stage_t)[kNB][kLdsRow];
@@ -88,6 +98,9 @@ __global__ __launch_bounds__(kGemmThreads) void gather_gemm_kernel(GemmParams p)
     // the hidden states do not depend on the merged set: request them before merging
 #pragma unroll
     for (int u = 0; u < PD; ++u) issue_b(u, u);
+    if (MODE == 3) {
+        for (int i = tid; i < p.N * p.K; i += kGemmThreads) prev_lds[i] = f.prev[(size_t)g * p.N * p.K + i];
+    }
 
     int M;
     int32_t *uniq = nullptr;
@@ -106,13 +119,21 @@ __global__ __launch_bounds__(kGemmThreads) void gather_gemm_kernel(GemmParams p)
                 if (i < n_ids) p.cols_out[(size_t)g * n_ids + i] = col_of[e];
             }
         }
+        if (MODE == 3) {
+#pragma unroll
+            for (int e = 0; e < kMergePerThread; ++e) {
+                int i = tid + e * kGemmThreads;
+                if (i < n_ids) cols_lds[i] = col_of[e];
+            }
+        }
         M = Mtrue;
     } else {
         M = p.Mptr ? p.Mptr[g] : p.Mcap;
     }
-    if (M > p.Mcap) M = p.Mcap;
+    const bool overflow = M > p.Mcap;
+    if (overflow) M = p.Mcap;
     const int m0 = blockIdx.x * (16 * TPW * kGemmWaves);
-    if (m0 >= M) return;  // uniform over the workgroup
+    if (MODE != 3 && m0 >= M) return;  // uniform over the workgroup
 
     // ---- A side: this lane's rows
     const half_t *rowptr[TPW];
@@ -158,18 +179,23 @@ __global__ __launch_bounds__(kGemmThreads) void gather_gemm_kernel(GemmParams p)
         for (int u = 0; u < PD; ++u) {
             const int kc = kc0 + u;
             if (kc < nchunks) {  // uniform over the workgroup
-                // split x = h*gamma into hi + lo and publish this stage
+                // split x = h*gamma into hi + lo and publish this stage.  Packed fp16 arithmetic does it
+                // exactly: hi = round(h*gamma) and lo = round(fma(h, gamma, -hi)), whose argument is the
+                // exact residual; the sum of squares accumulates in fp32 through the 2-way dot product.
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
                     half8 hi, lo;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        float hf = (float)h_buf[u][i][e];
-                        float x = hf * (float)g_buf[u][e];
-                        half_t xh = (half_t)x;
-                        hi[e] = xh;
-                        lo[e] = (half_t)(x - (float)xh);
-                        ssq[i] += hf * hf;
+                    for (int e = 0; e < 4; ++e) {
+                        const half2_t hh = {h_buf[u][i][2 * e], h_buf[u][i][2 * e + 1]};
+                        const half2_t gg = {g_buf[u][2 * e], g_buf[u][2 * e + 1]};
+                        const half2_t x = hh * gg;
+                        const half2_t rres = __builtin_elementwise_fma(hh, gg, -x);
+                        ssq[i] = __builtin_amdgcn_fdot2(hh, hh, ssq[i], false);
+                        hi[2 * e] = x[0];
+                        hi[2 * e + 1] = x[1];
+                        lo[2 * e] = rres[0];
+                        lo[2 * e + 1] = rres[1];
                     }
                     const int r = r0 + 32 * i;
                     *reinterpret_cast<half8 *>(&lds_hi[buf][r][vc * 8]) = hi;
@@ -228,6 +254,53 @@ __global__ __launch_bounds__(kGemmThreads) void gather_gemm_kernel(GemmParams p)
     }
 
     // ---- epilogue: lane holds Z[mt + 4q .. +3][n0 + nt*16 + c]
+    if (MODE == 3) {
+        // un-normalised logits of the whole tree into LDS (the staging buffers are dead: every wave
+        // passed the barrier above after its last matrix instruction)
+        // the predictor rows are requested only now: holding them across the contraction would halve
+        // the number of resident workgroups
+        FinishRows<KC> fr;
+        finish_load_rows<KC>(fr, f, lane);
+        float *Zl = reinterpret_cast<float *>(smem);
+        const int Mpad = 64 * TPW;
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+            for (int tp = 0; tp < TPW; ++tp) {
+                const int m = (wave * TPW + tp) * 16 + q * 4;
+                *reinterpret_cast<floatx4 *>(&Zl[(nt * 16 + c) * Mpad + m]) = acc[tp][nt];
+            }
+        __syncthreads();
+        const int K = p.K, N = p.N;
+        for (int n = wave; n < N; n += kGemmWaves) {
+            const size_t gn = (size_t)g * N + n;
+            float a = 0.f;
+            bool bad = overflow;
+            if (lane < K) {
+                const int id = p.ids[gn * K + lane];
+                if (id < 0 || id >= p.V) bad = true;
+                int col = cols_lds[n * K + lane];
+                col = (col >= 0 && col < Mpad) ? col : 0;
+                a = Zl[n * Mpad + col];
+            }
+            bad = __any(bad);
+            const float r = 1.0f / sqrtf(lds_ssq[n] / (float)d + p.eps);
+            float z[KC], prev[KC];
+#pragma unroll
+            for (int k = 0; k < KC; ++k) {
+                float v = __shfl(a, k < K ? k : 0, kWave);
+                z[k] = (k < K) ? (bad ? quiet_nan() : v * r) : 0.f;
+                prev[k] = (k < K) ? prev_lds[n * K + k] : 0.f;
+            }
+            const int ex = finish_score_node<KC>(fr, f, gn, z, prev, lane);
+            if (lane == 0) exit_lds[n] = ex;
+        }
+        if (f.path_exit) {
+            __syncthreads();
+            finish_paths(exit_lds, f.parent + (size_t)g * N, N, tid, kGemmThreads, f.path_exit + (size_t)g * N);
+        }
+        return;
+    }
     if (MODE == 2) {
         __shared__ float cand_v[kGemmWaves][kNB];
         __shared__ int cand_i[kGemmWaves][kNB];
@@ -311,7 +384,8 @@ template <int MODE, int TPW, int PD>
 static void launch_one(const GemmParams &p, int G, hipStream_t st) {
     const int rows_per_wg = 16 * TPW * kGemmWaves;
     dim3 grid((p.Mcap + rows_per_wg - 1) / rows_per_wg, p.S, G * ((p.N + kNB - 1) / kNB));
-    hipLaunchKernelGGL((gather_gemm_kernel<TPW, MODE, false, PD>), grid, dim3(kGemmThreads), 0, st, p);
+    hipLaunchKernelGGL((gather_gemm_kernel<TPW, MODE, false, PD>), grid, dim3(kGemmThreads), 0, st, p,
+                       TreeFinishParams{});
 }
 
 // Streaming configurations measured on MI355X (fp16 head, N = 16..64 hidden states):
@@ -334,9 +408,34 @@ hipError_t launch_tree_gemm(const GemmParams &p, int G, hipStream_t st) {
     const int rows_per_wg = 16 * kGemmWaves;
     dim3 grid((p.Mcap + rows_per_wg - 1) / rows_per_wg, p.S, G * ((p.N + kNB - 1) / kNB));
     if (p.ids)
-        hipLaunchKernelGGL((gather_gemm_kernel<1, 0, true, kTreePD>), grid, dim3(kGemmThreads), 0, st, p);
+        hipLaunchKernelGGL((gather_gemm_kernel<1, 0, true, kTreePD>), grid, dim3(kGemmThreads), 0, st, p,
+                           TreeFinishParams{});
     else
-        hipLaunchKernelGGL((gather_gemm_kernel<1, 0, false, kTreePD>), grid, dim3(kGemmThreads), 0, st, p);
+        hipLaunchKernelGGL((gather_gemm_kernel<1, 0, false, kTreePD>), grid, dim3(kGemmThreads), 0, st, p,
+                           TreeFinishParams{});
+    return hipGetLastError();
+}
+
+// Whole tree per workgroup: one launch does merge, contraction, scoring and the path rule.
+bool tree_whole_supported(int N, int K, int Mcap) {
+    return N <= kNB && N * K <= kGemmFusedMax && Mcap <= 128;
+}
+
+template <int TPW, int KC>
+static void launch_whole(const GemmParams &p, const TreeFinishParams &f, int G, hipStream_t st) {
+    hipLaunchKernelGGL((gather_gemm_kernel<TPW, 3, true, kTreePD, KC>), dim3(1, 1, G), dim3(kGemmThreads), 0, st, p,
+                       f);
+}
+
+hipError_t launch_tree_whole(const GemmParams &p, const TreeFinishParams &f, int G, hipStream_t st) {
+    const bool wide = p.Mcap > 64;
+    if (f.K <= 4) {
+        if (wide) launch_whole<2, 4>(p, f, G, st); else launch_whole<1, 4>(p, f, G, st);
+    } else if (f.K <= 8) {
+        if (wide) launch_whole<2, 8>(p, f, G, st); else launch_whole<1, 8>(p, f, G, st);
+    } else {
+        if (wide) launch_whole<2, 16>(p, f, G, st); else launch_whole<1, 16>(p, f, G, st);
+    }
     return hipGetLastError();
 }
 

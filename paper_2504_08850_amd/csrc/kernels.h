@@ -74,6 +74,8 @@ hipError_t launch_merge(const int32_t *ids, int n, int G, int Mcap, int32_t *mer
 bool tree_gemm_can_fuse_merge(int n_ids);
 hipError_t launch_tree_gemm(const GemmParams &p, int G, hipStream_t st);
 hipError_t launch_tree_finish(const TreeFinishParams &p, int G, hipStream_t st);
+bool tree_whole_supported(int N, int K, int Mcap);
+hipError_t launch_tree_whole(const GemmParams &p, const TreeFinishParams &f, int G, hipStream_t st);
 // Full-vocabulary head for several hidden states on the matrix cores
 hipError_t launch_lm_head_gemm(int d, int V, float eps, int N, const half_t *hidden, const half_t *gamma,
                                const half_t *lm_head, float *out, hipStream_t st);

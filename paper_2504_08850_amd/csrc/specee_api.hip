@@ -55,6 +55,8 @@ TreeSplit tree_split(int d, int n_total, int N, int Mcap) {
     return {S, dslice};
 }
 
+constexpr int kWholeTreeMinTrees = 16;
+
 inline size_t align256(size_t b) {
     return (b + 255) & ~(size_t)255;
 }
@@ -206,29 +208,39 @@ int specee_predict_tree(const specee_dims *dm, int G, int N, int Mcap, const spe
     float *partial = reinterpret_cast<float *>(ws + lay.partial_off);
     float *ssq_part = reinterpret_cast<float *>(ws + lay.ssq_off);
 
-    // few trees: merge inside the contraction kernel (one launch less on the latency path);
-    // many trees: merge once per tree in its own small kernel instead of once per workgroup
-    const bool fuse = tree_gemm_can_fuse_merge(N * dm->K) && (long long)G * ts.S <= 64;
-    if (!fuse && launch_merge(ids, N * dm->K, G, Mcap, merged_ids, M_out, cols, st) != hipSuccess) return SPECEE_EHIP;
-
     GemmParams gp{};
     gp.d = dm->d; gp.V = dm->V; gp.N = N; gp.eps = dm->eps;
     gp.hidden = H(hidden); gp.gamma = H(gamma); gp.lm_head = H(lm_head);
     gp.rowlist = merged_ids; gp.Mptr = M_out; gp.Mcap = Mcap;
-    gp.dslice = ts.dslice; gp.S = ts.S;
     gp.out = partial; gp.ssq_part = ssq_part; gp.Mpad = lay.Mpad; gp.Npad = N;
-    gp.ids = fuse ? ids : nullptr; gp.K = dm->K;
+    gp.K = dm->K;
     gp.merged_out = merged_ids; gp.M_out = M_out; gp.cols_out = cols;
-    if (launch_tree_gemm(gp, G, st) != hipSuccess) return SPECEE_EHIP;
 
     TreeFinishParams fp{};
-    fp.d = dm->d; fp.V = dm->V; fp.K = dm->K; fp.H = dm->H; fp.N = N; fp.S = ts.S; fp.Mcap = Mcap;
+    fp.d = dm->d; fp.V = dm->V; fp.K = dm->K; fp.H = dm->H; fp.N = N; fp.Mcap = Mcap;
     fp.Mpad = lay.Mpad; fp.Npad = N; fp.eps = dm->eps; fp.threshold = dm->threshold;
     fp.partial = partial; fp.ssq_part = ssq_part; fp.ids = ids; fp.cols = cols; fp.M_out = M_out;
     fp.prev = prev_probs;
     fp.W1 = H(mlp->W1); fp.b1 = H(mlp->b1); fp.w2 = H(mlp->w2); fp.b2 = H(mlp->b2);
     fp.logits = logits; fp.probs = probs; fp.scores = scores; fp.exit_flags = exit_flags;
     fp.parent = parent; fp.path_exit = path_exit;
+
+    // enough small trees to occupy the GPU with one workgroup each: a single launch does merge,
+    // contraction over all of d, scoring and the path rule, and no partial sums touch memory
+    if (G >= kWholeTreeMinTrees && tree_whole_supported(N, dm->K, Mcap)) {
+        gp.ids = ids;
+        gp.dslice = ((dm->d + 63) / 64) * 64; gp.S = 1;
+        return launch_tree_whole(gp, fp, G, st) == hipSuccess ? SPECEE_OK : SPECEE_EHIP;
+    }
+
+    // few trees: split d over many workgroups; merge inside the contraction kernel (one launch less on the
+    // latency path) unless that would repeat it too often
+    const bool fuse = tree_gemm_can_fuse_merge(N * dm->K) && (long long)G * ts.S <= 64;
+    if (!fuse && launch_merge(ids, N * dm->K, G, Mcap, merged_ids, M_out, cols, st) != hipSuccess) return SPECEE_EHIP;
+    gp.ids = fuse ? ids : nullptr;
+    gp.dslice = ts.dslice; gp.S = ts.S;
+    if (launch_tree_gemm(gp, G, st) != hipSuccess) return SPECEE_EHIP;
+    fp.S = ts.S;
     if (launch_tree_finish(fp, G, st) != hipSuccess) return SPECEE_EHIP;
     return SPECEE_OK;
 }

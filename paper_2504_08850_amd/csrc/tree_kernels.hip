@@ -13,7 +13,7 @@
 #include "device_utils.h"
 #include "kernels.h"
 #include "merge_block.h"
-#include "predictor_tail.h"
+#include "tree_finish.h"
 
 namespace specee {
 
@@ -34,8 +34,6 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(const int32_t *ids
         if (i < n) cols[(size_t)g * n + i] = col_of[e];
     }
 }
-
-constexpr int kFinishUnits = 8;  // hidden units per lane held in registers (H <= 512)
 
 // Sum over the S d-slices of one partial value, ascending slice order, sixteen loads in flight.
 __device__ __forceinline__ float sum_slices(const float *src, size_t stride, int S) {
@@ -72,21 +70,16 @@ __global__ __launch_bounds__(WHOLE ? 512 : 256) void tree_finish_kernel(TreeFini
     constexpr int kWaves = THREADS / kWave;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = blockIdx.y;
-    const int K = p.K, H = p.H, S = p.S, N = p.N;
+    const int K = p.K, S = p.S, N = p.N;
     const int n_begin = blockIdx.x * nodes_per_wg;
     const int n_end = min(N, n_begin + nodes_per_wg);
-    const bool regs = (K == KC) && (H <= kFinishUnits * kWave) && KC <= 8;
     float *zsum = finish_lds;
     float *prevl = zsum + (size_t)N * (K + 1);
     int32_t *exit_lds = reinterpret_cast<int32_t *>(prevl + (size_t)N * K);
 
-    MlpRow<KC> rows[KC <= 8 ? kFinishUnits : 1];
-    if (regs) {
-#pragma unroll
-        for (int u = 0; u < kFinishUnits; ++u) mlp_row_load<KC>(rows[u], p.W1, p.b1, p.w2, K, H, lane + u * kWave);
-    }
+    FinishRows<KC> fr;
+    finish_load_rows<KC>(fr, p, lane);
     const int M = p.M_out[g];
-    const float b2 = p.b2 ? (float)p.b2[0] : 0.f;
     const size_t pstride = (size_t)p.Npad * p.Mpad;
 
     if (WHOLE) {
@@ -112,7 +105,7 @@ __global__ __launch_bounds__(WHOLE ? 512 : 256) void tree_finish_kernel(TreeFini
 
     for (int n = n_begin + wave; n < n_end; n += kWaves) {
         const size_t gn = (size_t)g * N + n;
-        float z[KC], pr[KC], prev[KC];
+        float z[KC], prev[KC];
         if (WHOLE) {
             const float r = 1.0f / sqrtf(zsum[n * (K + 1) + K] / (float)p.d + p.eps);
 #pragma unroll
@@ -147,68 +140,12 @@ __global__ __launch_bounds__(WHOLE ? 512 : 256) void tree_finish_kernel(TreeFini
                 z[k] = (k < K) ? (bad ? quiet_nan() : v * r) : 0.f;
             }
         }
-        local_softmax<KC>(z, K, pr);
-        // a NaN logit (invalid id / overflowing merged set) poisons the whole node
-        bool poisoned = false;
-#pragma unroll
-        for (int k = 0; k < KC; ++k)
-            if (k < K && z[k] != z[k]) poisoned = true;
-
-        float part = 0.f;
-        if (regs) {
-            // keep the rows packed as fp16 across nodes: without this the compiler widens all of them to
-            // fp32 outside the node loop and runs out of registers
-#pragma unroll
-            for (int u = 0; u < kFinishUnits; ++u)
-#pragma unroll
-                for (int q = 0; q < (3 * KC) / 4; ++q)
-                    asm volatile("" : "+v"(rows[u].w1[q].x), "+v"(rows[u].w1[q].y));
-#pragma unroll
-            for (int u = 0; u < kFinishUnits; ++u)
-                if (lane + u * kWave < H) part += mlp_unit<KC>(rows[u], p.W1, K, lane + u * kWave, z, pr, prev);
-        } else {
-            for (int j = lane; j < H; j += kWave) {
-                MlpRow<KC> row;
-                mlp_row_load<KC>(row, p.W1, p.b1, p.w2, K, H, j);
-                part += mlp_unit<KC>(row, p.W1, K, j, z, pr, prev);
-            }
-        }
-        part = wave_sum(part);
-        const float sc = sigmoidf(b2 + part);
-        const int ex = (sc > p.threshold) ? 1 : 0;
-        if (lane == 0) {
-            p.scores[gn] = sc;
-            p.exit_flags[gn] = ex;
-            if (WHOLE) exit_lds[n] = ex;
-        }
-        if (lane < K) {
-            float zl = 0.f, pl = 0.f;
-#pragma unroll
-            for (int k = 0; k < KC; ++k)
-                if (k == lane) {
-                    zl = z[k];
-                    pl = pr[k];
-                }
-            p.logits[gn * K + lane] = poisoned ? quiet_nan() : zl;
-            p.probs[gn * K + lane] = pl;
-        }
+        const int ex = finish_score_node<KC>(fr, p, gn, z, prev, lane);
+        if (WHOLE && lane == 0) exit_lds[n] = ex;
     }
     if (WHOLE && p.path_exit) {  // whole tree in this workgroup: the path rule from LDS
         __syncthreads();
-        const int32_t *par = p.parent + (size_t)g * N;
-        for (int n = tid; n < N; n += THREADS) {
-            int cur = n, ok = 1;
-            for (int step = 0; step < N && cur >= 0; ++step) {  // parents precede children: at most N steps
-                ok &= exit_lds[cur];
-                int up = par[cur];
-                if (up >= cur) {  // malformed tree: refuse the path rather than loop
-                    ok = 0;
-                    break;
-                }
-                cur = up;
-            }
-            p.path_exit[(size_t)g * N + n] = ok;
-        }
+        finish_paths(exit_lds, p.parent + (size_t)g * N, N, tid, THREADS, p.path_exit + (size_t)g * N);
     }
 }
 

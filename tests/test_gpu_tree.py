@@ -137,6 +137,90 @@ def test_tree_batch_of_independent_trees(sp, oracle):
     assert len(set(ref["M"].tolist())) > 1       # trees really differ in merged size
 
 
+def stack_trees(ts):
+    stack = lambda k: np.stack([t[k] for t in ts])
+    return dict(ts[0], hidden=stack("hidden"), ids=stack("ids"), prev_probs=stack("prev_probs"),
+                parent=stack("parent"))
+
+
+@pytest.mark.parametrize("name,G,bias", [("T3", 20, True), ("T3", 16, False)])
+def test_tree_many_trees_one_workgroup_each(sp, oracle, name, G, bias):
+    """Sixteen or more small trees take the single-launch path (merge, contraction, scoring and path rule
+    in one workgroup per tree); it must agree with the oracle like every other path."""
+    ts = [synth.make(name, seed=s, bias=bias) for s in range(G)]
+    c = ts[0]["cfg"]
+    tb = stack_trees(ts)
+    ref = ref_tree(oracle, tb, c.Mcap)
+    got = run_tree(sp, tb, dev(tb["lm_head"]), c.Mcap)
+    check_tree(got, ref, c.threshold, f"{G} x {name}")
+    assert 0 < ref["path_exit"].sum() < ref["exit"].sum()
+
+
+@pytest.mark.parametrize("d,V,K,H,N,Mcap", [
+    (520, 777, 8, 512, 21, 128),     # ragged d, K = 8, wide merged set (two row tiles per wave)
+    (1024, 300, 3, 100, 64, 64),     # K odd (generic MLP path), full 64 nodes
+    (256, 5000, 16, 2048, 40, 128),  # K = KMAX, H = HMAX
+    (4096, 2000, 4, 512, 60, 64),    # C3 shape
+    (64, 40, 1, 8, 5, 7),            # tiny
+])
+def test_tree_many_trees_shapes(sp, oracle, d, V, K, H, N, Mcap):
+    G = 17
+    ts = []
+    for gidx in range(G):
+        t = make_tree(1000 * gidx + d, d, V, K, H, N, bias=(K % 2 == 1))
+        pool = np.random.default_rng(gidx).permutation(V)[:Mcap]
+        t["ids"] = pool[np.random.default_rng(100 + gidx).integers(0, Mcap, size=(N, K))].astype(np.int32)
+        ts.append(t)
+    for t in ts[1:]:                 # one model: shared head, norm weight and predictor
+        for k in ("gamma", "lm_head", "W1", "w2", "b1", "b2"):
+            t[k] = ts[0][k]
+    tb = stack_trees(ts)
+    ref = ref_tree(oracle, tb, Mcap)
+    got = run_tree(sp, tb, dev(tb["lm_head"]), Mcap)
+    check_tree(got, ref, 0.5, f"17 trees d={d} K={K} N={N}")
+
+
+def test_tree_many_trees_overflow_invalid_ids_and_no_parent(sp, oracle):
+    ts = [synth.make("T3", seed=s) for s in range(16)]
+    c = ts[0]["cfg"]
+    tb = stack_trees(ts)
+    lm_d = dev(tb["lm_head"])
+    Ms = [len(np.unique(t["ids"])) for t in ts]
+    cap = sorted(Ms)[len(Ms) // 2]                       # about half of the trees overflow this capacity
+    got = run_tree(sp, tb, lm_d, cap)
+    assert np.array_equal(got["M"], np.array(Ms))
+    over = np.array(Ms) > cap
+    assert over.any() and not over.all()
+    assert np.all(np.isnan(got["scores"][over])) and got["exit"][over].sum() == 0 and got["path_exit"][over].sum() == 0
+    ref = ref_tree(oracle, tb, c.Mcap)
+    close(got["scores"][~over], ref["scores"][~over], 1e-3, "trees that fit beside trees that overflow")
+    bad = dict(tb, ids=tb["ids"].copy())
+    bad["ids"][3, 4, 1] = c.V
+    bad["ids"][7, 0, 0] = -3
+    got = run_tree(sp, bad, lm_d, c.Mcap, parent=None)
+    assert got["path_exit"] is None
+    assert np.isnan(got["scores"][3, 4]) and np.isnan(got["scores"][7, 0]) and got["exit"][3, 4] == 0
+    mask = np.ones((16, c.N), bool); mask[3, 4] = mask[7, 0] = False
+    close(got["scores"][mask], ref["scores"][mask], 1e-3, "valid nodes beside invalid ones")
+
+
+def test_tree_many_trees_c3_batch(sp, oracle):
+    c = synth.CONFIGS["C3"]
+    lm_h, lm_d = lm_for(c)
+    ts = [synth.make("C3", seed=100 + s, lm=lm_h) for s in range(24)]
+    tb = stack_trees(ts)
+    oracle.set_threads(8)
+    ref = ref_tree(oracle, tb, c.Mcap)
+    oracle.set_threads(1)
+    got = run_tree(sp, tb, lm_d, c.Mcap)
+    e = check_tree(got, ref, c.threshold, "24 x C3")
+    print("24 x C3 worst", e)
+    one = dict(ts[0], hidden=ts[5]["hidden"], ids=ts[5]["ids"], prev_probs=ts[5]["prev_probs"], parent=ts[5]["parent"])
+    single = run_tree(sp, one, lm_d, c.Mcap)            # the few-trees path gives the same answers
+    close(got["scores"][5], single["scores"], 1e-3, "whole-tree vs split path")
+    assert np.array_equal(got["merged"][5], single["merged"]) and np.array_equal(got["cols"][5], single["cols"])
+
+
 def test_tree_without_parent_and_with_malformed_parent(sp, oracle):
     t = synth.make("T4")
     c = t["cfg"]
