@@ -81,23 +81,24 @@ __global__ __launch_bounds__(kGemvThreads) void lm_head_gemv_kernel(int d, int V
         const half_t *w0 = lm_head + (size_t)row * d;
         const half_t *w1 = lm_head + (size_t)(two ? row + 1 : row) * d;
         float acc0 = 0.f, acc1 = 0.f;
+        // loads are unconditional (vector index clamped, contribution selected afterwards) so that the
+        // compiler keeps them all in flight instead of draining the memory pipeline at a branch join
         for (int v0 = lane; v0 < nv; v0 += kWave * kGemvUnroll) {
             half8 a[kGemvUnroll], b[kGemvUnroll];
 #pragma unroll
             for (int u = 0; u < kGemvUnroll; ++u) {
-                int v = v0 + u * kWave;
-                bool in = v < nv;
-                a[u] = in ? load_half8(w0 + v * 8) : zero_half8();
-                b[u] = in ? load_half8(w1 + v * 8) : zero_half8();
+                const int v = min(v0 + u * kWave, nv - 1);
+                a[u] = load_half8(w0 + v * 8);
+                b[u] = load_half8(w1 + v * 8);
             }
 #pragma unroll
             for (int u = 0; u < kGemvUnroll; ++u) {
-                int v = v0 + u * kWave;
-                if (v < nv) {
-                    floatx4 pa = xa[v], pb = xb[v];
-                    acc0 = dot8(a[u], pa, pb, acc0);
-                    acc1 = dot8(b[u], pa, pb, acc1);
-                }
+                const bool in = v0 + u * kWave < nv;
+                const int v = min(v0 + u * kWave, nv - 1);
+                const floatx4 pa = xa[v], pb = xb[v];
+                const float t0 = dot8(a[u], pa, pb, 0.f), t1 = dot8(b[u], pa, pb, 0.f);
+                acc0 += in ? t0 : 0.f;
+                acc1 += in ? t1 : 0.f;
             }
         }
         acc0 = wave_sum(acc0);

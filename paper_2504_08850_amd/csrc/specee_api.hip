@@ -25,7 +25,7 @@ int check_dims(const specee_dims *dm, bool need_predictor) {
 
 int check_mlp(const specee_mlp *m) {
     if (!m || !m->W1 || !m->w2) return SPECEE_EINVAL;
-    if (misaligned(m->W1) || misaligned(m->w2)) return SPECEE_EALIGN;
+    if (misaligned(m->W1) || misaligned(m->w2) || misaligned(m->b1)) return SPECEE_EALIGN;
     return SPECEE_OK;
 }
 

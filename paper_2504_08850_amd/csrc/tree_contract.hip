@@ -1,0 +1,429 @@
+// Token-tree contraction (paper Sec. 6.2, merged mapping): Z[n][m] = x_n . W[merged_m]
+// for the N <= 64 nodes of a tree against its M merged LM-head rows, on the matrix cores.
+//
+// A tree has few rows (M is tens to a couple of hundred) and up to 64 nodes, so the
+// operand that every wavefront needs in full is the small tile of LM-head rows, and the
+// operand that can stay private is a wavefront's own 16 nodes:
+//   * wavefront w owns node tile w.  Its B operand -- x = h*gamma of its 16 nodes, split
+//     exactly into hi + lo halves -- is built in registers from two 16-byte loads per
+//     lane and never touches LDS;
+//   * the A operand -- 16*MT gathered LM-head rows, 128 bytes of each per stage -- is
+//     loaded once per workgroup (16 bytes per lane, coalesced per row) into a
+//     double-buffered LDS tile and read by all four wavefronts.
+// Per 64-element stage the workgroup moves 8 KB into LDS and reads it four times, half
+// the LDS traffic of sharing x instead, and there is one barrier per stage.
+// v_mfma_f32_16x16x32_f16: lane = 16*q + c holds A[row c][k-slots of q], B[k-slots of q][node c]
+// and D[rows 4q..4q+3][node c].
+//
+// MODE 0: one d-slice per workgroup, un-normalised partial sums and partial sums of
+//         squares go to the workspace (few trees: many CUs share one tree).
+// MODE 3: one workgroup per tree over all of d.  The logits stay in LDS; the same
+//         workgroup gathers every node's K columns, builds the features and evaluates the
+//         predictor MLP -- for K in {4, 8} also on the matrix cores (W1 rows are the A
+//         operand, the 16 nodes' hi/lo-split features the B operand) -- then applies the
+//         path rule.  Only inputs are read and only outputs written.
+// FUSED: the merge of the tree's ids runs in the prologue (N*K <= 1024).
+#include "device_utils.h"
+#include "kernels.h"
+#include "merge_block.h"
+#include "tree_finish.h"
+
+namespace specee {
+
+constexpr int kTcThreads = 256;
+constexpr int kTcWaves = 4;
+constexpr int kTcKC = 64;             // k elements per stage
+constexpr int kTcRow = kTcKC + 8;     // halves per LDS row (144 bytes)
+constexpr int kTcFusedMax = kMergePerThread * kTcThreads;
+constexpr int kTcFeat = 32;           // feature slots per node in the matrix-core MLP (3K <= 32)
+
+// Predictor MLP for the 16 nodes of a wavefront on the matrix cores.
+// F: this wavefront's [16][kTcFeat] fp32 features in LDS (zero beyond 3K).  Returns the output
+// pre-activation (without b2) of node c = lane & 15 in every lane.
+__device__ __forceinline__ float mlp_mfma_16(const float *F, const TreeFinishParams &f, int lane) {
+    const int c = lane & 15, q = lane >> 4;
+    const int K3 = 3 * f.K, H = f.H;
+    half8 bhi, blo;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float v = F[c * kTcFeat + q * 8 + e];
+        const half_t h = (half_t)v;
+        bhi[e] = h;
+        blo[e] = (half_t)(v - (float)h);
+    }
+    const bool any_feat = q * 8 < K3;  // slots of this lane group that hold features at all
+    float acc_u = 0.f;
+    const int htiles = (H + 15) >> 4;
+    for (int ht = 0; ht < htiles; ++ht) {
+        const int unit = ht * 16 + c;  // W1 row this lane supplies
+        half8 a = zero_half8();
+        if (unit < H && any_feat) {
+            const uint2 *src = reinterpret_cast<const uint2 *>(f.W1 + (size_t)unit * K3 + q * 8);
+            const half4 lo4 = __builtin_bit_cast(half4, src[0]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) a[e] = lo4[e];
+            if (q * 8 + 4 < K3) {
+                const half4 hi4 = __builtin_bit_cast(half4, src[1]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) a[4 + e] = hi4[e];
+            }
+        }
+        floatx4 dacc = {0.f, 0.f, 0.f, 0.f};
+        dacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bhi, dacc, 0, 0, 0);
+        dacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, blo, dacc, 0, 0, 0);
+        // lane holds pre-activations of units ht*16 + 4q + r for node c
+        const int u0 = ht * 16 + 4 * q;
+        half4 w2v = {(half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f}, b1v = w2v;
+        if (u0 + 3 < H) {
+            w2v = __builtin_bit_cast(half4, *reinterpret_cast<const uint2 *>(f.w2 + u0));
+            if (f.b1) b1v = __builtin_bit_cast(half4, *reinterpret_cast<const uint2 *>(f.b1 + u0));
+        } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (u0 + r < H) {
+                    w2v[r] = f.w2[u0 + r];
+                    if (f.b1) b1v[r] = f.b1[u0 + r];
+                }
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc_u += (float)w2v[r] * fmaxf(dacc[r] + (float)b1v[r], 0.f);
+    }
+    acc_u += __shfl_xor(acc_u, 16, kWave);
+    acc_u += __shfl_xor(acc_u, 32, kWave);
+    return acc_u;
+}
+
+template <int MT, int MODE, bool FUSED, int PD, int KC>
+__global__ __launch_bounds__(kTcThreads) void tree_contract_kernel(GemmParams p, TreeFinishParams f) {
+    constexpr int ROWS = 16 * MT;            // LM-head rows per workgroup
+    constexpr int APT = MT / 2;              // 16-byte A vectors per thread per stage (ROWS*8/256)
+    constexpr int kALdsHalves = 2 * ROWS * kTcRow;
+    __shared__ __attribute__((aligned(16))) half_t smem[kALdsHalves];
+    __shared__ int32_t cols_lds[MODE == 3 ? kTcFusedMax : 1];
+    __shared__ float prev_lds[MODE == 3 ? kTcFusedMax : 1];
+    __shared__ float feat_lds[MODE == 3 ? kTcWaves * 16 * kTcFeat : 1];
+    __shared__ float ssq_lds[MODE == 3 ? 64 : 1];
+    __shared__ int32_t bad_lds[MODE == 3 ? 64 : 1];
+    __shared__ int32_t exit_lds[MODE == 3 ? 64 : 1];
+    static_assert(MT == 4 || MT == 8, "row tiles per workgroup");
+    static_assert(sizeof(half_t) * kALdsHalves >= sizeof(int32_t) * merge_lds_ints(kTcFusedMax),
+                  "merge scratch must fit in the row tile buffers");
+    static_assert(sizeof(half_t) * kALdsHalves >= sizeof(float) * 64 * ROWS, "whole-tree logits must fit");
+    static_assert(MODE != 3 || FUSED, "the whole-tree mode merges in its prologue");
+    typedef half_t (*tile_t)[ROWS][kTcRow];
+    tile_t a_lds = reinterpret_cast<tile_t>(smem);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, q = lane >> 4;
+    const int NBn = (p.N + 63) / 64;
+    const int g = blockIdx.z / NBn, nb = blockIdx.z - g * NBn;
+    const int n0 = nb * 64;
+    const int s = blockIdx.y;
+    const int d = p.d;
+    const int k_begin = s * p.dslice;
+    const int k_end = min(d, k_begin + p.dslice);
+    const int nchunks = (k_end - k_begin + kTcKC - 1) / kTcKC;
+
+    // ---- B side: this lane's node and k-slots; requested before anything else
+    const int node = n0 + wave * 16 + c;
+    const bool node_ok = node < p.N;
+    const half_t *hrow = p.hidden + ((size_t)g * p.N + (node_ok ? node : 0)) * d;
+    half8 h_buf[PD][2], g_buf[PD][2];
+    // Loads are unconditional (addresses clamped into the row, results zeroed by a select when they
+    // are consumed): a load under a branch makes the compiler drain every outstanding load at the
+    // join, which would serialise the prefetch stages.
+    auto issue_b = [&](int kc, int slot) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int ko = min(k_begin + kc * kTcKC + q * 16 + j * 8, d - 8);  // stages past the end re-read the tail
+            g_buf[slot][j] = load_half8(p.gamma + ko);
+            h_buf[slot][j] = load_half8(hrow + ko);
+        }
+    };
+    auto b_valid = [&](int kc, int j) {
+        return node_ok && k_begin + kc * kTcKC + q * 16 + j * 8 < k_end;
+    };
+#pragma unroll
+    for (int u = 0; u < PD; ++u) issue_b(u, u);
+    if (MODE == 3) {
+        const int n_ids = p.N * p.K;
+        for (int i = tid; i < n_ids; i += kTcThreads) prev_lds[i] = f.prev[(size_t)g * n_ids + i];
+        if (tid < 64) bad_lds[tid] = 0;
+    }
+
+    // ---- merged rows
+    int M;
+    int32_t *uniq = nullptr;
+    if (FUSED) {
+        const int n_ids = p.N * p.K;
+        int col_of[kMergePerThread];
+        const int Mtrue = merge_block<kTcThreads>(p.ids + (size_t)g * n_ids, n_ids, reinterpret_cast<int32_t *>(smem),
+                                                  uniq, col_of);
+        if (blockIdx.x == 0 && blockIdx.y == 0 && nb == 0) {
+            if (tid == 0) p.M_out[g] = Mtrue;
+            for (int m = tid; m < p.Mcap; m += kTcThreads)
+                p.merged_out[(size_t)g * p.Mcap + m] = m < Mtrue ? uniq[m] : -1;
+#pragma unroll
+            for (int e = 0; e < kMergePerThread; ++e) {
+                const int i = tid + e * kTcThreads;
+                if (i < n_ids) p.cols_out[(size_t)g * n_ids + i] = col_of[e];
+            }
+        }
+        if (MODE == 3) {
+#pragma unroll
+            for (int e = 0; e < kMergePerThread; ++e) {
+                const int i = tid + e * kTcThreads;
+                if (i < n_ids) {
+                    cols_lds[i] = col_of[e];
+                    const int id = p.ids[(size_t)g * n_ids + i];
+                    if (id < 0 || id >= p.V) bad_lds[i / p.K] = 1;  // benign race: every writer stores 1
+                }
+            }
+        }
+        M = Mtrue;
+    } else {
+        M = p.Mptr ? p.Mptr[g] : p.Mcap;
+    }
+    const bool overflow = M > p.Mcap;
+    if (overflow) M = p.Mcap;
+    const int m0 = blockIdx.x * ROWS;
+    if (MODE != 3 && m0 >= M) return;  // uniform over the workgroup
+
+    // ---- A side: this thread copies vectors (row, v) of the row tile: index = tid + 256*i
+    const half_t *arow[APT];
+    bool arow_ok[APT];
+    int a_r[APT], a_v[APT];
+#pragma unroll
+    for (int i = 0; i < APT; ++i) {
+        const int vi = tid + kTcThreads * i;
+        a_r[i] = vi >> 3;
+        a_v[i] = vi & 7;
+        const int m = m0 + a_r[i];
+        arow_ok[i] = m < M;
+        int row = 0;
+        if (arow_ok[i]) {
+            row = FUSED ? uniq[m] : (p.rowlist ? p.rowlist[(size_t)g * p.Mcap + m] : m);
+            if (row < 0 || row >= p.V) row = 0;  // invalid id: the node is reported NaN, nothing is read out of bounds
+        }
+        arow[i] = p.lm_head + (size_t)row * d;
+    }
+    if (FUSED) __syncthreads();  // the merge scratch becomes the row tile buffers
+    half8 a_buf[PD][APT];
+    auto issue_a = [&](int kc, int slot) {
+#pragma unroll
+        for (int i = 0; i < APT; ++i) {
+            const int ko = min(k_begin + kc * kTcKC + a_v[i] * 8, d - 8);
+            a_buf[slot][i] = load_half8(arow[i] + ko);
+        }
+    };
+    auto a_valid = [&](int kc, int i) {
+        return arow_ok[i] && k_begin + kc * kTcKC + a_v[i] * 8 < k_end;
+    };
+#pragma unroll
+    for (int u = 0; u < PD; ++u) issue_a(u, u);
+
+    floatx4 acc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    float ssq = 0.f;
+
+    // The stage loop is free of branches (stages past the end are issued on clamped addresses and
+    // contribute zeros) so that the compiler can keep PD stages of loads outstanding instead of
+    // draining the memory pipeline at every control-flow join.
+    const int nstages = ((nchunks + PD - 1) / PD) * PD;
+    int buf = 0;
+    for (int kc0 = 0; kc0 < nstages; kc0 += PD) {
+#pragma unroll
+        for (int u = 0; u < PD; ++u) {
+            const int kc = kc0 + u;
+#pragma unroll
+            for (int i = 0; i < APT; ++i)
+                *reinterpret_cast<half8 *>(&a_lds[buf][a_r[i]][a_v[i] * 8]) =
+                    a_valid(kc, i) ? a_buf[u][i] : zero_half8();
+            // x = h*gamma split exactly into hi = round(h*gamma), lo = round(fma(h, gamma, -hi))
+            half8 bhi[2], blo[2];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const half8 hsel = b_valid(kc, j) ? h_buf[u][j] : zero_half8();
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const half2_t hh = {hsel[2 * e], hsel[2 * e + 1]};
+                    const half2_t gg = {g_buf[u][j][2 * e], g_buf[u][j][2 * e + 1]};
+                    const half2_t x = hh * gg;
+                    const half2_t rres = __builtin_elementwise_fma(hh, gg, -x);
+                    ssq = __builtin_amdgcn_fdot2(hh, hh, ssq, false);
+                    bhi[j][2 * e] = x[0];
+                    bhi[j][2 * e + 1] = x[1];
+                    blo[j][2 * e] = rres[0];
+                    blo[j][2 * e + 1] = rres[1];
+                }
+            }
+            __syncthreads();
+            issue_a(kc + PD, u);
+            issue_b(kc + PD, u);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                half8 a[MT];
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    a[mt] = *reinterpret_cast<const half8 *>(&a_lds[buf][mt * 16 + c][q * 16 + j * 8]);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], bhi[j], acc[mt], 0, 0, 0);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], blo[j], acc[mt], 0, 0, 0);
+            }
+            buf ^= 1;
+        }
+    }
+    // sum of squares of node c over this k-range: combine the four k-slot groups
+    ssq += __shfl_xor(ssq, 16, kWave);
+    ssq += __shfl_xor(ssq, 32, kWave);
+
+    if (MODE == 0) {
+        if (blockIdx.x == 0 && q == 0 && node_ok) p.ssq_part[((size_t)g * p.S + s) * p.Npad + node] = ssq;
+        if (node_ok) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const int mtile = m0 + mt * 16;
+                if (mtile < M) {  // Mpad is a multiple of 16: the quad is in bounds and aligned
+                    float *dst = p.out + (((size_t)g * p.S + s) * p.Npad + node) * p.Mpad + mtile + q * 4;
+                    *reinterpret_cast<floatx4 *>(dst) = acc[mt];
+                }
+            }
+        }
+        return;
+    }
+
+    // ---- MODE 3: score the whole tree here
+    __syncthreads();  // every wavefront is done with the row tiles: reuse them for the logits
+    float *Zl = reinterpret_cast<float *>(smem);  // [64 nodes][ROWS]
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+        *reinterpret_cast<floatx4 *>(&Zl[(wave * 16 + c) * ROWS + mt * 16 + q * 4]) = acc[mt];
+    if (q == 0) ssq_lds[wave * 16 + c] = ssq;
+    __syncthreads();
+
+    const int K = p.K, N = p.N;
+    const bool mfma_mlp = (K == 4 || K == 8) && KC <= 8;
+    if (mfma_mlp) {
+        // lanes q == 0 build the features of node c; all lanes then feed the matrix cores
+        float *F = feat_lds + wave * 16 * kTcFeat;
+        const int n = wave * 16 + c;  // node within the tree (N <= 64: n0 == 0)
+        const size_t gn = (size_t)g * N + n;
+        bool poisoned = false;
+        float z[KC], pr[KC];
+        if (q == 0) {
+            const float r = 1.0f / sqrtf(ssq_lds[n] / (float)d + p.eps);
+            const bool bad = overflow || (n < N && bad_lds[n] != 0);
+#pragma unroll
+            for (int k = 0; k < KC; ++k) {
+                float v = 0.f;
+                if (k < K && n < N) {
+                    int col = cols_lds[n * K + k];
+                    col = (col >= 0 && col < ROWS) ? col : 0;
+                    v = bad ? quiet_nan() : Zl[n * ROWS + col] * r;
+                }
+                z[k] = v;
+            }
+            local_softmax<KC>(z, K, pr);
+            poisoned = bad;
+#pragma unroll
+            for (int k = 0; k < KC; ++k)
+                if (k < K) {
+                    const float pv = n < N ? prev_lds[n * K + k] : 0.f;
+                    F[c * kTcFeat + k] = z[k];
+                    F[c * kTcFeat + K + k] = pr[k];
+                    F[c * kTcFeat + 2 * K + k] = pr[k] - pv;
+                }
+            for (int t = 3 * K; t < kTcFeat; ++t) F[c * kTcFeat + t] = 0.f;
+        }
+        __syncthreads();
+        const float u = mlp_mfma_16(F, f, lane);
+        if (q == 0 && n < N) {
+            const float b2 = f.b2 ? (float)f.b2[0] : 0.f;
+            float sc = sigmoidf(b2 + u);
+            if (poisoned) sc = quiet_nan();
+            const int ex = (sc > f.threshold) ? 1 : 0;
+            f.scores[gn] = sc;
+            f.exit_flags[gn] = ex;
+            exit_lds[n] = ex;
+#pragma unroll
+            for (int k = 0; k < KC; ++k)
+                if (k < K) {
+                    f.logits[gn * K + k] = z[k];
+                    f.probs[gn * K + k] = pr[k];
+                }
+        }
+    } else {
+        FinishRows<KC> fr;
+        finish_load_rows<KC>(fr, f, lane);
+        for (int n = wave; n < N; n += kTcWaves) {
+            const size_t gn = (size_t)g * N + n;
+            float a = 0.f;
+            if (lane < K) {
+                int col = cols_lds[n * K + lane];
+                col = (col >= 0 && col < ROWS) ? col : 0;
+                a = Zl[n * ROWS + col];
+            }
+            const bool bad = overflow || bad_lds[n] != 0;
+            const float r = 1.0f / sqrtf(ssq_lds[n] / (float)d + p.eps);
+            float z[KC], prev[KC];
+#pragma unroll
+            for (int k = 0; k < KC; ++k) {
+                float v = __shfl(a, k < K ? k : 0, kWave);
+                z[k] = (k < K) ? (bad ? quiet_nan() : v * r) : 0.f;
+                prev[k] = (k < K) ? prev_lds[n * K + k] : 0.f;
+            }
+            const int ex = finish_score_node<KC>(fr, f, gn, z, prev, lane);
+            if (lane == 0) exit_lds[n] = ex;
+        }
+    }
+    if (f.path_exit) {
+        __syncthreads();
+        finish_paths(exit_lds, f.parent + (size_t)g * N, N, tid, kTcThreads, f.path_exit + (size_t)g * N);
+    }
+}
+
+constexpr int kTcPD = 4;  // a 256-element d-slice is requested in one go; longer ranges keep 4 stages in flight
+
+bool tree_gemm_can_fuse_merge(int n_ids) {
+    return n_ids <= kTcFusedMax;
+}
+
+// d-slice partial sums: grid (row groups of 64, d-slices, trees x node blocks)
+hipError_t launch_tree_gemm(const GemmParams &p, int G, hipStream_t st) {
+    dim3 grid((p.Mcap + 63) / 64, p.S, G * ((p.N + 63) / 64));
+    if (p.ids)
+        hipLaunchKernelGGL((tree_contract_kernel<4, 0, true, kTcPD, 4>), grid, dim3(kTcThreads), 0, st, p,
+                           TreeFinishParams{});
+    else
+        hipLaunchKernelGGL((tree_contract_kernel<4, 0, false, kTcPD, 4>), grid, dim3(kTcThreads), 0, st, p,
+                           TreeFinishParams{});
+    return hipGetLastError();
+}
+
+// Whole tree per workgroup: one launch does merge, contraction, scoring and the path rule.
+bool tree_whole_supported(int N, int K, int Mcap) {
+    return N <= 64 && N * K <= kTcFusedMax && Mcap <= 128;
+}
+
+template <int MT, int KC>
+static void launch_whole(const GemmParams &p, const TreeFinishParams &f, int G, hipStream_t st) {
+    hipLaunchKernelGGL((tree_contract_kernel<MT, 3, true, kTcPD, KC>), dim3(1, 1, G), dim3(kTcThreads), 0, st, p, f);
+}
+
+hipError_t launch_tree_whole(const GemmParams &p, const TreeFinishParams &f, int G, hipStream_t st) {
+    const bool wide = p.Mcap > 64;
+    if (f.K <= 4) {
+        if (wide) launch_whole<8, 4>(p, f, G, st); else launch_whole<4, 4>(p, f, G, st);
+    } else if (f.K <= 8) {
+        if (wide) launch_whole<8, 8>(p, f, G, st); else launch_whole<4, 8>(p, f, G, st);
+    } else {
+        if (wide) launch_whole<8, 16>(p, f, G, st); else launch_whole<4, 16>(p, f, G, st);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace specee
