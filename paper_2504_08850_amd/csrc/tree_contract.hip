@@ -32,14 +32,15 @@ namespace specee {
 
 constexpr int kTcThreads = 256;
 constexpr int kTcWaves = 4;
-constexpr int kTcKC = 64;             // k elements per stage
-constexpr int kTcRow = kTcKC + 8;     // halves per LDS row (144 bytes)
 constexpr int kTcFusedMax = kMergePerThread * kTcThreads;
 constexpr int kTcFeat = 32;           // feature slots per node in the matrix-core MLP (3K <= 32)
 
-// Predictor MLP for the 16 nodes of a wavefront on the matrix cores.
-// F: this wavefront's [16][kTcFeat] fp32 features in LDS (zero beyond 3K).  Returns the output
-// pre-activation (without b2) of node c = lane & 15 in every lane.
+// Predictor MLP for the 16 nodes of a wavefront on the matrix cores (needs K in {4, 8} and H a
+// multiple of 64).  F: this wavefront's [16][kTcFeat] fp32 features in LDS (zero beyond 3K).
+// Returns the output pre-activation (without b2) of node c = lane & 15 in every lane.
+// The loop over tiles of 16 hidden units is free of branches -- every load is in bounds and
+// unconditional, invalid k-slots are zeroed by selects -- so that it can be unrolled with the
+// weight loads of several tiles in flight.
 __device__ __forceinline__ float mlp_mfma_16(const float *F, const TreeFinishParams &f, int lane) {
     const int c = lane & 15, q = lane >> 4;
     const int K3 = 3 * f.K, H = f.H;
@@ -51,52 +52,52 @@ __device__ __forceinline__ float mlp_mfma_16(const float *F, const TreeFinishPar
         bhi[e] = h;
         blo[e] = (half_t)(v - (float)h);
     }
-    const bool any_feat = q * 8 < K3;  // slots of this lane group that hold features at all
+    const bool lo_ok = q * 8 < K3;       // first four k-slots of this lane group hold features
+    const bool hi_ok = q * 8 + 4 < K3;   // so do the last four
+    const half_t *wbase = f.W1 + (lo_ok ? q * 8 : 0);
+    const half_t *b1p = f.b1 ? f.b1 : f.w2;  // always a valid address; masked below
+    const float b1m = f.b1 ? 1.f : 0.f;
     float acc_u = 0.f;
-    const int htiles = (H + 15) >> 4;
-    for (int ht = 0; ht < htiles; ++ht) {
-        const int unit = ht * 16 + c;  // W1 row this lane supplies
-        half8 a = zero_half8();
-        if (unit < H && any_feat) {
-            const uint2 *src = reinterpret_cast<const uint2 *>(f.W1 + (size_t)unit * K3 + q * 8);
-            const half4 lo4 = __builtin_bit_cast(half4, src[0]);
+    const int htiles = H >> 4;  // a multiple of 4 (H is a multiple of 64)
+    for (int ht0 = 0; ht0 < htiles; ht0 += 4)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) a[e] = lo4[e];
-            if (q * 8 + 4 < K3) {
-                const half4 hi4 = __builtin_bit_cast(half4, src[1]);
+    for (int hi_ = 0; hi_ < 4; ++hi_) {
+        const int ht = ht0 + hi_;
+        const uint2 *src = reinterpret_cast<const uint2 *>(wbase + (size_t)(ht * 16 + c) * K3);
+        const uint2 raw0 = src[0];
+        const uint2 raw1 = src[hi_ok ? 1 : 0];
+        const half4 lo4 = __builtin_bit_cast(half4, raw0), hi4 = __builtin_bit_cast(half4, raw1);
+        half8 a;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) a[4 + e] = hi4[e];
-            }
+        for (int e = 0; e < 4; ++e) {
+            a[e] = lo_ok ? lo4[e] : (half_t)0.f;
+            a[4 + e] = hi_ok ? hi4[e] : (half_t)0.f;
         }
+        const int u0 = ht * 16 + 4 * q;  // this lane's four hidden units of the tile
+        const half4 w2v = __builtin_bit_cast(half4, *reinterpret_cast<const uint2 *>(f.w2 + u0));
+        const half4 b1v = __builtin_bit_cast(half4, *reinterpret_cast<const uint2 *>(b1p + u0));
         floatx4 dacc = {0.f, 0.f, 0.f, 0.f};
         dacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bhi, dacc, 0, 0, 0);
         dacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, blo, dacc, 0, 0, 0);
-        // lane holds pre-activations of units ht*16 + 4q + r for node c
-        const int u0 = ht * 16 + 4 * q;
-        half4 w2v = {(half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f}, b1v = w2v;
-        if (u0 + 3 < H) {
-            w2v = __builtin_bit_cast(half4, *reinterpret_cast<const uint2 *>(f.w2 + u0));
-            if (f.b1) b1v = __builtin_bit_cast(half4, *reinterpret_cast<const uint2 *>(f.b1 + u0));
-        } else {
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                if (u0 + r < H) {
-                    w2v[r] = f.w2[u0 + r];
-                    if (f.b1) b1v[r] = f.b1[u0 + r];
-                }
-        }
-#pragma unroll
-        for (int r = 0; r < 4; ++r) acc_u += (float)w2v[r] * fmaxf(dacc[r] + (float)b1v[r], 0.f);
+        for (int r = 0; r < 4; ++r) acc_u += (float)w2v[r] * fmaxf(dacc[r] + b1m * (float)b1v[r], 0.f);
     }
     acc_u += __shfl_xor(acc_u, 16, kWave);
     acc_u += __shfl_xor(acc_u, 32, kWave);
     return acc_u;
 }
 
-template <int MT, int MODE, bool FUSED, int PD, int KC>
+// KCH: k elements per stage (64 or 128).  A stage is one barrier and one LDS write -> read -> matrix
+// instruction dependency chain, so longer stages amortise that latency; 128 needs the row tile to
+// fit twice in LDS (MT = 4).  k-slots of lane group q within a stage: 64*(j/2) + 16*q + 8*(j%2).
+template <int MT, int MODE, bool FUSED, int PD, int KC, int KCH>
 __global__ __launch_bounds__(kTcThreads) void tree_contract_kernel(GemmParams p, TreeFinishParams f) {
+    constexpr int kTcKC = KCH;
+    constexpr int kTcRow = KCH + 8;          // halves per LDS row (pad keeps 16-byte reads spread over banks)
+    constexpr int JN = KCH / 32;             // matrix-instruction k-steps per stage
+    constexpr int VPR = KCH / 8;             // 16-byte vectors per row per stage
     constexpr int ROWS = 16 * MT;            // LM-head rows per workgroup
-    constexpr int APT = MT / 2;              // 16-byte A vectors per thread per stage (ROWS*8/256)
+    constexpr int APT = ROWS * VPR / kTcThreads;  // 16-byte A vectors per thread per stage
     constexpr int kALdsHalves = 2 * ROWS * kTcRow;
     __shared__ __attribute__((aligned(16))) half_t smem[kALdsHalves];
     __shared__ int32_t cols_lds[MODE == 3 ? kTcFusedMax : 1];
@@ -115,6 +116,7 @@ __global__ __launch_bounds__(kTcThreads) void tree_contract_kernel(GemmParams p,
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, q = lane >> 4;
+    auto koff = [&](int j) { return 64 * (j >> 1) + 16 * q + 8 * (j & 1); };
     const int NBn = (p.N + 63) / 64;
     const int g = blockIdx.z / NBn, nb = blockIdx.z - g * NBn;
     const int n0 = nb * 64;
@@ -128,20 +130,20 @@ __global__ __launch_bounds__(kTcThreads) void tree_contract_kernel(GemmParams p,
     const int node = n0 + wave * 16 + c;
     const bool node_ok = node < p.N;
     const half_t *hrow = p.hidden + ((size_t)g * p.N + (node_ok ? node : 0)) * d;
-    half8 h_buf[PD][2], g_buf[PD][2];
+    half8 h_buf[PD][JN], g_buf[PD][JN];
     // Loads are unconditional (addresses clamped into the row, results zeroed by a select when they
     // are consumed): a load under a branch makes the compiler drain every outstanding load at the
     // join, which would serialise the prefetch stages.
     auto issue_b = [&](int kc, int slot) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int ko = min(k_begin + kc * kTcKC + q * 16 + j * 8, d - 8);  // stages past the end re-read the tail
+        for (int j = 0; j < JN; ++j) {
+            const int ko = min(k_begin + kc * kTcKC + koff(j), d - 8);  // stages past the end re-read the tail
             g_buf[slot][j] = load_half8(p.gamma + ko);
             h_buf[slot][j] = load_half8(hrow + ko);
         }
     };
     auto b_valid = [&](int kc, int j) {
-        return node_ok && k_begin + kc * kTcKC + q * 16 + j * 8 < k_end;
+        return node_ok && k_begin + kc * kTcKC + koff(j) < k_end;
     };
 #pragma unroll
     for (int u = 0; u < PD; ++u) issue_b(u, u);
@@ -196,8 +198,8 @@ __global__ __launch_bounds__(kTcThreads) void tree_contract_kernel(GemmParams p,
 #pragma unroll
     for (int i = 0; i < APT; ++i) {
         const int vi = tid + kTcThreads * i;
-        a_r[i] = vi >> 3;
-        a_v[i] = vi & 7;
+        a_r[i] = vi / VPR;
+        a_v[i] = vi % VPR;
         const int m = m0 + a_r[i];
         arow_ok[i] = m < M;
         int row = 0;
@@ -241,9 +243,9 @@ __global__ __launch_bounds__(kTcThreads) void tree_contract_kernel(GemmParams p,
                 *reinterpret_cast<half8 *>(&a_lds[buf][a_r[i]][a_v[i] * 8]) =
                     a_valid(kc, i) ? a_buf[u][i] : zero_half8();
             // x = h*gamma split exactly into hi = round(h*gamma), lo = round(fma(h, gamma, -hi))
-            half8 bhi[2], blo[2];
+            half8 bhi[JN], blo[JN];
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
+            for (int j = 0; j < JN; ++j) {
                 const half8 hsel = b_valid(kc, j) ? h_buf[u][j] : zero_half8();
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -262,11 +264,11 @@ __global__ __launch_bounds__(kTcThreads) void tree_contract_kernel(GemmParams p,
             issue_a(kc + PD, u);
             issue_b(kc + PD, u);
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
+            for (int j = 0; j < JN; ++j) {
                 half8 a[MT];
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
-                    a[mt] = *reinterpret_cast<const half8 *>(&a_lds[buf][mt * 16 + c][q * 16 + j * 8]);
+                    a[mt] = *reinterpret_cast<const half8 *>(&a_lds[buf][mt * 16 + c][koff(j)]);
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
                     acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], bhi[j], acc[mt], 0, 0, 0);
@@ -306,7 +308,7 @@ __global__ __launch_bounds__(kTcThreads) void tree_contract_kernel(GemmParams p,
     __syncthreads();
 
     const int K = p.K, N = p.N;
-    const bool mfma_mlp = (K == 4 || K == 8) && KC <= 8;
+    const bool mfma_mlp = (K == 4 || K == 8) && KC <= 8 && (f.H & 63) == 0;
     if (mfma_mlp) {
         // lanes q == 0 build the features of node c; all lanes then feed the matrix cores
         float *F = feat_lds + wave * 16 * kTcFeat;
@@ -386,7 +388,7 @@ __global__ __launch_bounds__(kTcThreads) void tree_contract_kernel(GemmParams p,
     }
 }
 
-constexpr int kTcPD = 4;  // a 256-element d-slice is requested in one go; longer ranges keep 4 stages in flight
+// 256 elements of every row in flight per wavefront: four 64-element stages, or two of 128
 
 bool tree_gemm_can_fuse_merge(int n_ids) {
     return n_ids <= kTcFusedMax;
@@ -396,10 +398,10 @@ bool tree_gemm_can_fuse_merge(int n_ids) {
 hipError_t launch_tree_gemm(const GemmParams &p, int G, hipStream_t st) {
     dim3 grid((p.Mcap + 63) / 64, p.S, G * ((p.N + 63) / 64));
     if (p.ids)
-        hipLaunchKernelGGL((tree_contract_kernel<4, 0, true, kTcPD, 4>), grid, dim3(kTcThreads), 0, st, p,
+        hipLaunchKernelGGL((tree_contract_kernel<4, 0, true, 4, 4, 64>), grid, dim3(kTcThreads), 0, st, p,
                            TreeFinishParams{});
     else
-        hipLaunchKernelGGL((tree_contract_kernel<4, 0, false, kTcPD, 4>), grid, dim3(kTcThreads), 0, st, p,
+        hipLaunchKernelGGL((tree_contract_kernel<4, 0, false, 4, 4, 64>), grid, dim3(kTcThreads), 0, st, p,
                            TreeFinishParams{});
     return hipGetLastError();
 }
@@ -411,7 +413,12 @@ bool tree_whole_supported(int N, int K, int Mcap) {
 
 template <int MT, int KC>
 static void launch_whole(const GemmParams &p, const TreeFinishParams &f, int G, hipStream_t st) {
-    hipLaunchKernelGGL((tree_contract_kernel<MT, 3, true, kTcPD, KC>), dim3(1, 1, G), dim3(kTcThreads), 0, st, p, f);
+    if constexpr (MT == 4)
+        hipLaunchKernelGGL((tree_contract_kernel<MT, 3, true, 2, KC, 128>), dim3(1, 1, G), dim3(kTcThreads), 0, st, p,
+                           f);
+    else
+        hipLaunchKernelGGL((tree_contract_kernel<MT, 3, true, 4, KC, 64>), dim3(1, 1, G), dim3(kTcThreads), 0, st, p,
+                           f);
 }
 
 hipError_t launch_tree_whole(const GemmParams &p, const TreeFinishParams &f, int G, hipStream_t st) {
