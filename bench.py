@@ -294,7 +294,7 @@ def main():
         extra["c3_tree_N60"] = {"us_per_call": us, "mean_M": float(np.mean(Ms)), "algorithmic_bytes": byts,
                                 "achieved_GBps": byts / us / 1e3, "node_evals_per_s": c3.N / us * 1e6}
         # throughput: G different trees per launch (own hidden states, own id pools)
-        for G in (64, 256, 1024):
+        for G in (64, 256):
             tg = [synth.make("C3", seed=1000 + i, lm=lm_h) for i in range(G)]
             hh = up(np.stack([t["hidden"] for t in tg]))
             ii_h = np.stack([t["ids"] for t in tg])

@@ -30,71 +30,23 @@
 
 namespace specee {
 
-constexpr int kTcThreads = 256;
-constexpr int kTcWaves = 4;
-constexpr int kTcFusedMax = kMergePerThread * kTcThreads;
-constexpr int kTcFeat = 32;           // feature slots per node in the matrix-core MLP (3K <= 32)
-
-// Predictor MLP for the 16 nodes of a wavefront on the matrix cores (needs K in {4, 8} and H a
-// multiple of 64).  F: this wavefront's [16][kTcFeat] fp32 features in LDS (zero beyond 3K).
-// Returns the output pre-activation (without b2) of node c = lane & 15 in every lane.
-// The loop over tiles of 16 hidden units is free of branches -- every load is in bounds and
-// unconditional, invalid k-slots are zeroed by selects -- so that it can be unrolled with the
-// weight loads of several tiles in flight.
-__device__ __forceinline__ float mlp_mfma_16(const float *F, const TreeFinishParams &f, int lane) {
-    const int c = lane & 15, q = lane >> 4;
-    const int K3 = 3 * f.K, H = f.H;
-    half8 bhi, blo;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const float v = F[c * kTcFeat + q * 8 + e];
-        const half_t h = (half_t)v;
-        bhi[e] = h;
-        blo[e] = (half_t)(v - (float)h);
-    }
-    const bool lo_ok = q * 8 < K3;       // first four k-slots of this lane group hold features
-    const bool hi_ok = q * 8 + 4 < K3;   // so do the last four
-    const half_t *wbase = f.W1 + (lo_ok ? q * 8 : 0);
-    const half_t *b1p = f.b1 ? f.b1 : f.w2;  // always a valid address; masked below
-    const float b1m = f.b1 ? 1.f : 0.f;
-    float acc_u = 0.f;
-    const int htiles = H >> 4;  // a multiple of 4 (H is a multiple of 64)
-    for (int ht0 = 0; ht0 < htiles; ht0 += 4)
-#pragma unroll
-    for (int hi_ = 0; hi_ < 4; ++hi_) {
-        const int ht = ht0 + hi_;
-        const uint2 *src = reinterpret_cast<const uint2 *>(wbase + (size_t)(ht * 16 + c) * K3);
-        const uint2 raw0 = src[0];
-        const uint2 raw1 = src[hi_ok ? 1 : 0];
-        const half4 lo4 = __builtin_bit_cast(half4, raw0), hi4 = __builtin_bit_cast(half4, raw1);
-        half8 a;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            a[e] = lo_ok ? lo4[e] : (half_t)0.f;
-            a[4 + e] = hi_ok ? hi4[e] : (half_t)0.f;
-        }
-        const int u0 = ht * 16 + 4 * q;  // this lane's four hidden units of the tile
-        const half4 w2v = __builtin_bit_cast(half4, *reinterpret_cast<const uint2 *>(f.w2 + u0));
-        const half4 b1v = __builtin_bit_cast(half4, *reinterpret_cast<const uint2 *>(b1p + u0));
-        floatx4 dacc = {0.f, 0.f, 0.f, 0.f};
-        dacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bhi, dacc, 0, 0, 0);
-        dacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, blo, dacc, 0, 0, 0);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) acc_u += (float)w2v[r] * fmaxf(dacc[r] + b1m * (float)b1v[r], 0.f);
-    }
-    acc_u += __shfl_xor(acc_u, 16, kWave);
-    acc_u += __shfl_xor(acc_u, 32, kWave);
-    return acc_u;
-}
+constexpr int kTcFusedMax = kMergePerThread * 256;  // ids per tree when the merge is fused
 
 // KCH: k elements per stage (64 or 128).  A stage is one barrier and one LDS write -> read -> matrix
 // instruction dependency chain, so longer stages amortise that latency; 128 needs the row tile to
 // fit twice in LDS (MT = 4).  k-slots of lane group q within a stage: 64*(j/2) + 16*q + 8*(j%2).
-template <int MT, int MODE, bool FUSED, int PD, int KC, int KCH>
-__global__ __launch_bounds__(kTcThreads) void tree_contract_kernel(GemmParams p, TreeFinishParams f) {
+// THREADS: 256 (wavefront w owns node tile w) or 512 (wavefronts w and w+4 share node tile w and
+// split the k-steps of every stage between them; their accumulators are added through LDS at the
+// end).  Eight wavefronts halve the per-wavefront instruction stream of a stage, which is what bounds
+// a workgroup that streams a whole tree on its own.
+template <int MT, int MODE, bool FUSED, int PD, int KC, int KCH, int THREADS = 256>
+__global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, TreeFinishParams f) {
+    constexpr int kTcThreads = THREADS;
+    constexpr int kTcWaves = THREADS / 64;
+    constexpr int KH = THREADS / 256;        // wavefronts per node tile
     constexpr int kTcKC = KCH;
     constexpr int kTcRow = KCH + 8;          // halves per LDS row (pad keeps 16-byte reads spread over banks)
-    constexpr int JN = KCH / 32;             // matrix-instruction k-steps per stage
+    constexpr int JN = KCH / 32 / KH;        // matrix-instruction k-steps per stage and wavefront
     constexpr int VPR = KCH / 8;             // 16-byte vectors per row per stage
     constexpr int ROWS = 16 * MT;            // LM-head rows per workgroup
     constexpr int APT = ROWS * VPR / kTcThreads;  // 16-byte A vectors per thread per stage
@@ -102,7 +54,7 @@ __global__ __launch_bounds__(kTcThreads) void tree_contract_kernel(GemmParams p,
     __shared__ __attribute__((aligned(16))) half_t smem[kALdsHalves];
     __shared__ int32_t cols_lds[MODE == 3 ? kTcFusedMax : 1];
     __shared__ float prev_lds[MODE == 3 ? kTcFusedMax : 1];
-    __shared__ float feat_lds[MODE == 3 ? kTcWaves * 16 * kTcFeat : 1];
+    __shared__ float feat_lds[MODE == 3 ? 4 * 16 * kMlpFeat : 1];
     __shared__ float ssq_lds[MODE == 3 ? 64 : 1];
     __shared__ int32_t bad_lds[MODE == 3 ? 64 : 1];
     __shared__ int32_t exit_lds[MODE == 3 ? 64 : 1];
@@ -116,7 +68,11 @@ __global__ __launch_bounds__(kTcThreads) void tree_contract_kernel(GemmParams p,
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, q = lane >> 4;
-    auto koff = [&](int j) { return 64 * (j >> 1) + 16 * q + 8 * (j & 1); };
+    const int kh = (tid >> 6) >> 2, nt_w = (tid >> 6) & 3;  // k-share and node tile of this wavefront
+    auto koff = [&](int jj) {
+        const int j = kh * JN + jj;
+        return 64 * (j >> 1) + 16 * q + 8 * (j & 1);
+    };
     const int NBn = (p.N + 63) / 64;
     const int g = blockIdx.z / NBn, nb = blockIdx.z - g * NBn;
     const int n0 = nb * 64;
@@ -127,7 +83,7 @@ __global__ __launch_bounds__(kTcThreads) void tree_contract_kernel(GemmParams p,
     const int nchunks = (k_end - k_begin + kTcKC - 1) / kTcKC;
 
     // ---- B side: this lane's node and k-slots; requested before anything else
-    const int node = n0 + wave * 16 + c;
+    const int node = n0 + nt_w * 16 + c;
     const bool node_ok = node < p.N;
     const half_t *hrow = p.hidden + ((size_t)g * p.N + (node_ok ? node : 0)) * d;
     half8 h_buf[PD][JN], g_buf[PD][JN];
@@ -301,22 +257,50 @@ __global__ __launch_bounds__(kTcThreads) void tree_contract_kernel(GemmParams p,
     // ---- MODE 3: score the whole tree here
     __syncthreads();  // every wavefront is done with the row tiles: reuse them for the logits
     float *Zl = reinterpret_cast<float *>(smem);  // [64 nodes][ROWS]
+    if (KH == 2) {
+        // the two wavefronts of a node tile hold complementary k-shares: add them in a fixed order
+        float *tmp = Zl + 64 * ROWS;  // [4 tiles][64 lanes][MT quads]
+        static_assert(KH == 1 || sizeof(half_t) * kALdsHalves >= sizeof(float) * 2 * 64 * ROWS,
+                      "room for the second wavefront's accumulators");
+        if (kh == 1) {
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-        *reinterpret_cast<floatx4 *>(&Zl[(wave * 16 + c) * ROWS + mt * 16 + q * 4]) = acc[mt];
-    if (q == 0) ssq_lds[wave * 16 + c] = ssq;
+            for (int mt = 0; mt < MT; ++mt)
+                *reinterpret_cast<floatx4 *>(&tmp[((nt_w * 64 + lane) * MT + mt) * 4]) = acc[mt];
+            if (q == 0) ssq_lds[nt_w * 16 + c] = ssq;
+        }
+        __syncthreads();
+        if (kh == 0) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                acc[mt] += *reinterpret_cast<const floatx4 *>(&tmp[((nt_w * 64 + lane) * MT + mt) * 4]);
+            ssq += ssq_lds[nt_w * 16 + c];
+        }
+        __syncthreads();
+    }
+    if (kh == 0) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+            *reinterpret_cast<floatx4 *>(&Zl[(nt_w * 16 + c) * ROWS + mt * 16 + q * 4]) = acc[mt];
+        if (q == 0) ssq_lds[nt_w * 16 + c] = ssq;
+    }
     __syncthreads();
 
     const int K = p.K, N = p.N;
-    const bool mfma_mlp = (K == 4 || K == 8) && KC <= 8 && (f.H & 63) == 0;
+    const bool mfma_mlp = KC <= 8 && mlp_mfma_ok(K, f.H);
     if (mfma_mlp) {
+        // the predictor is copied into the part of the row-tile buffers that the logits leave free,
+        // when it fits; the copy is published by the barrier after the features are written
+        TreeFinishParams fl = f;
+        constexpr size_t kFree = sizeof(half_t) * kALdsHalves - sizeof(float) * 64 * ROWS;
+        if ((size_t)mlp_lds_halves(K, f.H) * sizeof(half_t) <= kFree)
+            fl = stage_mlp_to_lds(reinterpret_cast<half_t *>(Zl + 64 * ROWS), f, tid, kTcThreads);
         // lanes q == 0 build the features of node c; all lanes then feed the matrix cores
-        float *F = feat_lds + wave * 16 * kTcFeat;
-        const int n = wave * 16 + c;  // node within the tree (N <= 64: n0 == 0)
+        float *F = feat_lds + nt_w * 16 * kMlpFeat;
+        const int n = nt_w * 16 + c;  // node within the tree (N <= 64: n0 == 0)
         const size_t gn = (size_t)g * N + n;
         bool poisoned = false;
         float z[KC], pr[KC];
-        if (q == 0) {
+        if (q == 0 && kh == 0) {
             const float r = 1.0f / sqrtf(ssq_lds[n] / (float)d + p.eps);
             const bool bad = overflow || (n < N && bad_lds[n] != 0);
 #pragma unroll
@@ -335,15 +319,15 @@ __global__ __launch_bounds__(kTcThreads) void tree_contract_kernel(GemmParams p,
             for (int k = 0; k < KC; ++k)
                 if (k < K) {
                     const float pv = n < N ? prev_lds[n * K + k] : 0.f;
-                    F[c * kTcFeat + k] = z[k];
-                    F[c * kTcFeat + K + k] = pr[k];
-                    F[c * kTcFeat + 2 * K + k] = pr[k] - pv;
+                    F[c * kMlpFeat + k] = z[k];
+                    F[c * kMlpFeat + K + k] = pr[k];
+                    F[c * kMlpFeat + 2 * K + k] = pr[k] - pv;
                 }
-            for (int t = 3 * K; t < kTcFeat; ++t) F[c * kTcFeat + t] = 0.f;
+            for (int t = 3 * K; t < kMlpFeat; ++t) F[c * kMlpFeat + t] = 0.f;
         }
         __syncthreads();
-        const float u = mlp_mfma_16(F, f, lane);
-        if (q == 0 && n < N) {
+        const float u = kh == 0 ? mlp_mfma_16(F, fl, lane) : 0.f;
+        if (q == 0 && kh == 0 && n < N) {
             const float b2 = f.b2 ? (float)f.b2[0] : 0.f;
             float sc = sigmoidf(b2 + u);
             if (poisoned) sc = quiet_nan();
@@ -398,10 +382,10 @@ bool tree_gemm_can_fuse_merge(int n_ids) {
 hipError_t launch_tree_gemm(const GemmParams &p, int G, hipStream_t st) {
     dim3 grid((p.Mcap + 63) / 64, p.S, G * ((p.N + 63) / 64));
     if (p.ids)
-        hipLaunchKernelGGL((tree_contract_kernel<4, 0, true, 4, 4, 64>), grid, dim3(kTcThreads), 0, st, p,
+        hipLaunchKernelGGL((tree_contract_kernel<4, 0, true, 4, 4, 64>), grid, dim3(256), 0, st, p,
                            TreeFinishParams{});
     else
-        hipLaunchKernelGGL((tree_contract_kernel<4, 0, false, 4, 4, 64>), grid, dim3(kTcThreads), 0, st, p,
+        hipLaunchKernelGGL((tree_contract_kernel<4, 0, false, 4, 4, 64>), grid, dim3(256), 0, st, p,
                            TreeFinishParams{});
     return hipGetLastError();
 }
@@ -414,10 +398,10 @@ bool tree_whole_supported(int N, int K, int Mcap) {
 template <int MT, int KC>
 static void launch_whole(const GemmParams &p, const TreeFinishParams &f, int G, hipStream_t st) {
     if constexpr (MT == 4)
-        hipLaunchKernelGGL((tree_contract_kernel<MT, 3, true, 2, KC, 128>), dim3(1, 1, G), dim3(kTcThreads), 0, st, p,
+        hipLaunchKernelGGL((tree_contract_kernel<MT, 3, true, 2, KC, 128, 512>), dim3(1, 1, G), dim3(512), 0, st, p,
                            f);
     else
-        hipLaunchKernelGGL((tree_contract_kernel<MT, 3, true, 4, KC, 64>), dim3(1, 1, G), dim3(kTcThreads), 0, st, p,
+        hipLaunchKernelGGL((tree_contract_kernel<MT, 3, true, 4, KC, 64, 256>), dim3(1, 1, G), dim3(256), 0, st, p,
                            f);
 }
 

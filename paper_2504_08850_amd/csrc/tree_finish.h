@@ -11,6 +11,12 @@
 namespace specee {
 
 constexpr int kFinishUnits = 8;  // hidden units per lane held in registers (H <= 512)
+constexpr int kMlpFeat = 32;     // feature slots per node in the matrix-core MLP (3K <= 32)
+
+// Shapes the matrix-core MLP handles; everything else takes the vector-ALU path.
+__host__ __device__ inline bool mlp_mfma_ok(int K, int H) {
+    return (K == 4 || K == 8) && (H & 63) == 0;
+}
 
 template <int KC>
 struct FinishRows {
@@ -81,6 +87,84 @@ __device__ __forceinline__ int finish_score_node(FinishRows<KC> &fr, const TreeF
         p.probs[gn * K + lane] = pl;
     }
     return ex;
+}
+
+// Predictor MLP for the 16 nodes of a wavefront on the matrix cores (needs K in {4, 8} and H a
+// multiple of 64).  F: this wavefront's [16][kMlpFeat] fp32 features in LDS (zero beyond 3K).
+// Returns the output pre-activation (without b2) of node c = lane & 15 in every lane.
+// The loop over tiles of 16 hidden units is free of branches -- every load is in bounds and
+// unconditional, invalid k-slots are zeroed by selects -- so that it can be unrolled with the
+// weight loads of several tiles in flight.
+__device__ __forceinline__ float mlp_mfma_16(const float *F, const TreeFinishParams &f, int lane) {
+    const int c = lane & 15, q = lane >> 4;
+    const int K3 = 3 * f.K, H = f.H;
+    half8 bhi, blo;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float v = F[c * kMlpFeat + q * 8 + e];
+        const half_t h = (half_t)v;
+        bhi[e] = h;
+        blo[e] = (half_t)(v - (float)h);
+    }
+    const bool lo_ok = q * 8 < K3;       // first four k-slots of this lane group hold features
+    const bool hi_ok = q * 8 + 4 < K3;   // so do the last four
+    const half_t *wbase = f.W1 + (lo_ok ? q * 8 : 0);
+    const half_t *b1p = f.b1 ? f.b1 : f.w2;  // always a valid address; masked below
+    const float b1m = f.b1 ? 1.f : 0.f;
+    float acc_u = 0.f;
+    const int htiles = H >> 4;  // a multiple of 4 (H is a multiple of 64)
+    for (int ht0 = 0; ht0 < htiles; ht0 += 4)
+#pragma unroll
+    for (int hi_ = 0; hi_ < 4; ++hi_) {
+        const int ht = ht0 + hi_;
+        const uint2 *src = reinterpret_cast<const uint2 *>(wbase + (size_t)(ht * 16 + c) * K3);
+        const uint2 raw0 = src[0];
+        const uint2 raw1 = src[hi_ok ? 1 : 0];
+        const half4 lo4 = __builtin_bit_cast(half4, raw0), hi4 = __builtin_bit_cast(half4, raw1);
+        half8 a;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            a[e] = lo_ok ? lo4[e] : (half_t)0.f;
+            a[4 + e] = hi_ok ? hi4[e] : (half_t)0.f;
+        }
+        const int u0 = ht * 16 + 4 * q;  // this lane's four hidden units of the tile
+        const half4 w2v = __builtin_bit_cast(half4, *reinterpret_cast<const uint2 *>(f.w2 + u0));
+        const half4 b1v = __builtin_bit_cast(half4, *reinterpret_cast<const uint2 *>(b1p + u0));
+        floatx4 dacc = {0.f, 0.f, 0.f, 0.f};
+        dacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bhi, dacc, 0, 0, 0);
+        dacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, blo, dacc, 0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc_u += (float)w2v[r] * fmaxf(dacc[r] + b1m * (float)b1v[r], 0.f);
+    }
+    acc_u += __shfl_xor(acc_u, 16, kWave);
+    acc_u += __shfl_xor(acc_u, 32, kWave);
+    return acc_u;
+}
+
+// Copy the predictor (W1 [H][3K] | w2 [H] | b1 [H], b1 zero-filled when absent) into LDS with
+// 16-byte vectors, and return parameters that point at the copy.  The matrix-core MLP walks the
+// weights tile by tile; from global memory that is a chain of cache-latency round trips, from LDS it
+// is not.  Needs mlp_mfma_ok(K, H); dst must be 16-byte aligned with room for mlp_lds_halves(K, H).
+__host__ __device__ inline int mlp_lds_halves(int K, int H) {
+    return H * 3 * K + 2 * H;
+}
+__device__ __forceinline__ TreeFinishParams stage_mlp_to_lds(half_t *dst, const TreeFinishParams &f, int tid,
+                                                            int threads) {
+    const int nW = f.H * 3 * f.K;
+    half8 *d8 = reinterpret_cast<half8 *>(dst);
+    const half8 *w8 = reinterpret_cast<const half8 *>(f.W1);
+    for (int i = tid; i < nW / 8; i += threads) d8[i] = w8[i];
+    const half8 *v8 = reinterpret_cast<const half8 *>(f.w2);
+    const half8 *b8 = reinterpret_cast<const half8 *>(f.b1);
+    for (int i = tid; i < f.H / 8; i += threads) {
+        d8[nW / 8 + i] = v8[i];
+        d8[nW / 8 + f.H / 8 + i] = f.b1 ? b8[i] : zero_half8();
+    }
+    TreeFinishParams g = f;
+    g.W1 = dst;
+    g.w2 = dst + nW;
+    g.b1 = dst + nW + f.H;
+    return g;
 }
 
 // Path rule from exit flags in LDS (paper Sec. 6.2): a token path exits only if every token on it

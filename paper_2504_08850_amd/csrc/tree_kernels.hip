@@ -77,8 +77,17 @@ __global__ __launch_bounds__(WHOLE ? 512 : 256) void tree_finish_kernel(TreeFini
     float *prevl = zsum + (size_t)N * (K + 1);
     int32_t *exit_lds = reinterpret_cast<int32_t *>(prevl + (size_t)N * K);
 
+    const bool use_mfma = WHOLE && KC <= 8 && mlp_mfma_ok(K, p.H);
     FinishRows<KC> fr;
-    finish_load_rows<KC>(fr, p, lane);
+    TreeFinishParams pl = p;  // predictor pointers redirected to the LDS copy when the matrix cores are used
+    if (use_mfma) {
+        // [zsum | prev | exit | features] then the predictor copy, 16-byte aligned
+        size_t off = ((size_t)N * (K + 1) + (size_t)N * K + N + 8 * 16 * kMlpFeat) * sizeof(float);
+        off = (off + 15) & ~(size_t)15;
+        pl = stage_mlp_to_lds(reinterpret_cast<half_t *>(reinterpret_cast<char *>(finish_lds) + off), p, tid, THREADS);
+    } else {
+        finish_load_rows<KC>(fr, p, lane);
+    }
     const int M = p.M_out[g];
     const size_t pstride = (size_t)p.Npad * p.Mpad;
 
@@ -103,6 +112,57 @@ __global__ __launch_bounds__(WHOLE ? 512 : 256) void tree_finish_kernel(TreeFini
         __syncthreads();
     }
 
+    if (use_mfma) {
+        // sixteen nodes per wavefront and round: lanes q == 0 build the features of node c, then the
+        // whole wavefront evaluates the MLP on the matrix cores
+        float *feat = reinterpret_cast<float *>(exit_lds + N);  // [kWaves][16][kMlpFeat]
+        float *F = feat + wave * 16 * kMlpFeat;
+        const int c = lane & 15, q = lane >> 4;
+        const int ntiles = (N + 15) >> 4;
+        const float b2 = p.b2 ? (float)p.b2[0] : 0.f;
+        for (int t0 = 0; t0 < ntiles; t0 += kWaves) {  // same trip count for every wavefront
+            const int n = (t0 + wave) * 16 + c;
+            const bool live = n < N;
+            const size_t gn = (size_t)g * N + (live ? n : 0);
+            float z[KC], pr[KC];
+            if (q == 0) {
+                const float r = live ? 1.0f / sqrtf(zsum[n * (K + 1) + K] / (float)p.d + p.eps) : 0.f;
+#pragma unroll
+                for (int k = 0; k < KC; ++k) z[k] = (k < K && live) ? zsum[n * (K + 1) + k] * r : 0.f;
+                local_softmax<KC>(z, K, pr);
+#pragma unroll
+                for (int k = 0; k < KC; ++k)
+                    if (k < K) {
+                        const float pv = live ? prevl[n * K + k] : 0.f;
+                        F[c * kMlpFeat + k] = z[k];
+                        F[c * kMlpFeat + K + k] = pr[k];
+                        F[c * kMlpFeat + 2 * K + k] = pr[k] - pv;
+                    }
+                for (int t = 3 * K; t < kMlpFeat; ++t) F[c * kMlpFeat + t] = 0.f;
+            }
+            __syncthreads();
+            const float u = mlp_mfma_16(F, pl, lane);
+            if (q == 0 && live) {
+                bool poisoned = false;
+#pragma unroll
+                for (int k = 0; k < KC; ++k)
+                    if (k < K && z[k] != z[k]) poisoned = true;
+                float sc = sigmoidf(b2 + u);
+                if (poisoned) sc = quiet_nan();
+                const int ex = (sc > p.threshold) ? 1 : 0;
+                p.scores[gn] = sc;
+                p.exit_flags[gn] = ex;
+                exit_lds[n] = ex;
+#pragma unroll
+                for (int k = 0; k < KC; ++k)
+                    if (k < K) {
+                        p.logits[gn * K + k] = z[k];
+                        p.probs[gn * K + k] = pr[k];
+                    }
+            }
+            __syncthreads();  // F is rewritten in the next round
+        }
+    } else
     for (int n = n_begin + wave; n < n_end; n += kWaves) {
         const size_t gn = (size_t)g * N + n;
         float z[KC], prev[KC];
@@ -178,9 +238,15 @@ hipError_t launch_merge(const int32_t *ids, int n, int G, int Mcap, int32_t *mer
 
 template <int KC>
 static hipError_t launch_finish_kc(const TreeFinishParams &p, int G, hipStream_t st) {
-    // enough trees to fill the GPU with one workgroup each: predictor weights are fetched once per tree,
-    // the path rule needs no second kernel
-    const size_t whole_lds = ((size_t)p.N * (p.K + 1) + (size_t)p.N * p.K + p.N) * sizeof(float);
+    // Enough trees to fill the GPU with one workgroup each: every partial sum of a tree is gathered in
+    // one sweep, the predictor runs on the matrix cores (or, for other shapes, with its rows held in
+    // registers across nodes) and the path rule needs no second kernel.  With few trees the serial
+    // instruction stream of one workgroup per tree is the bottleneck (measured: ~17 us for a 60-node
+    // tree against ~5 us when every node has its own wavefront), so those take the shape below.
+    const bool mfma = KC <= 8 && mlp_mfma_ok(p.K, p.H);
+    size_t whole_lds = ((size_t)p.N * (p.K + 1) + (size_t)p.N * p.K + p.N) * sizeof(float) +
+                       8 * 16 * kMlpFeat * sizeof(float);
+    if (mfma) whole_lds = ((whole_lds + 15) & ~(size_t)15) + (size_t)mlp_lds_halves(p.K, p.H) * sizeof(half_t);
     if (G >= 32 && whole_lds <= 60 * 1024) {
         hipLaunchKernelGGL((tree_finish_kernel<KC, true>), dim3(1, G), dim3(512), whole_lds, st, p, p.N);
         return hipGetLastError();
