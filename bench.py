@@ -377,7 +377,7 @@ def main():
                                         "algorithmic_bytes": byts, "achieved_GBps": byts / us_tree / 1e3}
         full = torch.empty((c5.N, c5.V), device=dev)
         g = capture(lambda: sp.lm_head_gemv(dts[0][0], g5, lm5, out=full))
-        us64 = ev_time(g.replay, 10, 2) * 1e3
+        us64 = ev_time(g.replay, 30, 5) * 1e3
         b64 = c5.V * c5.d * 2 + c5.N * c5.d * 2 + c5.N * c5.V * 4
         extra["lm_head_gemv_128256x8192_N64"] = {"us_per_call": us64, "algorithmic_bytes": b64,
                                                  "achieved_GBps": b64 / us64 / 1e3,
@@ -386,7 +386,7 @@ def main():
                                                  "traffic": MEASURED_TRAFFIC.get("lm_head_gemm_c5")}
         one = torch.empty((1, c5.V), device=dev)
         g = capture(lambda: sp.lm_head_gemv(dts[0][0][:1], g5, lm5, out=one))
-        us1 = ev_time(g.replay, 10, 2) * 1e3
+        us1 = ev_time(g.replay, 30, 5) * 1e3
         b1 = c5.V * c5.d * 2 + c5.d * 4 + c5.V * 4
         extra["lm_head_gemv_128256x8192_N1"] = {"us_per_call": us1, "algorithmic_bytes": b1,
                                                 "achieved_GBps": b1 / us1 / 1e3,

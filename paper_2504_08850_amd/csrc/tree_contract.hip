@@ -76,7 +76,10 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     const int NBn = (p.N + 63) / 64;
     const int g = blockIdx.z / NBn, nb = blockIdx.z - g * NBn;
     const int n0 = nb * 64;
-    const int s = blockIdx.y;
+    // d-slice in blockIdx.x, row group in blockIdx.y: workgroups are dealt to the eight XCDs round-robin
+    // by linear id, so the row groups of one d-slice (which re-read the same hidden-state slice) land on
+    // the same XCD and share its L2 when the number of slices is a multiple of eight
+    const int s = blockIdx.x;
     const int d = p.d;
     const int k_begin = s * p.dslice;
     const int k_end = min(d, k_begin + p.dslice);
@@ -93,7 +96,7 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     auto issue_b = [&](int kc, int slot) {
 #pragma unroll
         for (int j = 0; j < JN; ++j) {
-            const int ko = min(k_begin + kc * kTcKC + koff(j), d - 8);  // stages past the end re-read the tail
+            const int ko = min(k_begin + kc * kTcKC + koff(j), k_end - 8);  // stages past the end re-read the slice's tail
             g_buf[slot][j] = load_half8(p.gamma + ko);
             h_buf[slot][j] = load_half8(hrow + ko);
         }
@@ -144,7 +147,7 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     }
     const bool overflow = M > p.Mcap;
     if (overflow) M = p.Mcap;
-    const int m0 = blockIdx.x * ROWS;
+    const int m0 = blockIdx.y * ROWS;
     if (MODE != 3 && m0 >= M) return;  // uniform over the workgroup
 
     // ---- A side: this thread copies vectors (row, v) of the row tile: index = tid + 256*i
@@ -170,7 +173,7 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     auto issue_a = [&](int kc, int slot) {
 #pragma unroll
         for (int i = 0; i < APT; ++i) {
-            const int ko = min(k_begin + kc * kTcKC + a_v[i] * 8, d - 8);
+            const int ko = min(k_begin + kc * kTcKC + a_v[i] * 8, k_end - 8);
             a_buf[slot][i] = load_half8(arow[i] + ko);
         }
     };
@@ -240,7 +243,7 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     ssq += __shfl_xor(ssq, 32, kWave);
 
     if (MODE == 0) {
-        if (blockIdx.x == 0 && q == 0 && node_ok) p.ssq_part[((size_t)g * p.S + s) * p.Npad + node] = ssq;
+        if (blockIdx.y == 0 && q == 0 && node_ok) p.ssq_part[((size_t)g * p.S + s) * p.Npad + node] = ssq;
         if (node_ok) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
@@ -378,9 +381,9 @@ bool tree_gemm_can_fuse_merge(int n_ids) {
     return n_ids <= kTcFusedMax;
 }
 
-// d-slice partial sums: grid (row groups of 64, d-slices, trees x node blocks)
+// d-slice partial sums: grid (d-slices, row groups of 64, trees x node blocks)
 hipError_t launch_tree_gemm(const GemmParams &p, int G, hipStream_t st) {
-    dim3 grid((p.Mcap + 63) / 64, p.S, G * ((p.N + 63) / 64));
+    dim3 grid(p.S, (p.Mcap + 63) / 64, G * ((p.N + 63) / 64));
     if (p.ids)
         hipLaunchKernelGGL((tree_contract_kernel<4, 0, true, 4, 4, 64>), grid, dim3(256), 0, st, p,
                            TreeFinishParams{});
