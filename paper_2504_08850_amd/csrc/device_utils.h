@@ -43,6 +43,23 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+// Sum over the 64 lanes with DPP only (no LDS crossbar): after the four in-row steps every lane
+// of a 16-lane row holds its row's sum; row_bcast15 adds row 0 into row 1 and row 2 into row 3,
+// row_bcast31 adds rows 0+1 into rows 2 and 3.  The total is valid in lanes 48..63 ONLY.
+constexpr int kDppRowBcast15 = 0x142;
+constexpr int kDppRowBcast31 = 0x143;
+__device__ __forceinline__ float wave_sum_to_last_row(float v) {
+    v += dpp_f32<kDppXor1>(v);
+    v += dpp_f32<kDppXor2>(v);
+    v += dpp_f32<kDppHalfMirror>(v);
+    v += dpp_f32<kDppMirror>(v);
+    int i = __builtin_bit_cast(int, v);
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, i, kDppRowBcast15, 0xA, 0xF, false));
+    i = __builtin_bit_cast(int, v);
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, i, kDppRowBcast31, 0xC, 0xF, false));
+    return v;
+}
+
 template <int CTRL>
 __device__ __forceinline__ void dpp_argmax_step(float &v, int &i) {
     float ov = dpp_f32<CTRL>(v);

@@ -24,7 +24,10 @@ constexpr int kPredictWaves = kPredictThreads / kWave;
 // thread per row (d/8 <= VPT * 512 * tiles).  SWEEP: the previous layer's local
 // probabilities are recomputed from that layer's hidden state instead of read,
 // which makes every (layer, token) workgroup independent.
-template <int KC, int VPT, bool SWEEP>
+// EXACT: K == KC is known at compile time (the common K = 4 and K = 8): every `k < K` predicate and
+// the generic MLP path fold away, which shortens the serial instruction stream of this latency-bound
+// kernel.
+template <int KC, int VPT, bool SWEEP, bool EXACT>
 __global__ __launch_bounds__(kPredictThreads) void predict_kernel(PredictParams p) {
     __shared__ float red[kPredictWaves][2 * KC + 2];
     __shared__ float red_u[kPredictWaves];
@@ -34,7 +37,7 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(PredictParams 
     const int wave = tid >> 6;
     const int b = blockIdx.x;
     const int l = blockIdx.y;
-    const int K = p.K, H = p.H, d = p.d;
+    const int K = EXACT ? KC : p.K, H = p.H, d = p.d;
     const int nv = d >> 3;
     const size_t tok = (size_t)l * p.B + b;
 
@@ -154,15 +157,15 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(PredictParams 
     }
 
     // ---- wavefront reduction, then fixed-order combination of the eight wave partials
-    ssq = wave_sum(ssq);
+    ssq = wave_sum_to_last_row(ssq);
 #pragma unroll
-    for (int k = 0; k < KC; ++k) acc[k] = wave_sum(acc[k]);
+    for (int k = 0; k < KC; ++k) acc[k] = wave_sum_to_last_row(acc[k]);
     if (SWEEP) {
-        ssq_p = wave_sum(ssq_p);
+        ssq_p = wave_sum_to_last_row(ssq_p);
 #pragma unroll
-        for (int k = 0; k < KC; ++k) acc_p[k] = wave_sum(acc_p[k]);
+        for (int k = 0; k < KC; ++k) acc_p[k] = wave_sum_to_last_row(acc_p[k]);
     }
-    if (lane == 0) {
+    if (lane == kWave - 1) {
         red[wave][0] = ssq;
         red[wave][1] = ssq_p;
 #pragma unroll
@@ -205,8 +208,8 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(PredictParams 
 
     // ---- MLP: thread j owns hidden unit j (+512, ...); f = [z | p | p - prev]
     float part = mlp_partial<KC, kPredictThreads>(row0, W1, b1, w2, K, H, tid, z, pr, prev);
-    part = wave_sum(part);
-    if (lane == 0) red_u[wave] = part;
+    part = wave_sum_to_last_row(part);
+    if (lane == kWave - 1) red_u[wave] = part;
     __syncthreads();
 
     if (tid == 0) {
@@ -238,25 +241,27 @@ __global__ void first_exit_kernel(const int32_t *exit_flags, int L, int B, int32
     first_exit[b] = f;
 }
 
-template <int KC, bool SWEEP>
+template <int KC, bool SWEEP, bool EXACT>
 static hipError_t launch_vpt(const PredictParams &p, hipStream_t s) {
     dim3 grid(p.B, p.L), block(kPredictThreads);
     const int nv = p.d >> 3;
     const int vpt = (nv + kPredictThreads - 1) / kPredictThreads;
     if (vpt <= 1)
-        hipLaunchKernelGGL((predict_kernel<KC, 1, SWEEP>), grid, block, 0, s, p);
+        hipLaunchKernelGGL((predict_kernel<KC, 1, SWEEP, EXACT>), grid, block, 0, s, p);
     else if (vpt <= 2 || KC > 8)
-        hipLaunchKernelGGL((predict_kernel<KC, 2, SWEEP>), grid, block, 0, s, p);
+        hipLaunchKernelGGL((predict_kernel<KC, 2, SWEEP, EXACT>), grid, block, 0, s, p);
     else if constexpr (KC <= 8)
-        hipLaunchKernelGGL((predict_kernel<KC, 4, SWEEP>), grid, block, 0, s, p);
+        hipLaunchKernelGGL((predict_kernel<KC, 4, SWEEP, EXACT>), grid, block, 0, s, p);
     return hipGetLastError();
 }
 
 template <bool SWEEP>
 static hipError_t launch_kc(const PredictParams &p, hipStream_t s) {
-    if (p.K <= 4) return launch_vpt<4, SWEEP>(p, s);
-    if (p.K <= 8) return launch_vpt<8, SWEEP>(p, s);
-    return launch_vpt<16, SWEEP>(p, s);
+    if (p.K == 4) return launch_vpt<4, SWEEP, true>(p, s);
+    if (p.K == 8) return launch_vpt<8, SWEEP, true>(p, s);
+    if (p.K < 4) return launch_vpt<4, SWEEP, false>(p, s);
+    if (p.K < 8) return launch_vpt<8, SWEEP, false>(p, s);
+    return launch_vpt<16, SWEEP, false>(p, s);
 }
 
 hipError_t launch_predict(const PredictParams &p, hipStream_t s) {

@@ -19,10 +19,10 @@ __device__ __forceinline__ void local_softmax(const float (&z)[KC], int K, float
     float s = 0.f;
 #pragma unroll
     for (int k = 0; k < KC; ++k) {
-        p[k] = (k < K) ? expf(z[k] - m) : 0.f;
+        p[k] = (k < K) ? __expf(z[k] - m) : 0.f;
         s += p[k];
     }
-    float inv = 1.0f / s;
+    float inv = __frcp_rn(s);
 #pragma unroll
     for (int k = 0; k < KC; ++k) p[k] *= inv;
     bool bad = false;  // fmaxf drops NaN, so propagate it by hand
@@ -111,7 +111,7 @@ __device__ __forceinline__ float mlp_partial(const MlpRow<KC> &first, const half
 }
 
 __device__ __forceinline__ float sigmoidf(float u) {
-    return 1.0f / (1.0f + expf(-u));
+    return __frcp_rn(1.0f + __expf(-u));
 }
 
 }  // namespace specee

@@ -126,6 +126,53 @@ def test_tree_shapes(sp, oracle, d, V, K, H, N, Mcap):
     check_tree(run_tree(sp, t, dev(t["lm_head"]), Mcap), ref, 0.5, f"tree d={d} K={K} N={N}")
 
 
+def stack_trees(ts):
+    stack = lambda k: np.stack([t[k] for t in ts])
+    return dict(ts[0], hidden=stack("hidden"), ids=stack("ids"), prev_probs=stack("prev_probs"),
+                parent=stack("parent"))
+
+
+def test_tree_largest_supported_tree(sp, oracle):
+    """N*K = 4096 ids (the documented limit): the stand-alone merge kernel at full size, eight node blocks,
+    dozens of row groups, and the per-node finish (the per-tree finish would not fit in LDS)."""
+    d, V, K, H, N = 64, 20000, 8, 64, 512
+    t = make_tree(77, d, V, K, H, N)
+    M = len(np.unique(t["ids"]))
+    assert N * K == 4096 and M > 3000
+    ref = ref_tree(oracle, t, 4096)
+    got = run_tree(sp, t, dev(t["lm_head"]), 4096)
+    check_tree(got, ref, 0.5, "4096-id tree")
+    # a few of these in one call: the per-tree finish shape is skipped because its LDS need exceeds the limit
+    tb = stack_trees([t, make_tree(78, d, V, K, H, N), make_tree(79, d, V, K, H, N)])
+    for k in ("gamma", "lm_head", "W1", "w2", "b1", "b2"):
+        tb[k] = t[k]
+    ref = ref_tree(oracle, tb, 4096)
+    got = run_tree(sp, tb, dev(tb["lm_head"]), 4096)
+    check_tree(got, ref, 0.5, "three 4096-id trees")
+    with pytest.raises(sp.SpeceeError):            # one node more than the limit
+        big = make_tree(80, d, V, K, H, N + 1)
+        run_tree(sp, big, dev(big["lm_head"]), 4096)
+
+
+def test_tree_many_mid_size_trees_split_path(sp, oracle):
+    """Forty trees with more than 64 nodes each: too wide for one workgroup per tree, so the d-split
+    contraction runs with the stand-alone merge kernel and the per-tree finish (matrix-core MLP)."""
+    d, V, K, H, N, Mcap = 256, 3000, 4, 512, 80, 200
+    ts = []
+    for gidx in range(40):
+        t = make_tree(500 + gidx, d, V, K, H, N)
+        pool = np.random.default_rng(gidx).permutation(V)[:Mcap]
+        t["ids"] = pool[np.random.default_rng(900 + gidx).integers(0, Mcap, size=(N, K))].astype(np.int32)
+        ts.append(t)
+    for t in ts[1:]:
+        for k in ("gamma", "lm_head", "W1", "w2", "b1", "b2"):
+            t[k] = ts[0][k]
+    tb = stack_trees(ts)
+    ref = ref_tree(oracle, tb, Mcap)
+    got = run_tree(sp, tb, dev(tb["lm_head"]), Mcap)
+    check_tree(got, ref, 0.5, "40 trees of 80 nodes")
+
+
 def test_tree_batch_of_independent_trees(sp, oracle):
     ts = [synth.make("T4", seed=s) for s in range(3)]
     c = ts[0]["cfg"]
@@ -135,12 +182,6 @@ def test_tree_batch_of_independent_trees(sp, oracle):
     got = run_tree(sp, tb, dev(tb["lm_head"]), c.Mcap)
     check_tree(got, ref, c.threshold, "batched trees")
     assert len(set(ref["M"].tolist())) > 1       # trees really differ in merged size
-
-
-def stack_trees(ts):
-    stack = lambda k: np.stack([t[k] for t in ts])
-    return dict(ts[0], hidden=stack("hidden"), ids=stack("ids"), prev_probs=stack("prev_probs"),
-                parent=stack("parent"))
 
 
 @pytest.mark.parametrize("name,G,bias", [("T3", 20, True), ("T3", 16, False)])
