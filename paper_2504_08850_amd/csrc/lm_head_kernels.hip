@@ -101,9 +101,9 @@ __global__ __launch_bounds__(kGemvThreads) void lm_head_gemv_kernel(int d, int V
                 acc1 += in ? t1 : 0.f;
             }
         }
-        acc0 = wave_sum(acc0);
-        acc1 = wave_sum(acc1);
         if (ARGMAX) {
+            acc0 = wave_sum(acc0);
+            acc1 = wave_sum(acc1);
             float v0 = acc0 * r, v1 = acc1 * r;
             if (v0 > bv) {
                 bv = v0;
@@ -113,9 +113,13 @@ __global__ __launch_bounds__(kGemvThreads) void lm_head_gemv_kernel(int d, int V
                 bv = v1;
                 bi = row + 1;
             }
-        } else if (lane == 0) {
-            o[row] = acc0 * r;
-            if (two) o[row + 1] = acc1 * r;
+        } else {
+            acc0 = wave_sum_to_last_row(acc0);  // DPP only; the total lands in the last 16 lanes
+            acc1 = wave_sum_to_last_row(acc1);
+            if (lane == kWave - 1) {
+                o[row] = acc0 * r;
+                if (two) o[row + 1] = acc1 * r;
+            }
         }
     }
     if (ARGMAX) {

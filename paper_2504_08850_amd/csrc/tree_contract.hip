@@ -366,7 +366,7 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
                 prev[k] = (k < K) ? prev_lds[n * K + k] : 0.f;
             }
             const int ex = finish_score_node<KC>(fr, f, gn, z, prev, lane);
-            if (lane == 0) exit_lds[n] = ex;
+            if (lane == kWave - 1) exit_lds[n] = ex;
         }
     }
     if (f.path_exit) {

@@ -37,7 +37,8 @@ __device__ __forceinline__ void finish_load_rows(FinishRows<KC> &fr, const TreeF
 }
 
 // One wavefront scores node gn from its normalised logits z (NaN = invalid) and previous
-// probabilities; writes logits, probs, score and exit flag; returns the exit flag (all lanes).
+// probabilities; writes logits, probs, score and exit flag; returns the exit flag, valid in the
+// last lane (kWave - 1) only.
 template <int KC>
 __device__ __forceinline__ int finish_score_node(FinishRows<KC> &fr, const TreeFinishParams &p, size_t gn,
                                                  const float (&z)[KC], const float (&prev)[KC], int lane) {
@@ -68,10 +69,10 @@ __device__ __forceinline__ int finish_score_node(FinishRows<KC> &fr, const TreeF
             part += mlp_unit<KC>(row, p.W1, K, j, z, pr, prev);
         }
     }
-    part = wave_sum(part);
+    part = wave_sum_to_last_row(part);
     const float sc = sigmoidf(fr.b2 + part);
     const int ex = (sc > p.threshold) ? 1 : 0;
-    if (lane == 0) {
+    if (lane == kWave - 1) {
         p.scores[gn] = sc;
         p.exit_flags[gn] = ex;
     }

@@ -201,7 +201,7 @@ __global__ __launch_bounds__(WHOLE ? 512 : 256) void tree_finish_kernel(TreeFini
             }
         }
         const int ex = finish_score_node<KC>(fr, p, gn, z, prev, lane);
-        if (WHOLE && lane == 0) exit_lds[n] = ex;
+        if (WHOLE && lane == kWave - 1) exit_lds[n] = ex;
     }
     if (WHOLE && p.path_exit) {  // whole tree in this workgroup: the path rule from LDS
         __syncthreads();
