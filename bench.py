@@ -164,7 +164,7 @@ def main():
             "ms_per_step": ms_per_step,
             "us_per_call": us_per_call,
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-            "dtype": "f32 (fp16 inputs widened, fp32 accumulation)", "data": "synthetic",
+            "dtype": "f32", "dtype_note": "fp16 inputs widened exactly, fp32 products and sums", "data": "synthetic",
             "config": {"workload": "C2: 32-layer exit sweep for one token, d=4096 V=32000 K=4, MLP 12->512->1, "
                                    "32 dependent specee_predict launches per step (HIP graph replay), "
                                    f"{R} rotating input sets", "batch": 1, "layers": L},

@@ -46,12 +46,18 @@ __device__ inline int merge_block(const int32_t *ids, int n, int32_t *lds, int32
     int32_t *wtot = lds + 3 * n4;           // [<= 64] ballot totals
     uniq = table + n4;                      // [n4]  (after the table is dead) sorted distinct keys
 
+    // element slots in use: a tree of at most T ids needs one per thread, and every loop below skips
+    // the unused slots with a workgroup-uniform test (this code sits on the latency path of a tree call)
+    const int E = (n4 + T - 1) / T;
     int kreg[kMergePerThread], rep[kMergePerThread];
 #pragma unroll
     for (int e = 0; e < kMergePerThread; ++e) {
-        const int i = tid + e * T;
-        kreg[e] = i < n ? ids[i] : 0x7fffffff;
-        if (i < n4) key[i] = kreg[e];
+        kreg[e] = 0x7fffffff;
+        if (e < E) {
+            const int i = tid + e * T;
+            kreg[e] = i < n ? ids[i] : 0x7fffffff;
+            if (i < n4) key[i] = kreg[e];
+        }
     }
     for (unsigned t = tid; t < TS; t += T) table[t] = -1;
     __syncthreads();
@@ -61,7 +67,7 @@ __device__ inline int merge_block(const int32_t *ids, int n, int32_t *lds, int32
     for (int e = 0; e < kMergePerThread; ++e) {
         const int i = tid + e * T;
         rep[e] = -1;
-        if (i < n) {
+        if (e < E && i < n) {
             const int k = kreg[e];
             unsigned h = (unsigned)(((unsigned long long)((unsigned)k * 2654435761u) * TS) >> 32);
             for (unsigned probe = 0; probe < TS; ++probe) {  // the table is larger than n: always ends early
@@ -87,9 +93,14 @@ __device__ inline int merge_block(const int32_t *ids, int n, int32_t *lds, int32
     for (int e = 0; e < kMergePerThread; ++e) {
         const int i = tid + e * T;
         isrep[e] = i < n && rep[e] == i;
-        const unsigned long long mask = __ballot(isrep[e]);
-        incl[e] = __popcll(mask & (~0ull >> (63 - lane)));
-        if (lane == 0) wtot[e * nwaves + wave] = __popcll(mask);
+        incl[e] = 0;
+        if (e < E) {
+            const unsigned long long mask = __ballot(isrep[e]);
+            incl[e] = __popcll(mask & (~0ull >> (63 - lane)));
+            if (lane == 0) wtot[e * nwaves + wave] = __popcll(mask);
+        } else if (lane == 0) {
+            wtot[e * nwaves + wave] = 0;
+        }
     }
     __syncthreads();
     int M = 0;
@@ -135,7 +146,7 @@ __device__ inline int merge_block(const int32_t *ids, int n, int32_t *lds, int32
         const int a = tid + e * T;
         rnk[e] = 0;
         kd[e] = 0;
-        if (a < M) {
+        if (e < E && a < M) {
             const int k = key[a];
             int r0 = 0, r1 = 0, r2 = 0, r3 = 0;
 #pragma unroll 4

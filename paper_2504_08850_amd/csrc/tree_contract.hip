@@ -385,10 +385,10 @@ bool tree_gemm_can_fuse_merge(int n_ids) {
 hipError_t launch_tree_gemm(const GemmParams &p, int G, hipStream_t st) {
     dim3 grid(p.S, (p.Mcap + 63) / 64, G * ((p.N + 63) / 64));
     if (p.ids)
-        hipLaunchKernelGGL((tree_contract_kernel<4, 0, true, 4, 4, 64>), grid, dim3(256), 0, st, p,
+        hipLaunchKernelGGL((tree_contract_kernel<4, 0, true, 2, 4, 128>), grid, dim3(256), 0, st, p,
                            TreeFinishParams{});
     else
-        hipLaunchKernelGGL((tree_contract_kernel<4, 0, false, 4, 4, 64>), grid, dim3(256), 0, st, p,
+        hipLaunchKernelGGL((tree_contract_kernel<4, 0, false, 2, 4, 128>), grid, dim3(256), 0, st, p,
                            TreeFinishParams{});
     return hipGetLastError();
 }

@@ -88,6 +88,25 @@ def test_predict_c1_llama7b_shape(sp, oracle):
     assert 0 < exits < 8
 
 
+def test_predict_throughput_configuration_sampled_tokens(sp, oracle):
+    """The batched launch the benchmark times (8000 tokens, ids distinct across the batch): every output of
+    a sample of tokens against the oracle, and cheap whole-batch properties."""
+    c = synth.CONFIGS["C1"]
+    lm_h, lm_d = lm_for(c)
+    B = 8000
+    rng = np.random.default_rng(8000)
+    hid = rng.standard_normal((B, c.d), dtype=np.float32).astype(np.float16)
+    ids = rng.permutation(c.V)[:B * c.K].reshape(B, c.K).astype(np.int32)
+    t = synth.make("C1", lm=lm_h)
+    t = dict(t, hidden=hid, ids=ids, prev_probs=synth.prob_rows(B, c.K, 9))
+    got = run_predict(sp, t, lm_d)
+    pick = np.unique(np.concatenate([[0, B - 1], rng.integers(0, B, 96)]))
+    ref = oracle.predict(hid[pick], t["gamma"], lm_h, ids[pick], t["prev_probs"][pick], t["W1"], t["w2"])
+    check_scored({k: v[pick] for k, v in got.items()}, ref, c.threshold, "B=8000 sampled")
+    np.testing.assert_allclose(got["probs"].sum(axis=1), 1.0, atol=1e-5)
+    assert np.all(np.isfinite(got["scores"])) and 0.05 < got["exit"].mean() < 0.95
+
+
 def test_predict_is_deterministic(sp):
     c = synth.CONFIGS["C1"]
     lm_h, lm_d = lm_for(c)

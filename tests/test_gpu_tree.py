@@ -262,6 +262,29 @@ def test_tree_many_trees_c3_batch(sp, oracle):
     assert np.array_equal(got["merged"][5], single["merged"]) and np.array_equal(got["cols"][5], single["cols"])
 
 
+def test_tree_throughput_configuration_sampled_trees(sp, oracle):
+    """The 256-tree launch the benchmark times: integer outputs of every tree against numpy, all outputs of
+    a sample of trees against the oracle."""
+    c = synth.CONFIGS["C3"]
+    lm_h, lm_d = lm_for(c)
+    G = 256
+    ts = [synth.make("C3", seed=1000 + i, lm=lm_h) for i in range(G)]
+    tb = stack_trees(ts)
+    got = run_tree(sp, tb, lm_d, c.Mcap)
+    for g_ in range(G):
+        u, inv = np.unique(ts[g_]["ids"], return_inverse=True)
+        assert got["M"][g_] == len(u)
+        assert np.array_equal(got["merged"][g_, :len(u)], u) and np.all(got["merged"][g_, len(u):] == -1)
+        assert np.array_equal(got["cols"][g_].ravel(), inv.ravel())
+    pick = [0, 17, 101, 255]
+    sub = stack_trees([ts[i] for i in pick])
+    sub = dict(sub, gamma=tb["gamma"], W1=tb["W1"], w2=tb["w2"], b1=tb["b1"], b2=tb["b2"])
+    oracle.set_threads(8)
+    ref = ref_tree(oracle, sub, c.Mcap)
+    oracle.set_threads(1)
+    check_tree({k: (v[pick] if v is not None else None) for k, v in got.items()}, ref, c.threshold, "256 x C3 sampled")
+
+
 def test_tree_without_parent_and_with_malformed_parent(sp, oracle):
     t = synth.make("T4")
     c = t["cfg"]
