@@ -154,11 +154,17 @@ int lm_head_gemv(const specee_dims *dims, int N, const specee_half *hidden, cons
  * Verification (Sec. 4.3.3): arg-max of the full-vocabulary logits (lowest id
  * on ties) without materialising them, and whether it is one of the K
  * speculative ids.  token [N], max_logit [N] fp32, hit [N] int32.
+ * gate (optional): verification follows a positive prediction only, so the exit
+ * flags of specee_predict can be passed here; hidden states with gate[n] == 0
+ * are skipped on the device -- token -1, max_logit 0, hit 0 -- and when no state
+ * of a launch is gated in, the pass over the LM head is not made at all.  This
+ * keeps the predict -> verify sequence free of host round trips.
  * Workspace: SPECEE_OP_VERIFY with n = N.
  */
 int specee_verify(const specee_dims *dims, int N, const specee_half *hidden, const specee_half *gamma,
-                  const specee_half *lm_head, const int32_t *ids, int32_t *token, float *max_logit, int32_t *hit,
-                  void *workspace, size_t workspace_bytes, void *stream);
+                  const specee_half *lm_head, const int32_t *ids, const int32_t *gate /* [N] or NULL */,
+                  int32_t *token, float *max_logit, int32_t *hit, void *workspace, size_t workspace_bytes,
+                  void *stream);
 
 /* Bytes of device workspace `op` needs for n tokens / nodes (Mcap: tree only).
  * Pure host function; 0 means none; (size_t)-1 means invalid arguments. */

@@ -46,11 +46,16 @@ struct GemmParams {
     int Mpad, Npad;
     float *best_val;         // arg-max mode: [N][gridDim.x] candidates
     int32_t *best_idx;
+    const int32_t *gate;     // arg-max mode: [N] or null; states with gate == 0 are not verified
     // fused merge (tree, N*K <= 1024): the kernel merges ids itself and workgroup (0,0) of each tree
     // publishes the results
     const int32_t *ids;      // [G][N][K] or null (rowlist / Mptr are then inputs)
     int K;
     int32_t *merged_out, *M_out, *cols_out;
+    // whole-tree kernel with S > 1: the S workgroups of a tree leave their accumulators in `out`
+    // ([G][S][256 threads][row tiles] quads) and `ssq_part` ([G][S][64]); the one that draws the last
+    // ticket adds them up in slice order and scores the tree.  tickets [G] must be zero at launch.
+    int32_t *tickets;
 };
 
 struct TreeFinishParams {
@@ -69,6 +74,7 @@ struct TreeFinishParams {
     int32_t *path_exit;      // [G][N] or null
 };
 
+hipError_t launch_zero_i32(int32_t *p, int n, hipStream_t st);
 hipError_t launch_merge(const int32_t *ids, int n, int G, int Mcap, int32_t *merged, int32_t *M_out, int32_t *cols,
                         hipStream_t st);
 bool tree_gemm_can_fuse_merge(int n_ids);
@@ -88,10 +94,13 @@ hipError_t launch_lm_head_gemv(int d, int V, float eps, int N, const half_t *hid
 int lm_head_gemv_workgroups(int V);
 int lm_head_gemm_workgroups(int V);
 hipError_t launch_lm_head_argmax_gemv(int d, int V, float eps, int N, const half_t *hidden, const half_t *gamma,
-                                      const half_t *lm_head, float *best_val, int32_t *best_idx, hipStream_t s);
+                                      const half_t *lm_head, float *best_val, int32_t *best_idx, const int32_t *gate,
+                                      hipStream_t s);
 hipError_t launch_lm_head_argmax_gemm(int d, int V, float eps, int N, const half_t *hidden, const half_t *gamma,
-                                      const half_t *lm_head, float *best_val, int32_t *best_idx, hipStream_t s);
+                                      const half_t *lm_head, float *best_val, int32_t *best_idx, const int32_t *gate,
+                                      hipStream_t s);
 hipError_t launch_verify_finish(const float *best_val, const int32_t *best_idx, int P, int N, const int32_t *ids,
-                                int K, int32_t *token, float *max_logit, int32_t *hit, hipStream_t s);
+                                int K, const int32_t *gate, int32_t *token, float *max_logit, int32_t *hit,
+                                hipStream_t s);
 
 }  // namespace specee

@@ -55,7 +55,13 @@ TreeSplit tree_split(int d, int n_total, int N, int Mcap) {
     return {S, dslice};
 }
 
-constexpr int kWholeTreeMinTrees = 16;
+// Trees per launch from which one workgroup (or a few, see below) per tree beats spreading every
+// tree over the whole GPU, and the workgroups per launch the ticketed d-slices aim for (one
+// 512-thread workgroup per CU).  With more slices than kWholeMaxSlices the serial hand-off to the
+// last workgroup costs more than the slices save.  Measured on MI355X with 60-node trees.
+constexpr int kWholeTreeMinTrees = 20;
+constexpr int kWholeTargetWgs = 256;
+constexpr int kWholeMaxSlices = 8;
 
 inline size_t align256(size_t b) {
     return (b + 255) & ~(size_t)255;
@@ -229,7 +235,26 @@ int specee_predict_tree(const specee_dims *dm, int G, int N, int Mcap, const spe
     // contraction over all of d, scoring and the path rule, and no partial sums touch memory
     if (G >= kWholeTreeMinTrees && tree_whole_supported(N, dm->K, Mcap)) {
         gp.ids = ids;
-        gp.dslice = ((dm->d + 63) / 64) * 64; gp.S = 1;
+        // fewer trees than the GPU holds workgroups: S workgroups per tree, one d-slice each, and the
+        // last to finish adds the slices up and scores the tree
+        int S = kWholeTargetWgs / G;
+        if (S > kWholeMaxSlices) S = kWholeMaxSlices;
+        if (S < 1) S = 1;
+        int dslice = (((dm->d + S - 1) / S + 127) / 128) * 128;
+        S = (dm->d + dslice - 1) / dslice;
+        const size_t quads = (size_t)256 * (Mcap > 64 ? 8 : 4);
+        const size_t part_bytes = align256((size_t)G * S * quads * 16);
+        const size_t ssq_bytes = align256((size_t)G * S * 64 * sizeof(float));
+        const size_t tick_bytes = align256((size_t)G * sizeof(int32_t));
+        if (S > 1 && part_bytes + ssq_bytes + tick_bytes > workspace_bytes) {
+            S = 1;
+            dslice = ((dm->d + 127) / 128) * 128;
+        }
+        gp.dslice = dslice; gp.S = S;
+        gp.out = reinterpret_cast<float *>(ws);
+        gp.ssq_part = reinterpret_cast<float *>(ws + part_bytes);
+        gp.tickets = reinterpret_cast<int32_t *>(ws + part_bytes + ssq_bytes);
+        if (S > 1 && launch_zero_i32(gp.tickets, G, st) != hipSuccess) return SPECEE_EHIP;
         return launch_tree_whole(gp, fp, G, st) == hipSuccess ? SPECEE_OK : SPECEE_EHIP;
     }
 
@@ -246,8 +271,8 @@ int specee_predict_tree(const specee_dims *dm, int G, int N, int Mcap, const spe
 }
 
 int specee_verify(const specee_dims *dm, int N, const specee_half *hidden, const specee_half *gamma,
-                  const specee_half *lm_head, const int32_t *ids, int32_t *token, float *max_logit, int32_t *hit,
-                  void *workspace, size_t workspace_bytes, void *stream) {
+                  const specee_half *lm_head, const int32_t *ids, const int32_t *gate, int32_t *token,
+                  float *max_logit, int32_t *hit, void *workspace, size_t workspace_bytes, void *stream) {
     int rc = check_dims(dm, false);
     if (rc) return rc;
     if (N < 0 || N > 65535 || dm->K < 1 || dm->K > SPECEE_KMAX) return SPECEE_EINVAL;
@@ -262,11 +287,11 @@ int specee_verify(const specee_dims *dm, int N, const specee_half *hidden, const
     int32_t *best_idx = reinterpret_cast<int32_t *>(static_cast<char *>(workspace) + half_ws);
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e = vec ? launch_lm_head_argmax_gemv(dm->d, dm->V, dm->eps, N, H(hidden), H(gamma), H(lm_head),
-                                                    best_val, best_idx, st)
+                                                    best_val, best_idx, gate, st)
                        : launch_lm_head_argmax_gemm(dm->d, dm->V, dm->eps, N, H(hidden), H(gamma), H(lm_head),
-                                                    best_val, best_idx, st);
+                                                    best_val, best_idx, gate, st);
     if (e != hipSuccess) return SPECEE_EHIP;
-    e = launch_verify_finish(best_val, best_idx, P, N, ids, dm->K, token, max_logit, hit, st);
+    e = launch_verify_finish(best_val, best_idx, P, N, ids, dm->K, gate, token, max_logit, hit, st);
     return e == hipSuccess ? SPECEE_OK : SPECEE_EHIP;
 }
 

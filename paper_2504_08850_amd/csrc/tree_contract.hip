@@ -31,6 +31,7 @@
 namespace specee {
 
 constexpr int kTcFusedMax = kMergePerThread * 256;  // ids per tree when the merge is fused
+constexpr int kWholeWideMaxWgs = 256;               // one 512-thread workgroup per CU
 
 // KCH: k elements per stage (64 or 128).  A stage is one barrier and one LDS write -> read -> matrix
 // instruction dependency chain, so longer stages amortise that latency; 128 needs the row tile to
@@ -58,6 +59,8 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     __shared__ float ssq_lds[MODE == 3 ? 64 : 1];
     __shared__ int32_t bad_lds[MODE == 3 ? 64 : 1];
     __shared__ int32_t exit_lds[MODE == 3 ? 64 : 1];
+    __shared__ int32_t par_lds[MODE == 3 ? 64 : 1];
+    __shared__ int32_t last_lds;
     static_assert(MT == 4 || MT == 8, "row tiles per workgroup");
     static_assert(sizeof(half_t) * kALdsHalves >= sizeof(int32_t) * merge_lds_ints(kTcFusedMax),
                   "merge scratch must fit in the row tile buffers");
@@ -110,6 +113,7 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
         const int n_ids = p.N * p.K;
         for (int i = tid; i < n_ids; i += kTcThreads) prev_lds[i] = f.prev[(size_t)g * n_ids + i];
         if (tid < 64) bad_lds[tid] = 0;
+        if (f.path_exit && tid < p.N) par_lds[tid] = f.parent[(size_t)g * p.N + tid];
     }
 
     // ---- merged rows
@@ -183,6 +187,20 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
 #pragma unroll
     for (int u = 0; u < PD; ++u) issue_a(u, u);
 
+    // MODE 3: the predictor goes to LDS after the contraction (into the part of the row-tile buffers
+    // that the logits leave free, when it fits).  Its first kMlpPf vectors per thread are requested
+    // here and ride in registers through the stage loop, so that the scoring phase does not start
+    // with a round trip to memory.
+    constexpr int kMlpPf = 2;
+    constexpr size_t kMlpFree = sizeof(half_t) * kALdsHalves - sizeof(float) * 64 * ROWS;
+    const bool mfma_mlp = MODE == 3 && KC <= 8 && mlp_mfma_ok(p.K, f.H);
+    const bool mlp_in_lds = mfma_mlp && (size_t)mlp_lds_halves(p.K, f.H) * sizeof(half_t) <= kMlpFree;
+    half8 mlp_pf[kMlpPf];
+    if (MODE == 3 && mlp_in_lds) {
+#pragma unroll
+        for (int e = 0; e < kMlpPf; ++e) mlp_pf[e] = mlp_vector(f, tid + e * kTcThreads);
+    }
+
     floatx4 acc[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -191,49 +209,73 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     // The stage loop is free of branches (stages past the end are issued on clamped addresses and
     // contribute zeros) so that the compiler can keep PD stages of loads outstanding instead of
     // draining the memory pipeline at every control-flow join.
+    //
+    // It is software-pipelined by one stage: while the matrix cores work on stage kc (row tile in
+    // a_lds[buf], B operand in bhi/blo), the vector units turn the prefetched registers of stage kc+1
+    // into the next B operand and the next row tile (a_lds[buf ^ 1]), and that slot's registers are
+    // re-used for the loads of stage kc+1+PD.  One barrier per stage publishes the next tile and
+    // retires the reads of the current one.
+    auto tile_to_lds = [&](int kc, int slot, int b) {
+#pragma unroll
+        for (int i = 0; i < APT; ++i)
+            *reinterpret_cast<half8 *>(&a_lds[b][a_r[i]][a_v[i] * 8]) =
+                a_valid(kc, i) ? a_buf[slot][i] : zero_half8();
+    };
+    // x = h*gamma split exactly into hi = round(h*gamma), lo = round(fma(h, gamma, -hi))
+    auto build_b = [&](int kc, int slot, int j, half8 &hi, half8 &lo) {
+        const half8 hsel = b_valid(kc, j) ? h_buf[slot][j] : zero_half8();
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const half2_t hh = {hsel[2 * e], hsel[2 * e + 1]};
+            const half2_t gg = {g_buf[slot][j][2 * e], g_buf[slot][j][2 * e + 1]};
+            const half2_t x = hh * gg;
+            const half2_t rres = __builtin_elementwise_fma(hh, gg, -x);
+            ssq = __builtin_amdgcn_fdot2(hh, hh, ssq, false);
+            hi[2 * e] = x[0];
+            hi[2 * e + 1] = x[1];
+            lo[2 * e] = rres[0];
+            lo[2 * e + 1] = rres[1];
+        }
+    };
     const int nstages = ((nchunks + PD - 1) / PD) * PD;
+    half8 bhi[JN], blo[JN];
+    tile_to_lds(0, 0, 0);
+#pragma unroll
+    for (int j = 0; j < JN; ++j) build_b(0, 0, j, bhi[j], blo[j]);
+    issue_a(PD, 0);
+    issue_b(PD, 0);
+    __syncthreads();
     int buf = 0;
     for (int kc0 = 0; kc0 < nstages; kc0 += PD) {
 #pragma unroll
         for (int u = 0; u < PD; ++u) {
             const int kc = kc0 + u;
-#pragma unroll
-            for (int i = 0; i < APT; ++i)
-                *reinterpret_cast<half8 *>(&a_lds[buf][a_r[i]][a_v[i] * 8]) =
-                    a_valid(kc, i) ? a_buf[u][i] : zero_half8();
-            // x = h*gamma split exactly into hi = round(h*gamma), lo = round(fma(h, gamma, -hi))
-            half8 bhi[JN], blo[JN];
-#pragma unroll
-            for (int j = 0; j < JN; ++j) {
-                const half8 hsel = b_valid(kc, j) ? h_buf[u][j] : zero_half8();
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const half2_t hh = {hsel[2 * e], hsel[2 * e + 1]};
-                    const half2_t gg = {g_buf[u][j][2 * e], g_buf[u][j][2 * e + 1]};
-                    const half2_t x = hh * gg;
-                    const half2_t rres = __builtin_elementwise_fma(hh, gg, -x);
-                    ssq = __builtin_amdgcn_fdot2(hh, hh, ssq, false);
-                    bhi[j][2 * e] = x[0];
-                    bhi[j][2 * e + 1] = x[1];
-                    blo[j][2 * e] = rres[0];
-                    blo[j][2 * e + 1] = rres[1];
-                }
-            }
-            __syncthreads();
-            issue_a(kc + PD, u);
-            issue_b(kc + PD, u);
+            constexpr int kDummy = 0;
+            (void)kDummy;
+            const int nslot = (u + 1) % PD;  // folds: u is an unrolled constant
+            half8 nhi[JN], nlo[JN];
+            tile_to_lds(kc + 1, nslot, buf ^ 1);
 #pragma unroll
             for (int j = 0; j < JN; ++j) {
                 half8 a[MT];
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
                     a[mt] = *reinterpret_cast<const half8 *>(&a_lds[buf][mt * 16 + c][koff(j)]);
+                build_b(kc + 1, nslot, j, nhi[j], nlo[j]);
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
                     acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], bhi[j], acc[mt], 0, 0, 0);
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
                     acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], blo[j], acc[mt], 0, 0, 0);
+            }
+            issue_a(kc + 1 + PD, nslot);
+            issue_b(kc + 1 + PD, nslot);
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < JN; ++j) {
+                bhi[j] = nhi[j];
+                blo[j] = nlo[j];
             }
             buf ^= 1;
         }
@@ -280,6 +322,61 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
         }
         __syncthreads();
     }
+    if (p.S > 1) {
+        // This workgroup covered one d-slice of the tree.  Every slice leaves its accumulators in the
+        // workspace and draws a ticket; the holder of the last one adds the slices up in slice order
+        // (so the result does not depend on which workgroup that is) and goes on to score the tree.
+        // The accumulators travel as relaxed device-scope atomics: such stores are written through to
+        // the level all XCDs share and such loads are served from there, so no cache has to be flushed
+        // or invalidated around the ticket (a device-scope fence would walk this XCD's whole L2).
+        // __syncthreads() waits for every outstanding store of the workgroup before the ticket is drawn.
+        const int t256 = tid & 255;  // kh == 0 wavefronts are threads 0..255
+        // [G][S][row-tile quad element][256 threads]: a wavefront's accesses are contiguous
+        float *part = p.out + (size_t)g * p.S * (256 * MT * 4) + t256;
+        float *ssq_part = p.ssq_part + (size_t)g * p.S * 64 + nt_w * 16 + c;
+        const size_t sstride = (size_t)256 * MT * 4;
+        if (kh == 0) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    __hip_atomic_store(part + s * sstride + (mt * 4 + r) * 256, acc[mt][r], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+            if (q == 0)
+                __hip_atomic_store(ssq_part + (size_t)s * 64, ssq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+        if (tid == 0) last_lds = atomicAdd(&p.tickets[g], 1) == p.S - 1;
+        __syncthreads();
+        if (!last_lds) return;  // uniform over the workgroup
+        if (kh == 0) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+            ssq = 0.f;
+            for (int s0 = 0; s0 < p.S; s0 += 4) {
+                floatx4 v[4][MT];
+                float sq[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int ss = min(s0 + u, p.S - 1);  // clamped: always in bounds, masked below
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            v[u][mt][r] = __hip_atomic_load(part + ss * sstride + (mt * 4 + r) * 256, __ATOMIC_RELAXED,
+                                                            __HIP_MEMORY_SCOPE_AGENT);
+                    sq[u] = __hip_atomic_load(ssq_part + (size_t)ss * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (s0 + u < p.S) {
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt) acc[mt] += v[u][mt];
+                        ssq += sq[u];
+                    }
+            }
+        }
+    }
     if (kh == 0) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
@@ -289,14 +386,19 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     __syncthreads();
 
     const int K = p.K, N = p.N;
-    const bool mfma_mlp = KC <= 8 && mlp_mfma_ok(K, f.H);
     if (mfma_mlp) {
-        // the predictor is copied into the part of the row-tile buffers that the logits leave free,
-        // when it fits; the copy is published by the barrier after the features are written
+        // the copy of the predictor is published by the barrier after the features are written
         TreeFinishParams fl = f;
-        constexpr size_t kFree = sizeof(half_t) * kALdsHalves - sizeof(float) * 64 * ROWS;
-        if ((size_t)mlp_lds_halves(K, f.H) * sizeof(half_t) <= kFree)
-            fl = stage_mlp_to_lds(reinterpret_cast<half_t *>(Zl + 64 * ROWS), f, tid, kTcThreads);
+        if (mlp_in_lds) {
+            half_t *dst = reinterpret_cast<half_t *>(Zl + 64 * ROWS);
+            const int nvec = mlp_lds_halves(K, f.H) / 8;
+#pragma unroll
+            for (int e = 0; e < kMlpPf; ++e)
+                if (tid + e * kTcThreads < nvec) reinterpret_cast<half8 *>(dst)[tid + e * kTcThreads] = mlp_pf[e];
+            for (int i = tid + kMlpPf * kTcThreads; i < nvec; i += kTcThreads)
+                reinterpret_cast<half8 *>(dst)[i] = mlp_vector(f, i);
+            fl = mlp_params_at(dst, f);
+        }
         // lanes q == 0 build the features of node c; all lanes then feed the matrix cores
         float *F = feat_lds + nt_w * 16 * kMlpFeat;
         const int n = nt_w * 16 + c;  // node within the tree (N <= 64: n0 == 0)
@@ -329,7 +431,19 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
             for (int t = 3 * K; t < kMlpFeat; ++t) F[c * kMlpFeat + t] = 0.f;
         }
         __syncthreads();
-        const float u = kh == 0 ? mlp_mfma_16(F, fl, lane) : 0.f;
+        // the two wavefronts of a node tile take half of the hidden units each
+        const int htiles = f.H >> 4;
+        const bool split = KH == 2 && (htiles & 7) == 0;
+        const int per = split ? htiles >> 1 : htiles;
+        float u = 0.f;
+        if (kh == 0 || split)
+            u = mlp_in_lds ? mlp_mfma_16<true>(F, fl, lane, split ? kh * per : 0, per)
+                           : mlp_mfma_16<false>(F, fl, lane, split ? kh * per : 0, per);
+        if (KH == 2 && split) {
+            if (kh == 1 && q == 0) ssq_lds[n] = u;
+            __syncthreads();
+            if (kh == 0) u += ssq_lds[n];
+        }
         if (q == 0 && kh == 0 && n < N) {
             const float b2 = f.b2 ? (float)f.b2[0] : 0.f;
             float sc = sigmoidf(b2 + u);
@@ -371,7 +485,7 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     }
     if (f.path_exit) {
         __syncthreads();
-        finish_paths(exit_lds, f.parent + (size_t)g * N, N, tid, kTcThreads, f.path_exit + (size_t)g * N);
+        finish_paths(exit_lds, par_lds, N, tid, kTcThreads, f.path_exit + (size_t)g * N);
     }
 }
 
@@ -398,14 +512,21 @@ bool tree_whole_supported(int N, int K, int Mcap) {
     return N <= 64 && N * K <= kTcFusedMax && Mcap <= 128;
 }
 
+// Variants of the whole-tree kernel.  Up to 64 merged rows: 512 threads (two wavefronts share a
+// node tile) when each CU gets at most one workgroup, 256 threads when there are more workgroups
+// than CUs, because two of those fit on a CU and one's prologue and scoring overlap the other's
+// streaming.  65..128 merged rows: 256 threads, eight row tiles.
 template <int MT, int KC>
 static void launch_whole(const GemmParams &p, const TreeFinishParams &f, int G, hipStream_t st) {
-    if constexpr (MT == 4)
-        hipLaunchKernelGGL((tree_contract_kernel<MT, 3, true, 2, KC, 128, 512>), dim3(1, 1, G), dim3(512), 0, st, p,
-                           f);
-    else
-        hipLaunchKernelGGL((tree_contract_kernel<MT, 3, true, 4, KC, 64, 256>), dim3(1, 1, G), dim3(256), 0, st, p,
-                           f);
+    const dim3 grid(p.S, 1, G);
+    if constexpr (MT == 4) {
+        if ((long long)G * p.S <= kWholeWideMaxWgs)
+            hipLaunchKernelGGL((tree_contract_kernel<4, 3, true, 2, KC, 128, 512>), grid, dim3(512), 0, st, p, f);
+        else
+            hipLaunchKernelGGL((tree_contract_kernel<4, 3, true, 4, KC, 64, 256>), grid, dim3(256), 0, st, p, f);
+    } else {
+        hipLaunchKernelGGL((tree_contract_kernel<8, 3, true, 4, KC, 64, 256>), grid, dim3(256), 0, st, p, f);
+    }
 }
 
 hipError_t launch_tree_whole(const GemmParams &p, const TreeFinishParams &f, int G, hipStream_t st) {

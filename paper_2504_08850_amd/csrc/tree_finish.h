@@ -92,11 +92,24 @@ __device__ __forceinline__ int finish_score_node(FinishRows<KC> &fr, const TreeF
 
 // Predictor MLP for the 16 nodes of a wavefront on the matrix cores (needs K in {4, 8} and H a
 // multiple of 64).  F: this wavefront's [16][kMlpFeat] fp32 features in LDS (zero beyond 3K).
-// Returns the output pre-activation (without b2) of node c = lane & 15 in every lane.
+// Covers the ht_count tiles of 16 hidden units from tile ht_begin (ht_count a multiple of 4) and
+// returns their share of the output pre-activation (without b2) of node c = lane & 15 in every lane.
 // The loop over tiles of 16 hidden units is free of branches -- every load is in bounds and
 // unconditional, invalid k-slots are zeroed by selects -- so that it can be unrolled with the
 // weight loads of several tiles in flight.
-__device__ __forceinline__ float mlp_mfma_16(const float *F, const TreeFinishParams &f, int lane) {
+// LDS = true: the predictor pointers in f address a copy in LDS.  They are generic pointers, which
+// the compiler would read with flat loads (a trip through the vector memory path before the request
+// reaches LDS); the explicit address space turns them into plain LDS reads.
+template <bool LDS>
+__device__ __forceinline__ half4 mlp_load8(const half_t *p) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    if constexpr (LDS) return *(const __attribute__((address_space(3))) half4 *)p;
+#endif
+    return *reinterpret_cast<const half4 *>(p);
+}
+template <bool LDS>
+__device__ __forceinline__ float mlp_mfma_16(const float *F, const TreeFinishParams &f, int lane, int ht_begin,
+                                             int ht_count) {
     const int c = lane & 15, q = lane >> 4;
     const int K3 = 3 * f.K, H = f.H;
     half8 bhi, blo;
@@ -113,15 +126,14 @@ __device__ __forceinline__ float mlp_mfma_16(const float *F, const TreeFinishPar
     const half_t *b1p = f.b1 ? f.b1 : f.w2;  // always a valid address; masked below
     const float b1m = f.b1 ? 1.f : 0.f;
     float acc_u = 0.f;
-    const int htiles = H >> 4;  // a multiple of 4 (H is a multiple of 64)
-    for (int ht0 = 0; ht0 < htiles; ht0 += 4)
+    (void)H;
+    for (int ht0 = ht_begin; ht0 < ht_begin + ht_count; ht0 += 4)
 #pragma unroll
     for (int hi_ = 0; hi_ < 4; ++hi_) {
         const int ht = ht0 + hi_;
-        const uint2 *src = reinterpret_cast<const uint2 *>(wbase + (size_t)(ht * 16 + c) * K3);
-        const uint2 raw0 = src[0];
-        const uint2 raw1 = src[hi_ok ? 1 : 0];
-        const half4 lo4 = __builtin_bit_cast(half4, raw0), hi4 = __builtin_bit_cast(half4, raw1);
+        const half_t *src = wbase + (size_t)(ht * 16 + c) * K3;
+        const half4 lo4 = mlp_load8<LDS>(src);
+        const half4 hi4 = mlp_load8<LDS>(src + (hi_ok ? 4 : 0));
         half8 a;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -129,8 +141,8 @@ __device__ __forceinline__ float mlp_mfma_16(const float *F, const TreeFinishPar
             a[4 + e] = hi_ok ? hi4[e] : (half_t)0.f;
         }
         const int u0 = ht * 16 + 4 * q;  // this lane's four hidden units of the tile
-        const half4 w2v = __builtin_bit_cast(half4, *reinterpret_cast<const uint2 *>(f.w2 + u0));
-        const half4 b1v = __builtin_bit_cast(half4, *reinterpret_cast<const uint2 *>(b1p + u0));
+        const half4 w2v = mlp_load8<LDS>(f.w2 + u0);
+        const half4 b1v = mlp_load8<LDS>(b1p + u0);
         floatx4 dacc = {0.f, 0.f, 0.f, 0.f};
         dacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bhi, dacc, 0, 0, 0);
         dacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, blo, dacc, 0, 0, 0);
@@ -149,23 +161,31 @@ __device__ __forceinline__ float mlp_mfma_16(const float *F, const TreeFinishPar
 __host__ __device__ inline int mlp_lds_halves(int K, int H) {
     return H * 3 * K + 2 * H;
 }
-__device__ __forceinline__ TreeFinishParams stage_mlp_to_lds(half_t *dst, const TreeFinishParams &f, int tid,
-                                                            int threads) {
+// 16-byte vector i of that image, read from global memory; i is clamped into the image, so the load
+// is always in bounds and needs no branch.
+__device__ __forceinline__ half8 mlp_vector(const TreeFinishParams &f, int i) {
+    const int nW8 = f.H * 3 * f.K / 8, H8 = f.H / 8;
+    i = min(i, nW8 + 2 * H8 - 1);
+    const half_t *src = f.W1 + (size_t)i * 8;
+    if (i >= nW8) src = f.w2 + (size_t)(i - nW8) * 8;
+    const bool bias = i >= nW8 + H8;
+    if (bias) src = (f.b1 ? f.b1 : f.w2) + (size_t)(i - nW8 - H8) * 8;
+    const half8 v = load_half8(src);
+    return (bias && !f.b1) ? zero_half8() : v;
+}
+__device__ __forceinline__ TreeFinishParams mlp_params_at(half_t *dst, const TreeFinishParams &f) {
     const int nW = f.H * 3 * f.K;
-    half8 *d8 = reinterpret_cast<half8 *>(dst);
-    const half8 *w8 = reinterpret_cast<const half8 *>(f.W1);
-    for (int i = tid; i < nW / 8; i += threads) d8[i] = w8[i];
-    const half8 *v8 = reinterpret_cast<const half8 *>(f.w2);
-    const half8 *b8 = reinterpret_cast<const half8 *>(f.b1);
-    for (int i = tid; i < f.H / 8; i += threads) {
-        d8[nW / 8 + i] = v8[i];
-        d8[nW / 8 + f.H / 8 + i] = f.b1 ? b8[i] : zero_half8();
-    }
     TreeFinishParams g = f;
     g.W1 = dst;
     g.w2 = dst + nW;
     g.b1 = dst + nW + f.H;
     return g;
+}
+__device__ __forceinline__ TreeFinishParams stage_mlp_to_lds(half_t *dst, const TreeFinishParams &f, int tid,
+                                                            int threads) {
+    const int nvec = mlp_lds_halves(f.K, f.H) / 8;
+    for (int i = tid; i < nvec; i += threads) reinterpret_cast<half8 *>(dst)[i] = mlp_vector(f, i);
+    return mlp_params_at(dst, f);
 }
 
 // Path rule from exit flags in LDS (paper Sec. 6.2): a token path exits only if every token on it

@@ -141,7 +141,7 @@ __global__ __launch_bounds__(WHOLE ? 512 : 256) void tree_finish_kernel(TreeFini
                 for (int t = 3 * K; t < kMlpFeat; ++t) F[c * kMlpFeat + t] = 0.f;
             }
             __syncthreads();
-            const float u = mlp_mfma_16(F, pl, lane);
+            const float u = mlp_mfma_16<true>(F, pl, lane, 0, p.H >> 4);
             if (q == 0 && live) {
                 bool poisoned = false;
 #pragma unroll
@@ -227,6 +227,17 @@ __global__ void path_kernel(const int32_t *exit_flags, const int32_t *parent, in
         cur = up;
     }
     path_exit[i] = ok;
+}
+
+__global__ void zero_i32_kernel(int32_t *p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+// A fill kernel rather than a memset node: it behaves the same eagerly and under graph capture.
+hipError_t launch_zero_i32(int32_t *p, int n, hipStream_t st) {
+    hipLaunchKernelGGL(zero_i32_kernel, dim3((n + 255) / 256), dim3(256), 0, st, p, n);
+    return hipGetLastError();
 }
 
 hipError_t launch_merge(const int32_t *ids, int n, int G, int Mcap, int32_t *merged, int32_t *M_out, int32_t *cols,

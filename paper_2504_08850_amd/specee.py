@@ -202,8 +202,9 @@ def lm_head_gemv(hidden, gamma, lm_head, eps=1e-5, out=None, workspace=None, str
     return out
 
 
-def verify(hidden, gamma, lm_head, ids, eps=1e-5, out=None, workspace=None, stream=None):
-    """specee_verify: arg-max token of the full head and membership in the K ids."""
+def verify(hidden, gamma, lm_head, ids, gate=None, eps=1e-5, out=None, workspace=None, stream=None):
+    """specee_verify: arg-max token of the full head and membership in the K ids; `gate` ([N] int32, e.g.
+    the predictor's exit flags) skips hidden states whose entry is 0 on the device."""
     N, d = hidden.shape
     V = lm_head.shape[0]
     K = ids.shape[1]
@@ -216,7 +217,8 @@ def verify(hidden, gamma, lm_head, ids, eps=1e-5, out=None, workspace=None, stre
     workspace, wbytes = _workspace(OP_VERIFY, dims, N, 0, workspace, dev)
     f16 = torch.float16
     rc = lib().specee_verify(C.byref(dims), C.c_int(N), _ptr(hidden, f16), _ptr(gamma, f16), _ptr(lm_head, f16),
-                             _ptr(ids, torch.int32), _ptr(out["token"]), _ptr(out["max_logit"]), _ptr(out["hit"]),
+                             _ptr(ids, torch.int32), _ptr(gate, torch.int32), _ptr(out["token"]),
+                             _ptr(out["max_logit"]), _ptr(out["hit"]),
                              _ptr(workspace), wbytes, _stream(stream))
     if rc:
         raise SpeceeError("specee_verify", rc)

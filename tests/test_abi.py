@@ -93,7 +93,8 @@ def test_host_side_validation_without_a_gpu(sp):
     args_path = (fake,) * 3 + (fake, None, fake, C.byref(mlp)) + (fake,) * 4 + (other,) + (fake,) * 2 + (fake,)
     assert lib.specee_predict_tree(C.byref(ok), 1, 60, 64, *args_path, fake, C.c_size_t(1 << 30), None) == -1
     assert lib.lm_head_gemv(C.byref(ok), 1, fake, fake, odd, fake, None, C.c_size_t(0), None) == -2
-    assert lib.specee_verify(C.byref(ok), 1, fake, fake, fake, fake, fake, fake, fake, None, C.c_size_t(0), None) == -3
+    assert lib.specee_verify(C.byref(ok), 1, fake, fake, fake, fake, None, fake, fake, fake, None, C.c_size_t(0),
+                             None) == -3
 
 
 def test_workspace_sizes(sp):

@@ -184,10 +184,13 @@ def test_tree_batch_of_independent_trees(sp, oracle):
     assert len(set(ref["M"].tolist())) > 1       # trees really differ in merged size
 
 
-@pytest.mark.parametrize("name,G,bias", [("T3", 20, True), ("T3", 16, False)])
+@pytest.mark.parametrize("name,G,bias", [("T3", 20, True), ("T3", 16, False), ("T3", 40, False), ("T3", 130, True),
+                                         ("T3", 260, False)])
 def test_tree_many_trees_one_workgroup_each(sp, oracle, name, G, bias):
-    """Sixteen or more small trees take the single-launch path (merge, contraction, scoring and path rule
-    in one workgroup per tree); it must agree with the oracle like every other path."""
+    """Batches of small trees: below about twenty trees every tree is spread over the GPU; from there on
+    a single launch does merge, contraction, scoring and path rule -- with a few workgroups per tree
+    that hand their d-slices to the last one (20, 40 trees), one 512-thread workgroup per tree (130) or
+    one 256-thread workgroup per tree (260).  All must agree with the oracle."""
     ts = [synth.make(name, seed=s, bias=bias) for s in range(G)]
     c = ts[0]["cfg"]
     tb = stack_trees(ts)
@@ -204,8 +207,8 @@ def test_tree_many_trees_one_workgroup_each(sp, oracle, name, G, bias):
     (4096, 2000, 4, 512, 60, 64),    # C3 shape
     (64, 40, 1, 8, 5, 7),            # tiny
 ])
-def test_tree_many_trees_shapes(sp, oracle, d, V, K, H, N, Mcap):
-    G = 17
+@pytest.mark.parametrize("G", [17, 33])
+def test_tree_many_trees_shapes(sp, oracle, d, V, K, H, N, Mcap, G):
     ts = []
     for gidx in range(G):
         t = make_tree(1000 * gidx + d, d, V, K, H, N, bias=(K % 2 == 1))
@@ -218,11 +221,12 @@ def test_tree_many_trees_shapes(sp, oracle, d, V, K, H, N, Mcap):
     tb = stack_trees(ts)
     ref = ref_tree(oracle, tb, Mcap)
     got = run_tree(sp, tb, dev(tb["lm_head"]), Mcap)
-    check_tree(got, ref, 0.5, f"17 trees d={d} K={K} N={N}")
+    check_tree(got, ref, 0.5, f"{G} trees d={d} K={K} N={N}")
 
 
-def test_tree_many_trees_overflow_invalid_ids_and_no_parent(sp, oracle):
-    ts = [synth.make("T3", seed=s) for s in range(16)]
+@pytest.mark.parametrize("G", [16, 24])
+def test_tree_many_trees_overflow_invalid_ids_and_no_parent(sp, oracle, G):
+    ts = [synth.make("T3", seed=s) for s in range(G)]
     c = ts[0]["cfg"]
     tb = stack_trees(ts)
     lm_d = dev(tb["lm_head"])
@@ -241,7 +245,7 @@ def test_tree_many_trees_overflow_invalid_ids_and_no_parent(sp, oracle):
     got = run_tree(sp, bad, lm_d, c.Mcap, parent=None)
     assert got["path_exit"] is None
     assert np.isnan(got["scores"][3, 4]) and np.isnan(got["scores"][7, 0]) and got["exit"][3, 4] == 0
-    mask = np.ones((16, c.N), bool); mask[3, 4] = mask[7, 0] = False
+    mask = np.ones((G, c.N), bool); mask[3, 4] = mask[7, 0] = False
     close(got["scores"][mask], ref["scores"][mask], 1e-3, "valid nodes beside invalid ones")
 
 
@@ -260,6 +264,26 @@ def test_tree_many_trees_c3_batch(sp, oracle):
     single = run_tree(sp, one, lm_d, c.Mcap)            # the few-trees path gives the same answers
     close(got["scores"][5], single["scores"], 1e-3, "whole-tree vs split path")
     assert np.array_equal(got["merged"][5], single["merged"]) and np.array_equal(got["cols"][5], single["cols"])
+
+
+def test_tree_sliced_batch_is_reproducible(sp):
+    """With a few workgroups per tree, whichever finishes last adds the d-slices up -- in slice order, so
+    repeated launches give identical bits."""
+    c = synth.CONFIGS["C3"]
+    lm_h, lm_d = lm_for(c)
+    ts = [synth.make("C3", seed=300 + s, lm=lm_h) for s in range(64)]
+    tb = stack_trees(ts)
+    first = run_tree(sp, tb, lm_d, c.Mcap)
+    for _ in range(4):
+        again = run_tree(sp, tb, lm_d, c.Mcap)
+        for k in ("logits", "probs", "scores", "exit", "path_exit", "merged", "cols", "M"):
+            assert np.array_equal(first[k], again[k], equal_nan=(first[k].dtype.kind == "f")), k
+    for g_ in (0, 31, 63):      # and the same answers as a launch of that tree alone (different path)
+        one = dict(ts[0], hidden=ts[g_]["hidden"], ids=ts[g_]["ids"], prev_probs=ts[g_]["prev_probs"],
+                   parent=ts[g_]["parent"])   # the batch shares tree 0's norm weight and predictor
+        single = run_tree(sp, one, lm_d, c.Mcap)
+        close(first["scores"][g_], single["scores"], 1e-3, "sliced batch vs single tree")
+        close(first["logits"][g_], single["logits"], 1.0, "sliced batch vs single tree logits")
 
 
 def test_tree_throughput_configuration_sampled_trees(sp, oracle):
