@@ -31,9 +31,11 @@ __host__ __device__ constexpr int merge_lds_ints(int n) {
 // Returns M.  `lds` is clobbered; uniq points into it.
 // T = blockDim.x (compile time, so the short serial loops over per-wave totals unroll into
 // independent LDS reads).
+// own_ids[e] returns the thread's own ids (INT_MAX for slots beyond n) to callers that go on to
+// validate them, which saves reading them a second time.
 template <int T>
 __device__ inline int merge_block(const int32_t *ids, int n, int32_t *lds, int32_t *&uniq,
-                                  int (&col_of)[kMergePerThread]) {
+                                  int (&col_of)[kMergePerThread], int (&own_ids)[kMergePerThread]) {
     const int tid = threadIdx.x;
     constexpr int nwaves = T >> 6;
     constexpr int kTotals = kMergePerThread * nwaves;
@@ -177,9 +179,17 @@ __device__ inline int merge_block(const int32_t *ids, int n, int32_t *lds, int32
     for (int e = 0; e < kMergePerThread; ++e) {
         const int i = tid + e * T;
         col_of[e] = (i < n && rep[e] >= 0) ? key[cidx[rep[e]]] : 0;
+        own_ids[e] = kreg[e];
     }
     __syncthreads();
     return M;
+}
+
+template <int T>
+__device__ inline int merge_block(const int32_t *ids, int n, int32_t *lds, int32_t *&uniq,
+                                  int (&col_of)[kMergePerThread]) {
+    int own_ids[kMergePerThread];
+    return merge_block<T>(ids, n, lds, uniq, col_of, own_ids);
 }
 
 }  // namespace specee

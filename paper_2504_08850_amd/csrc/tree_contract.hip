@@ -32,6 +32,7 @@ namespace specee {
 
 constexpr int kTcFusedMax = kMergePerThread * 256;  // ids per tree when the merge is fused
 constexpr int kWholeWideMaxWgs = 256;               // one 512-thread workgroup per CU
+constexpr int kGammaLds = 4096;                     // elements of the RMSNorm weight a workgroup may stage in LDS
 
 // KCH: k elements per stage (64 or 128).  A stage is one barrier and one LDS write -> read -> matrix
 // instruction dependency chain, so longer stages amortise that latency; 128 needs the row tile to
@@ -40,7 +41,11 @@ constexpr int kWholeWideMaxWgs = 256;               // one 512-thread workgroup 
 // split the k-steps of every stage between them; their accumulators are added through LDS at the
 // end).  Eight wavefronts halve the per-wavefront instruction stream of a stage, which is what bounds
 // a workgroup that streams a whole tree on its own.
-template <int MT, int MODE, bool FUSED, int PD, int KC, int KCH, int THREADS = 256>
+// GL: the RMSNorm weight of the workgroup's d-slice (at most kGammaLds elements) is staged in LDS
+// once instead of being fetched again by every lane at every stage: those fetches are cache hits,
+// but they take a third of the slots of the vector memory path, which is what a CU streaming a
+// tree runs out of first.
+template <int MT, int MODE, bool FUSED, int PD, int KC, int KCH, int THREADS = 256, bool GL = false>
 __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, TreeFinishParams f) {
     constexpr int kTcThreads = THREADS;
     constexpr int kTcWaves = THREADS / 64;
@@ -61,6 +66,7 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     __shared__ int32_t exit_lds[MODE == 3 ? 64 : 1];
     __shared__ int32_t par_lds[MODE == 3 ? 64 : 1];
     __shared__ int32_t last_lds;
+    __shared__ __attribute__((aligned(16))) half_t gam_lds[GL ? kGammaLds : 8];
     static_assert(MT == 4 || MT == 8, "row tiles per workgroup");
     static_assert(sizeof(half_t) * kALdsHalves >= sizeof(int32_t) * merge_lds_ints(kTcFusedMax),
                   "merge scratch must fit in the row tile buffers");
@@ -92,7 +98,7 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     const int node = n0 + nt_w * 16 + c;
     const bool node_ok = node < p.N;
     const half_t *hrow = p.hidden + ((size_t)g * p.N + (node_ok ? node : 0)) * d;
-    half8 h_buf[PD][JN], g_buf[PD][JN];
+    half8 h_buf[PD][JN], g_buf[GL ? 1 : PD][JN];
     // Loads are unconditional (addresses clamped into the row, results zeroed by a select when they
     // are consumed): a load under a branch makes the compiler drain every outstanding load at the
     // join, which would serialise the prefetch stages.
@@ -100,7 +106,7 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
 #pragma unroll
         for (int j = 0; j < JN; ++j) {
             const int ko = min(k_begin + kc * kTcKC + koff(j), k_end - 8);  // stages past the end re-read the slice's tail
-            g_buf[slot][j] = load_half8(p.gamma + ko);
+            if (!GL) g_buf[slot][j] = load_half8(p.gamma + ko);
             h_buf[slot][j] = load_half8(hrow + ko);
         }
     };
@@ -109,11 +115,26 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     };
 #pragma unroll
     for (int u = 0; u < PD; ++u) issue_b(u, u);
+    // GL: this thread's share of the slice's RMSNorm weight, parked in LDS after the merge
+    constexpr int kGamPt = GL ? kGammaLds / 8 / kTcThreads : 1;
+    half8 gam_r[kGamPt];
+    if (GL) {
+#pragma unroll
+        for (int e = 0; e < kGamPt; ++e)
+            gam_r[e] = load_half8(p.gamma + min(k_begin + (tid + e * kTcThreads) * 8, k_end - 8));
+    }
+    // MODE 3: previous probabilities and parents are requested now and parked in LDS after the merge,
+    // whose own wait for the ids then covers them (clamped addresses: no branch around a load)
+    constexpr int kPrevPt = MODE == 3 ? kTcFusedMax / kTcThreads : 1;
+    float prev_r[kPrevPt];
+    int par_r = -1;
     if (MODE == 3) {
         const int n_ids = p.N * p.K;
-        for (int i = tid; i < n_ids; i += kTcThreads) prev_lds[i] = f.prev[(size_t)g * n_ids + i];
+#pragma unroll
+        for (int e = 0; e < kPrevPt; ++e) prev_r[e] = f.prev[(size_t)g * n_ids + min(tid + e * kTcThreads, n_ids - 1)];
+        const int32_t *pp = f.path_exit ? f.parent + (size_t)g * p.N + min(tid, p.N - 1) : p.ids;
+        par_r = *pp;
         if (tid < 64) bad_lds[tid] = 0;
-        if (f.path_exit && tid < p.N) par_lds[tid] = f.parent[(size_t)g * p.N + tid];
     }
 
     // ---- merged rows
@@ -121,9 +142,9 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     int32_t *uniq = nullptr;
     if (FUSED) {
         const int n_ids = p.N * p.K;
-        int col_of[kMergePerThread];
+        int col_of[kMergePerThread], own_id[kMergePerThread];
         const int Mtrue = merge_block<kTcThreads>(p.ids + (size_t)g * n_ids, n_ids, reinterpret_cast<int32_t *>(smem),
-                                                  uniq, col_of);
+                                                  uniq, col_of, own_id);
         if (blockIdx.x == 0 && blockIdx.y == 0 && nb == 0) {
             if (tid == 0) p.M_out[g] = Mtrue;
             for (int m = tid; m < p.Mcap; m += kTcThreads)
@@ -140,10 +161,13 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
                 const int i = tid + e * kTcThreads;
                 if (i < n_ids) {
                     cols_lds[i] = col_of[e];
-                    const int id = p.ids[(size_t)g * n_ids + i];
-                    if (id < 0 || id >= p.V) bad_lds[i / p.K] = 1;  // benign race: every writer stores 1
+                    if (own_id[e] < 0 || own_id[e] >= p.V) bad_lds[i / p.K] = 1;  // benign race: all writers store 1
                 }
             }
+#pragma unroll
+            for (int e = 0; e < kPrevPt; ++e)
+                if (tid + e * kTcThreads < n_ids) prev_lds[tid + e * kTcThreads] = prev_r[e];
+            if (f.path_exit && tid < p.N) par_lds[tid] = par_r;
         }
         M = Mtrue;
     } else {
@@ -172,6 +196,14 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
         }
         arow[i] = p.lm_head + (size_t)row * d;
     }
+    if (GL) {
+        static_assert(!GL || FUSED, "the barrier below publishes the staged weight");
+#pragma unroll
+        for (int e = 0; e < kGamPt; ++e) {
+            const int idx = (tid + e * kTcThreads) * 8;
+            if (idx < k_end - k_begin) *reinterpret_cast<half8 *>(&gam_lds[idx]) = gam_r[e];
+        }
+    }
     if (FUSED) __syncthreads();  // the merge scratch becomes the row tile buffers
     half8 a_buf[PD][APT];
     auto issue_a = [&](int kc, int slot) {
@@ -187,18 +219,23 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
 #pragma unroll
     for (int u = 0; u < PD; ++u) issue_a(u, u);
 
-    // MODE 3: the predictor goes to LDS after the contraction (into the part of the row-tile buffers
-    // that the logits leave free, when it fits).  Its first kMlpPf vectors per thread are requested
-    // here and ride in registers through the stage loop, so that the scoring phase does not start
-    // with a round trip to memory.
-    constexpr int kMlpPf = 2;
+    // MODE 3: for the matrix-core MLP the predictor goes to LDS after the contraction, as a padded
+    // image in the part of the row-tile buffers that the logits leave free (when it fits).  Up to
+    // kMlpPf vectors per thread are requested here and ride in registers through the stage loop, so
+    // that the scoring phase does not start with a round trip to memory.
+    constexpr int kMlpPf = 1024 / kTcThreads;
     constexpr size_t kMlpFree = sizeof(half_t) * kALdsHalves - sizeof(float) * 64 * ROWS;
     const bool mfma_mlp = MODE == 3 && KC <= 8 && mlp_mfma_ok(p.K, f.H);
-    const bool mlp_in_lds = mfma_mlp && (size_t)mlp_lds_halves(p.K, f.H) * sizeof(half_t) <= kMlpFree;
-    half8 mlp_pf[kMlpPf];
-    if (MODE == 3 && mlp_in_lds) {
+    // only these instances carry the code (with eight row tiles the logits leave next to nothing free)
+    constexpr bool kPadded = MODE == 3 && MT == 4 && 3 * KC + 1 <= kMlpPad;
+    const bool mlp_in_lds = kPadded && mfma_mlp && mlp_padded_ok(p.K, f.H) &&
+                            (size_t)mlp_padded_halves(f.H) * sizeof(half_t) <= kMlpFree;
+    half8 mlp_pf[kPadded ? kMlpPf : 1], w2_pf;
+    if (kPadded) {  // unconditional loads (a branch here would drain the stage prefetch at its join)
 #pragma unroll
-        for (int e = 0; e < kMlpPf; ++e) mlp_pf[e] = mlp_vector(f, tid + e * kTcThreads);
+        for (int e = 0; e < kMlpPf; ++e)
+            mlp_pf[e] = mlp_padded_vector(f, tid + e * kTcThreads, mlp_in_lds, p.gamma);
+        w2_pf = load_half8(mlp_in_lds ? f.w2 + (size_t)min(tid, f.H / 8 - 1) * 8 : p.gamma);
     }
 
     floatx4 acc[MT];
@@ -224,10 +261,15 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     // x = h*gamma split exactly into hi = round(h*gamma), lo = round(fma(h, gamma, -hi))
     auto build_b = [&](int kc, int slot, int j, half8 &hi, half8 &lo) {
         const half8 hsel = b_valid(kc, j) ? h_buf[slot][j] : zero_half8();
+        half8 gvec;
+        if (GL)  // stages past the end read the slice's tail: in bounds, and hsel is zero there
+            gvec = *reinterpret_cast<const half8 *>(&gam_lds[min(kc * kTcKC + koff(j), k_end - k_begin - 8)]);
+        else
+            gvec = g_buf[slot][j];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const half2_t hh = {hsel[2 * e], hsel[2 * e + 1]};
-            const half2_t gg = {g_buf[slot][j][2 * e], g_buf[slot][j][2 * e + 1]};
+            const half2_t gg = {gvec[2 * e], gvec[2 * e + 1]};
             const half2_t x = hh * gg;
             const half2_t rres = __builtin_elementwise_fma(hh, gg, -x);
             ssq = __builtin_amdgcn_fdot2(hh, hh, ssq, false);
@@ -388,16 +430,16 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     const int K = p.K, N = p.N;
     if (mfma_mlp) {
         // the copy of the predictor is published by the barrier after the features are written
-        TreeFinishParams fl = f;
-        if (mlp_in_lds) {
-            half_t *dst = reinterpret_cast<half_t *>(Zl + 64 * ROWS);
-            const int nvec = mlp_lds_halves(K, f.H) / 8;
+        half_t *img = reinterpret_cast<half_t *>(Zl + 64 * ROWS);
+        if (kPadded && mlp_in_lds) {
+            half8 *img8 = reinterpret_cast<half8 *>(img);
+            const int nrowvec = 2 * f.H;
 #pragma unroll
             for (int e = 0; e < kMlpPf; ++e)
-                if (tid + e * kTcThreads < nvec) reinterpret_cast<half8 *>(dst)[tid + e * kTcThreads] = mlp_pf[e];
-            for (int i = tid + kMlpPf * kTcThreads; i < nvec; i += kTcThreads)
-                reinterpret_cast<half8 *>(dst)[i] = mlp_vector(f, i);
-            fl = mlp_params_at(dst, f);
+                if (tid + e * kTcThreads < nrowvec) img8[tid + e * kTcThreads] = mlp_pf[e];
+            for (int i = tid + kMlpPf * kTcThreads; i < nrowvec; i += kTcThreads) img8[i] = mlp_padded_vector(f, i, true, p.gamma);
+            if (tid < f.H / 8) img8[nrowvec + tid] = w2_pf;
+            if (tid == 0) img8[nrowvec + f.H / 8] = zero_half8();
         }
         // lanes q == 0 build the features of node c; all lanes then feed the matrix cores
         float *F = feat_lds + nt_w * 16 * kMlpFeat;
@@ -429,6 +471,7 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
                     F[c * kMlpFeat + 2 * K + k] = pr[k] - pv;
                 }
             for (int t = 3 * K; t < kMlpFeat; ++t) F[c * kMlpFeat + t] = 0.f;
+            if (kPadded && mlp_in_lds) F[c * kMlpFeat + 3 * K] = 1.f;  // the bias column of the padded image
         }
         __syncthreads();
         // the two wavefronts of a node tile take half of the hidden units each
@@ -437,8 +480,8 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
         const int per = split ? htiles >> 1 : htiles;
         float u = 0.f;
         if (kh == 0 || split)
-            u = mlp_in_lds ? mlp_mfma_16<true>(F, fl, lane, split ? kh * per : 0, per)
-                           : mlp_mfma_16<false>(F, fl, lane, split ? kh * per : 0, per);
+            u = (kPadded && mlp_in_lds) ? mlp_mfma_16_padded(F, img, f.H, lane, split ? kh * per : 0, per)
+                                        : mlp_mfma_16<false>(F, f, lane, split ? kh * per : 0, per);
         if (KH == 2 && split) {
             if (kh == 1 && q == 0) ssq_lds[n] = u;
             __syncthreads();
@@ -516,27 +559,33 @@ bool tree_whole_supported(int N, int K, int Mcap) {
 // node tile) when each CU gets at most one workgroup, 256 threads when there are more workgroups
 // than CUs, because two of those fit on a CU and one's prologue and scoring overlap the other's
 // streaming.  65..128 merged rows: 256 threads, eight row tiles.
-template <int MT, int KC>
+template <int MT, int KC, bool GL>
 static void launch_whole(const GemmParams &p, const TreeFinishParams &f, int G, hipStream_t st) {
     const dim3 grid(p.S, 1, G);
     if constexpr (MT == 4) {
         if ((long long)G * p.S <= kWholeWideMaxWgs)
-            hipLaunchKernelGGL((tree_contract_kernel<4, 3, true, 2, KC, 128, 512>), grid, dim3(512), 0, st, p, f);
+            hipLaunchKernelGGL((tree_contract_kernel<4, 3, true, 2, KC, 128, 512, GL>), grid, dim3(512), 0, st, p, f);
         else
-            hipLaunchKernelGGL((tree_contract_kernel<4, 3, true, 4, KC, 64, 256>), grid, dim3(256), 0, st, p, f);
+            hipLaunchKernelGGL((tree_contract_kernel<4, 3, true, 4, KC, 64, 256, GL>), grid, dim3(256), 0, st, p, f);
     } else {
-        hipLaunchKernelGGL((tree_contract_kernel<8, 3, true, 4, KC, 64, 256>), grid, dim3(256), 0, st, p, f);
+        hipLaunchKernelGGL((tree_contract_kernel<8, 3, true, 4, KC, 64, 256, GL>), grid, dim3(256), 0, st, p, f);
     }
+}
+
+template <int MT, int KC>
+static void launch_whole_gl(const GemmParams &p, const TreeFinishParams &f, int G, hipStream_t st) {
+    if (p.dslice <= kGammaLds) launch_whole<MT, KC, true>(p, f, G, st);
+    else launch_whole<MT, KC, false>(p, f, G, st);
 }
 
 hipError_t launch_tree_whole(const GemmParams &p, const TreeFinishParams &f, int G, hipStream_t st) {
     const bool wide = p.Mcap > 64;
     if (f.K <= 4) {
-        if (wide) launch_whole<8, 4>(p, f, G, st); else launch_whole<4, 4>(p, f, G, st);
+        if (wide) launch_whole_gl<8, 4>(p, f, G, st); else launch_whole_gl<4, 4>(p, f, G, st);
     } else if (f.K <= 8) {
-        if (wide) launch_whole<8, 8>(p, f, G, st); else launch_whole<4, 8>(p, f, G, st);
+        if (wide) launch_whole_gl<8, 8>(p, f, G, st); else launch_whole_gl<4, 8>(p, f, G, st);
     } else {
-        if (wide) launch_whole<8, 16>(p, f, G, st); else launch_whole<4, 16>(p, f, G, st);
+        if (wide) launch_whole_gl<8, 16>(p, f, G, st); else launch_whole_gl<4, 16>(p, f, G, st);
     }
     return hipGetLastError();
 }

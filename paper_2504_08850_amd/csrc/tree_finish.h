@@ -188,6 +188,86 @@ __device__ __forceinline__ TreeFinishParams stage_mlp_to_lds(half_t *dst, const 
     return mlp_params_at(dst, f);
 }
 
+// Padded LDS image of the predictor for K <= 5 (3K + 1 <= 16): W1 rows padded to 16 halves with
+// b1 in column 3K (the features carry a constant 1 there) and zeros after it, then w2 [H], then 16
+// zero bytes.  A row is then one aligned 16-byte LDS read per k-slot group with nothing to mask, and
+// the bias costs no instruction.  16 * H / 8 vectors of W1 rows, H / 8 of w2.
+constexpr int kMlpPad = 16;
+__host__ __device__ inline int mlp_padded_halves(int H) {
+    return H * kMlpPad + H + 8;
+}
+__host__ __device__ inline bool mlp_padded_ok(int K, int H) {
+    return 3 * K + 1 <= kMlpPad && (K & 3) == 0 && (H & 63) == 0;
+}
+// Vector i (two per row) of the padded W1 rows, from global memory.  Free of branches, so that it
+// can be issued among other outstanding loads: i is clamped into the image, and with on == false
+// (the image is not going to be used) every load goes to `safe`, any valid 16 bytes.
+__device__ __forceinline__ half8 mlp_padded_vector(const TreeFinishParams &f, int i, bool on, const half_t *safe) {
+    const int K3 = on ? 3 * f.K : 4;
+    i = min(i, 2 * f.H - 1);
+    const int j = i >> 1, part = i & 1;
+    const half_t *row = on ? f.W1 + (size_t)j * K3 : safe;
+    const half_t bias_raw = *((on && f.b1) ? f.b1 + j : safe);
+    const half_t bias = f.b1 ? bias_raw : (half_t)0.f;
+    half8 v;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int col0 = part * 8 + 4 * h;
+        const half4 w = *reinterpret_cast<const half4 *>(row + min(col0, K3 - 4));
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            half_t x = (half_t)0.f;
+            if (col0 + 4 <= K3) x = w[e];
+            else if (col0 + e == K3) x = bias;
+            v[4 * h + e] = x;
+        }
+    }
+    return v;
+}
+// Same contract as mlp_mfma_16, on the padded image at img (LDS); F must hold 1.0 in slot 3K.
+__device__ __forceinline__ float mlp_mfma_16_padded(const float *F, const half_t *img, int H, int lane, int ht_begin,
+                                                    int ht_count) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef const __attribute__((address_space(3))) half8 *lds_half8_ptr;
+    typedef const __attribute__((address_space(3))) half4 *lds_half4_ptr;
+    const int c = lane & 15, q = lane >> 4;
+    half8 bhi, blo;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float v = F[c * kMlpFeat + q * 8 + e];
+        const half_t h = (half_t)v;
+        bhi[e] = h;
+        blo[e] = (half_t)(v - (float)h);
+    }
+    // lane groups q >= 2 hold k-slots 16..31, which the padded rows do not have: they read the zero block
+    const bool live = q * 8 < kMlpPad;
+    const half_t *ap = live ? img + (size_t)(ht_begin * 16 + c) * kMlpPad + q * 8 : img + (size_t)H * kMlpPad + H;
+    const int astep = live ? 16 * kMlpPad : 0;
+    const half_t *wp = img + (size_t)H * kMlpPad + ht_begin * 16 + 4 * q;
+    float acc0 = 0.f, acc1 = 0.f;
+    for (int t0 = 0; t0 < ht_count; t0 += 4) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const half8 a = *(lds_half8_ptr)(ap + (size_t)(t0 + t) * astep);
+            const half4 w2v = *(lds_half4_ptr)(wp + (t0 + t) * 16);
+            floatx4 dacc = {0.f, 0.f, 0.f, 0.f};
+            dacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bhi, dacc, 0, 0, 0);
+            dacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, blo, dacc, 0, 0, 0);
+            float &acc = (t & 1) ? acc1 : acc0;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc += (float)w2v[r] * fmaxf(dacc[r], 0.f);
+        }
+    }
+    float acc_u = acc0 + acc1;
+    acc_u += __shfl_xor(acc_u, 16, kWave);
+    acc_u += __shfl_xor(acc_u, 32, kWave);
+    return acc_u;
+#else
+    (void)F; (void)img; (void)H; (void)lane; (void)ht_begin; (void)ht_count;
+    return 0.f;
+#endif
+}
+
 // Path rule from exit flags in LDS (paper Sec. 6.2): a token path exits only if every token on it
 // exits.  Parents precede children, so at most N steps; a malformed parent refuses the path.
 __device__ __forceinline__ void finish_paths(const int32_t *exit_lds, const int32_t *par, int N, int tid,
