@@ -92,12 +92,18 @@ typedef enum specee_op {
  *   prev_probs [B][K] fp32 (local probabilities of the last layer that ran a
  *   predictor; zeros for the first).
  *   logits [B][K], probs [B][K], scores [B] fp32; exit_flags [B] int32 (0/1).
+ * done (optional, device, [B]): tokens that already left the model at an earlier
+ * layer (done[b] != 0, as maintained by specee_verify) are skipped on the device:
+ * their LM-head rows are not read, logits are 0, probs repeat prev_probs (so the
+ * layer-to-layer chain stays defined), score 0 and exit flag 0.  With done and
+ * the gate of specee_verify a whole layer loop (predict -> verify -> next layer)
+ * runs from one HIP graph without the host looking at a flag.
  * probs must not alias prev_probs.  Needs no workspace.
  */
 int specee_predict(const specee_dims *dims, int B, const specee_half *hidden, const specee_half *gamma,
                    const specee_half *lm_head, const int32_t *ids, const float *prev_probs,
-                   const specee_mlp *mlp /* HOST struct of device pointers */, float *logits, float *probs,
-                   float *scores, int32_t *exit_flags, void *stream);
+                   const specee_mlp *mlp /* HOST struct of device pointers */, const int32_t *done /* [B] or NULL */,
+                   float *logits, float *probs, float *scores, int32_t *exit_flags, void *stream);
 
 /*
  * All L layers of B tokens in one call: layer l uses hidden[l], predictor l and
@@ -159,12 +165,16 @@ int lm_head_gemv(const specee_dims *dims, int N, const specee_half *hidden, cons
  * are skipped on the device -- token -1, max_logit 0, hit 0 -- and when no state
  * of a launch is gated in, the pass over the LM head is not made at all.  This
  * keeps the predict -> verify sequence free of host round trips.
+ * done (optional, in/out): states with done[n] != 0 are skipped like gated-off
+ * ones; where the verification hits, done[n] is set to 1 (the token leaves the
+ * model here, Sec. 4.3.3), which switches off this token's later predict and
+ * verify calls that are given the same array.
  * Workspace: SPECEE_OP_VERIFY with n = N.
  */
 int specee_verify(const specee_dims *dims, int N, const specee_half *hidden, const specee_half *gamma,
                   const specee_half *lm_head, const int32_t *ids, const int32_t *gate /* [N] or NULL */,
-                  int32_t *token, float *max_logit, int32_t *hit, void *workspace, size_t workspace_bytes,
-                  void *stream);
+                  int32_t *done /* [N] or NULL */, int32_t *token, float *max_logit, int32_t *hit, void *workspace,
+                  size_t workspace_bytes, void *stream);
 
 /* Bytes of device workspace `op` needs for n tokens / nodes (Mcap: tree only).
  * Pure host function; 0 means none; (size_t)-1 means invalid arguments. */

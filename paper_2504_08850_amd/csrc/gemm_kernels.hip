@@ -47,11 +47,12 @@ __global__ __launch_bounds__(kGemmThreads) void full_head_gemm_kernel(GemmParams
     const int c = lane & 15, q = lane >> 4;
     const int n0 = blockIdx.z * kNB;
     const int d = p.d, M = p.V;
-    if (MODE == 2 && p.gate) {
+    if (MODE == 2 && (p.gate || p.done)) {
         // verification is gated by the predictor's exit flags: when none of this block's hidden states
         // is to be verified the pass over the LM head is skipped (the tail kernel fills in the outputs)
         int any = 0;
-        if (tid < kNB && n0 + tid < p.N) any = p.gate[n0 + tid] != 0;
+        if (tid < kNB && n0 + tid < p.N)
+            any = (!p.gate || p.gate[n0 + tid] != 0) && (!p.done || p.done[n0 + tid] == 0);
         if (__syncthreads_or(any) == 0) return;
     }
     const int nchunks = (d + kKC - 1) / kKC;
@@ -286,11 +287,12 @@ hipError_t launch_lm_head_gemm(int d, int V, float eps, int N, const half_t *hid
 
 hipError_t launch_lm_head_argmax_gemm(int d, int V, float eps, int N, const half_t *hidden, const half_t *gamma,
                                       const half_t *lm_head, float *best_val, int32_t *best_idx, const int32_t *gate,
-                                      hipStream_t st) {
+                                      const int32_t *done, hipStream_t st) {
     GemmParams p = full_head_params(d, V, eps, N, hidden, gamma, lm_head);
     p.best_val = best_val;
     p.best_idx = best_idx;
     p.gate = gate;
+    p.done = done;
     return launch_stream<2>(p, st);
 }
 

@@ -21,6 +21,7 @@ struct PredictParams {
     const float *prev;      // [B][K] or null
     const half_t *W1, *b1, *w2, *b2;  // leading layer dimension L
     const int32_t *active;  // [L] or null (sweep only)
+    const int32_t *done;    // [B] or null (single layer only): tokens to skip
     float *logits, *probs, *scores;
     int32_t *exit_flags;
 };
@@ -47,6 +48,7 @@ struct GemmParams {
     float *best_val;         // arg-max mode: [N][gridDim.x] candidates
     int32_t *best_idx;
     const int32_t *gate;     // arg-max mode: [N] or null; states with gate == 0 are not verified
+    const int32_t *done;     // arg-max mode: [N] or null; states with done != 0 are not verified
     // fused merge (tree, N*K <= 1024): the kernel merges ids itself and workgroup (0,0) of each tree
     // publishes the results
     const int32_t *ids;      // [G][N][K] or null (rowlist / Mptr are then inputs)
@@ -95,12 +97,12 @@ int lm_head_gemv_workgroups(int V);
 int lm_head_gemm_workgroups(int V);
 hipError_t launch_lm_head_argmax_gemv(int d, int V, float eps, int N, const half_t *hidden, const half_t *gamma,
                                       const half_t *lm_head, float *best_val, int32_t *best_idx, const int32_t *gate,
-                                      hipStream_t s);
+                                      const int32_t *done, hipStream_t s);
 hipError_t launch_lm_head_argmax_gemm(int d, int V, float eps, int N, const half_t *hidden, const half_t *gamma,
                                       const half_t *lm_head, float *best_val, int32_t *best_idx, const int32_t *gate,
-                                      hipStream_t s);
+                                      const int32_t *done, hipStream_t s);
 hipError_t launch_verify_finish(const float *best_val, const int32_t *best_idx, int P, int N, const int32_t *ids,
-                                int K, const int32_t *gate, int32_t *token, float *max_logit, int32_t *hit,
-                                hipStream_t s);
+                                int K, const int32_t *gate, int32_t *done, int32_t *token, float *max_logit,
+                                int32_t *hit, hipStream_t s);
 
 }  // namespace specee

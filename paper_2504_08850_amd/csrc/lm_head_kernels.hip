@@ -38,13 +38,15 @@ template <bool ARGMAX>
 __global__ __launch_bounds__(kGemvThreads) void lm_head_gemv_kernel(int d, int V, float eps, const half_t *hidden,
                                                                     const half_t *gamma, const half_t *lm_head,
                                                                     float *out, int rows_per_wg, float *best_val,
-                                                                    int32_t *best_idx, const int32_t *gate) {
+                                                                    int32_t *best_idx, const int32_t *gate,
+                                                                    const int32_t *done) {
     extern __shared__ float4 lds_x[];  // [2][nv]: plane 0 = elements 0..3 of each vector, plane 1 = 4..7
     __shared__ float red[kGemvWaves];
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
     const int nv = d >> 3;
     const int n = blockIdx.y;
-    if (ARGMAX && gate && gate[n] == 0) return;  // uniform: this hidden state is not being verified
+    // uniform over the workgroup: this hidden state is not being verified
+    if (ARGMAX && ((gate && gate[n] == 0) || (done && done[n] != 0))) return;
     floatx4 *xa = reinterpret_cast<floatx4 *>(lds_x);
     floatx4 *xb = xa + nv;
 
@@ -148,11 +150,12 @@ __global__ __launch_bounds__(kGemvThreads) void lm_head_gemv_kernel(int d, int V
 // into the arg-max token (lowest id on ties) and test membership in the K ids.
 __global__ __launch_bounds__(256) void verify_finish_kernel(const float *best_val, const int32_t *best_idx, int P,
                                                             const int32_t *ids, int K, const int32_t *gate,
-                                                            int32_t *token, float *max_logit, int32_t *hit) {
+                                                            int32_t *done, int32_t *token, float *max_logit,
+                                                            int32_t *hit) {
     __shared__ float wv[4];
     __shared__ int wi[4];
     const int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (gate && gate[n] == 0) {  // not verified: no candidates were written for this state
+    if ((gate && gate[n] == 0) || (done && done[n] != 0)) {  // not verified: no candidates were written
         if (tid == 0) {
             token[n] = -1;
             max_logit[n] = 0.f;
@@ -188,6 +191,7 @@ __global__ __launch_bounds__(256) void verify_finish_kernel(const float *best_va
         token[n] = bi;
         max_logit[n] = bv;
         hit[n] = h;
+        if (done && h) done[n] = 1;  // the token leaves the model at this layer
     }
 }
 
@@ -201,7 +205,7 @@ hipError_t launch_lm_head_gemv(int d, int V, float eps, int N, const half_t *hid
     wgs = (V + rows_per_wg - 1) / rows_per_wg;
     size_t lds = (size_t)d * sizeof(float);
     hipLaunchKernelGGL(lm_head_gemv_kernel<false>, dim3(wgs, N), dim3(kGemvThreads), lds, s, d, V, eps, hidden,
-                       gamma, lm_head, out, rows_per_wg, nullptr, nullptr, nullptr);
+                       gamma, lm_head, out, rows_per_wg, nullptr, nullptr, nullptr, nullptr);
     return hipGetLastError();
 }
 
@@ -215,22 +219,22 @@ int lm_head_gemv_workgroups(int V) {
 
 hipError_t launch_lm_head_argmax_gemv(int d, int V, float eps, int N, const half_t *hidden, const half_t *gamma,
                                       const half_t *lm_head, float *best_val, int32_t *best_idx, const int32_t *gate,
-                                      hipStream_t s) {
+                                      const int32_t *done, hipStream_t s) {
     int wgs = lm_head_gemv_workgroups(V);
     int rows_per_wg = (V + wgs - 1) / wgs;
     const int quantum = kGemvWaves * kGemvRows;
     rows_per_wg = ((rows_per_wg + quantum - 1) / quantum) * quantum;
     size_t lds = (size_t)d * sizeof(float);
     hipLaunchKernelGGL(lm_head_gemv_kernel<true>, dim3(wgs, N), dim3(kGemvThreads), lds, s, d, V, eps, hidden,
-                       gamma, lm_head, nullptr, rows_per_wg, best_val, best_idx, gate);
+                       gamma, lm_head, nullptr, rows_per_wg, best_val, best_idx, gate, done);
     return hipGetLastError();
 }
 
 hipError_t launch_verify_finish(const float *best_val, const int32_t *best_idx, int P, int N, const int32_t *ids,
-                                int K, const int32_t *gate, int32_t *token, float *max_logit, int32_t *hit,
-                                hipStream_t s) {
-    hipLaunchKernelGGL(verify_finish_kernel, dim3(N), dim3(256), 0, s, best_val, best_idx, P, ids, K, gate, token,
-                       max_logit, hit);
+                                int K, const int32_t *gate, int32_t *done, int32_t *token, float *max_logit,
+                                int32_t *hit, hipStream_t s) {
+    hipLaunchKernelGGL(verify_finish_kernel, dim3(N), dim3(256), 0, s, best_val, best_idx, P, ids, K, gate, done,
+                       token, max_logit, hit);
     return hipGetLastError();
 }
 

@@ -91,6 +91,9 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(PredictParams 
     }
 
     // ---- the K speculative LM-head rows
+    // The token's done flag travels with the ids (same trip to memory), so looking at it costs the
+    // live tokens nothing; a token that already left the model stops here, before the rows are read.
+    const int dn = (!SWEEP && p.done) ? p.done[b] : 0;
     const half_t *rows[KC];
     bool bad_id = false;
 #pragma unroll
@@ -99,6 +102,17 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(PredictParams 
         bool ok = id >= 0 && id < p.V;
         if (k < K && !ok) bad_id = true;
         rows[k] = p.lm_head + (size_t)(ok ? id : 0) * d;
+    }
+    if (!SWEEP && dn != 0) {  // uniform over the workgroup
+        if (tid < K) {
+            p.logits[tok * K + tid] = 0.f;
+            p.probs[tok * K + tid] = p.prev[(size_t)b * K + tid];
+        }
+        if (tid == 0) {
+            p.scores[tok] = 0.f;
+            p.exit_flags[tok] = 0;
+        }
+        return;
     }
     half8 wv[KC][VPT];
 #pragma unroll

@@ -124,7 +124,8 @@ size_t specee_workspace_bytes(int op, const specee_dims *dm, int n, int Mcap) {
 
 int specee_predict(const specee_dims *dm, int B, const specee_half *hidden, const specee_half *gamma,
                    const specee_half *lm_head, const int32_t *ids, const float *prev_probs, const specee_mlp *mlp,
-                   float *logits, float *probs, float *scores, int32_t *exit_flags, void *stream) {
+                   const int32_t *done, float *logits, float *probs, float *scores, int32_t *exit_flags,
+                   void *stream) {
     int rc = check_dims(dm, true);
     if (rc) return rc;
     if (B < 0) return SPECEE_EINVAL;
@@ -140,6 +141,7 @@ int specee_predict(const specee_dims *dm, int B, const specee_half *hidden, cons
     p.hidden = H(hidden); p.gamma = H(gamma); p.lm_head = H(lm_head); p.ids = ids; p.prev = prev_probs;
     p.W1 = H(mlp->W1); p.b1 = H(mlp->b1); p.w2 = H(mlp->w2); p.b2 = H(mlp->b2);
     p.active = nullptr;
+    p.done = done;
     p.logits = logits; p.probs = probs; p.scores = scores; p.exit_flags = exit_flags;
     return launch_predict(p, static_cast<hipStream_t>(stream)) == hipSuccess ? SPECEE_OK : SPECEE_EHIP;
 }
@@ -271,8 +273,9 @@ int specee_predict_tree(const specee_dims *dm, int G, int N, int Mcap, const spe
 }
 
 int specee_verify(const specee_dims *dm, int N, const specee_half *hidden, const specee_half *gamma,
-                  const specee_half *lm_head, const int32_t *ids, const int32_t *gate, int32_t *token,
-                  float *max_logit, int32_t *hit, void *workspace, size_t workspace_bytes, void *stream) {
+                  const specee_half *lm_head, const int32_t *ids, const int32_t *gate, int32_t *done,
+                  int32_t *token, float *max_logit, int32_t *hit, void *workspace, size_t workspace_bytes,
+                  void *stream) {
     int rc = check_dims(dm, false);
     if (rc) return rc;
     if (N < 0 || N > 65535 || dm->K < 1 || dm->K > SPECEE_KMAX) return SPECEE_EINVAL;
@@ -287,11 +290,11 @@ int specee_verify(const specee_dims *dm, int N, const specee_half *hidden, const
     int32_t *best_idx = reinterpret_cast<int32_t *>(static_cast<char *>(workspace) + half_ws);
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e = vec ? launch_lm_head_argmax_gemv(dm->d, dm->V, dm->eps, N, H(hidden), H(gamma), H(lm_head),
-                                                    best_val, best_idx, gate, st)
+                                                    best_val, best_idx, gate, done, st)
                        : launch_lm_head_argmax_gemm(dm->d, dm->V, dm->eps, N, H(hidden), H(gamma), H(lm_head),
-                                                    best_val, best_idx, gate, st);
+                                                    best_val, best_idx, gate, done, st);
     if (e != hipSuccess) return SPECEE_EHIP;
-    e = launch_verify_finish(best_val, best_idx, P, N, ids, dm->K, gate, token, max_logit, hit, st);
+    e = launch_verify_finish(best_val, best_idx, P, N, ids, dm->K, gate, done, token, max_logit, hit, st);
     return e == hipSuccess ? SPECEE_OK : SPECEE_EHIP;
 }
 

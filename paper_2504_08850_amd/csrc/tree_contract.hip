@@ -280,6 +280,38 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
         }
     };
     const int nstages = ((nchunks + PD - 1) / PD) * PD;
+    if constexpr (MODE == 0) {
+        // d-slices of a stage or two: nothing to pipeline, so stage by stage (operand build, barrier,
+        // matrix instructions) without the extra trip of a pipelined loop
+        int buf = 0;
+        for (int kc0 = 0; kc0 < nstages; kc0 += PD) {
+#pragma unroll
+            for (int u = 0; u < PD; ++u) {
+                const int kc = kc0 + u;
+                half8 bhi[JN], blo[JN];
+                tile_to_lds(kc, u, buf);
+#pragma unroll
+                for (int j = 0; j < JN; ++j) build_b(kc, u, j, bhi[j], blo[j]);
+                __syncthreads();
+                issue_a(kc + PD, u);
+                issue_b(kc + PD, u);
+#pragma unroll
+                for (int j = 0; j < JN; ++j) {
+                    half8 a[MT];
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+                        a[mt] = *reinterpret_cast<const half8 *>(&a_lds[buf][mt * 16 + c][koff(j)]);
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+                        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], bhi[j], acc[mt], 0, 0, 0);
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+                        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], blo[j], acc[mt], 0, 0, 0);
+                }
+                buf ^= 1;
+            }
+        }
+    } else {
     half8 bhi[JN], blo[JN];
     tile_to_lds(0, 0, 0);
 #pragma unroll
@@ -321,6 +353,7 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
             }
             buf ^= 1;
         }
+    }
     }
     // sum of squares of node c over this k-range: combine the four k-slot groups
     ssq += __shfl_xor(ssq, 16, kWave);

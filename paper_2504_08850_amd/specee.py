@@ -93,8 +93,9 @@ def _workspace(op, dims, n, Mcap, workspace, device):
 
 
 def predict(hidden, gamma, lm_head, ids, prev_probs, W1, w2, b1=None, b2=None, eps=1e-5, threshold=0.5,
-            out=None, stream=None):
-    """specee_predict: B tokens at one layer.  Returns dict(logits, probs, scores, exit)."""
+            out=None, stream=None, done=None):
+    """specee_predict: B tokens at one layer.  Returns dict(logits, probs, scores, exit).  `done` ([B] int32):
+    tokens with a non-zero entry are skipped on the device."""
     B, d = hidden.shape
     V = lm_head.shape[0]
     K = ids.shape[1]
@@ -110,7 +111,7 @@ def predict(hidden, gamma, lm_head, ids, prev_probs, W1, w2, b1=None, b2=None, e
     f16 = torch.float16
     rc = lib().specee_predict(C.byref(dims), C.c_int(B), _ptr(hidden, f16), _ptr(gamma, f16), _ptr(lm_head, f16),
                               _ptr(ids, torch.int32), _ptr(prev_probs, torch.float32), C.byref(mlp),
-                              _ptr(out["logits"]), _ptr(out["probs"]), _ptr(out["scores"]), _ptr(out["exit"]),
+                              _ptr(done, torch.int32), _ptr(out["logits"]), _ptr(out["probs"]), _ptr(out["scores"]), _ptr(out["exit"]),
                               _stream(stream))
     if rc:
         raise SpeceeError("specee_predict", rc)
@@ -202,9 +203,10 @@ def lm_head_gemv(hidden, gamma, lm_head, eps=1e-5, out=None, workspace=None, str
     return out
 
 
-def verify(hidden, gamma, lm_head, ids, gate=None, eps=1e-5, out=None, workspace=None, stream=None):
+def verify(hidden, gamma, lm_head, ids, gate=None, eps=1e-5, out=None, workspace=None, stream=None, done=None):
     """specee_verify: arg-max token of the full head and membership in the K ids; `gate` ([N] int32, e.g.
-    the predictor's exit flags) skips hidden states whose entry is 0 on the device."""
+    the predictor's exit flags) skips hidden states whose entry is 0 on the device; `done` ([N] int32, in/out)
+    skips states whose entry is non-zero and is set to 1 where the verification hits."""
     N, d = hidden.shape
     V = lm_head.shape[0]
     K = ids.shape[1]
@@ -217,7 +219,8 @@ def verify(hidden, gamma, lm_head, ids, gate=None, eps=1e-5, out=None, workspace
     workspace, wbytes = _workspace(OP_VERIFY, dims, N, 0, workspace, dev)
     f16 = torch.float16
     rc = lib().specee_verify(C.byref(dims), C.c_int(N), _ptr(hidden, f16), _ptr(gamma, f16), _ptr(lm_head, f16),
-                             _ptr(ids, torch.int32), _ptr(gate, torch.int32), _ptr(out["token"]),
+                             _ptr(ids, torch.int32), _ptr(gate, torch.int32), _ptr(done, torch.int32),
+                             _ptr(out["token"]),
                              _ptr(out["max_logit"]), _ptr(out["hit"]),
                              _ptr(workspace), wbytes, _stream(stream))
     if rc:

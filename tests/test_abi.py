@@ -72,7 +72,7 @@ def test_host_side_validation_without_a_gpu(sp):
     other = C.c_void_p(0x2000)
 
     def predict(dm=None, B=1, hidden=fake, mlp_=C.byref(mlp), probs=other, prev=fake):
-        return lib.specee_predict(dm, B, hidden, fake, fake, fake, prev, mlp_, fake, probs, fake, fake, None)
+        return lib.specee_predict(dm, B, hidden, fake, fake, fake, prev, mlp_, None, fake, probs, fake, fake, None)
 
     ok = sp.Dims(4096, 32000, 4, 512, 1e-5, 0.5)
     for dm in bad_dims:
@@ -83,7 +83,8 @@ def test_host_side_validation_without_a_gpu(sp):
     assert predict(C.byref(ok), hidden=odd) == -2
     assert predict(C.byref(ok), mlp_=None) == -1
     assert predict(C.byref(ok), probs=fake, prev=fake) == -1          # probs aliases prev_probs
-    assert lib.specee_predict(C.byref(ok), 0, None, None, None, None, None, None, None, None, None, None, None) == 0
+    assert lib.specee_predict(C.byref(ok), 0, None, None, None, None, None, None, None, None, None, None, None,
+                              None) == 0
     # tree: limits and workspace
     args = (fake,) * 3 + (fake, None, fake, C.byref(mlp)) + (fake,) * 4 + (other,) + (fake,) * 2 + (None,)
     assert lib.specee_predict_tree(C.byref(ok), 1, 2000, 64, *args, fake, C.c_size_t(1 << 30), None) == -1  # N*K>4096
@@ -93,8 +94,8 @@ def test_host_side_validation_without_a_gpu(sp):
     args_path = (fake,) * 3 + (fake, None, fake, C.byref(mlp)) + (fake,) * 4 + (other,) + (fake,) * 2 + (fake,)
     assert lib.specee_predict_tree(C.byref(ok), 1, 60, 64, *args_path, fake, C.c_size_t(1 << 30), None) == -1
     assert lib.lm_head_gemv(C.byref(ok), 1, fake, fake, odd, fake, None, C.c_size_t(0), None) == -2
-    assert lib.specee_verify(C.byref(ok), 1, fake, fake, fake, fake, None, fake, fake, fake, None, C.c_size_t(0),
-                             None) == -3
+    assert lib.specee_verify(C.byref(ok), 1, fake, fake, fake, fake, None, None, fake, fake, fake, None,
+                             C.c_size_t(0), None) == -3
 
 
 def test_workspace_sizes(sp):
