@@ -316,7 +316,8 @@ def main():
                                             "algorithmic_bytes": bytsG, "achieved_GBps": bytsG / us / 1e3,
                                             "frac_of_8TBps": bytsG / us / 1e3 / HBM_PEAK_GBS,
                                             "bytes_with_rows_counted_per_tree": bytsT,
-                                            "frac_of_8TBps_rows_per_tree": bytsT / us / 1e3 / HBM_PEAK_GBS}
+                                            "frac_of_8TBps_rows_per_tree": bytsT / us / 1e3 / HBM_PEAK_GBS,
+                                            "traffic": MEASURED_TRAFFIC.get(f"tree_c3_batch_G{G}")}
 
     # ------------------------------------------------------------------ layer loop with device-side control (one token)
     if want("loop") and not args.no_extra:
