@@ -111,6 +111,32 @@ def predict(hidden, gamma, lm_head, ids, prev_probs, W1, w2, b1=None, b2=None, e
     return dict(logits=logits, probs=probs, features=feats, scores=scores, exit=ex)
 
 
+def predict_q4(hidden, gamma, qweight, scales, zeros, group, ids, prev_probs, W1, w2, b1=None, b2=None, eps=1e-5,
+               threshold=0.5):
+    """specee_predict_q4_ref: the predictor against a 4-bit group-quantised LM head
+    (qweight uint32 [V][d/8], scales / zeros fp16 [V][d/group])."""
+    hidden, gamma, scales, zeros = _h(hidden), _h(gamma), _h(scales), _h(zeros)
+    qweight = np.ascontiguousarray(qweight, dtype=np.uint32)
+    ids, prev = _i(ids), _f(prev_probs)
+    W1, w2, b1, b2 = _h(W1), _h(w2), _h(b1), _h(b2)
+    B, d = hidden.shape
+    V = qweight.shape[0]
+    K = ids.shape[1]
+    H = w2.shape[0]
+    assert qweight.shape == (V, d // 8) and scales.shape == (V, d // group) and zeros.shape == scales.shape
+    assert W1.shape == (H, 3 * K) and ids.shape == (B, K) and prev.shape == (B, K)
+    logits = np.zeros((B, K)); probs = np.zeros((B, K)); feats = np.zeros((B, 3 * K))
+    scores = np.zeros(B); ex = np.zeros(B, dtype=np.int32)
+    u16, u32, i32, f32, f64 = C.c_uint16, C.c_uint32, C.c_int32, C.c_float, C.c_double
+    rc = lib().specee_predict_q4_ref(
+        C.c_int(d), C.c_int(V), C.c_int(K), C.c_int(H), C.c_double(eps), C.c_float(threshold), C.c_int(B),
+        _p(hidden, u16), _p(gamma, u16), _p(qweight, u32), _p(scales, u16), _p(zeros, u16), C.c_int(group),
+        _p(ids, i32), _p(prev, f32), _p(W1, u16), _p(b1, u16), _p(w2, u16), _p(b2, u16),
+        _p(logits, f64), _p(probs, f64), _p(feats, f64), _p(scores, f64), _p(ex, i32))
+    _check(rc, "specee_predict_q4_ref")
+    return dict(logits=logits, probs=probs, features=feats, scores=scores, exit=ex)
+
+
 def predict_sweep(hidden, gamma, lm_head, ids, W1, w2, b1=None, b2=None, prev0=None, active=None,
                   eps=1e-5, threshold=0.5):
     """L layers x B tokens with the probabilities carried layer to layer.

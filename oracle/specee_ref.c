@@ -24,6 +24,8 @@
  *     rearmost exit position of its tokens.
  *   - "Online Scheduling" (Sec. 5.3): circular queue of the last exit layers
  *     plus a per-layer neighbourhood counter.
+ *   - the same predictor on a 4-bit group-quantised LM head (the quantised
+ *     setting of the cloud evaluation, Sec. 7.1 / 7.3; the format is a reading).
  *
  * Readings where the paper is silent (each is a stated convention, not a
  * quotation): the model's final RMSNorm (weight gamma, epsilon eps) is applied
@@ -192,6 +194,49 @@ int specee_predict_ref(int d, int V, int K, int H, double eps, float threshold, 
  * is the precision in which a caller hands them back.
  * first_exit [B]: smallest active layer with exit==1, or -1.
  */
+/*
+ * The predictor on a 4-bit group-quantised LM head (the paper combines SpecEE
+ * with a weight-quantised model in its cloud evaluation, Sec. 7.1 "Quantization"
+ * and Sec. 7.3; it fixes no storage format, so this is a stated reading):
+ * element i of row v is stored as a code c in 0..15 -- bits 4*(i%8)..4*(i%8)+3
+ * of 32-bit word i/8 of the row -- and stands for the weight
+ *     w[v][i] = scale[v][i/group] * (c - zero[v][i/group]),
+ * scale and zero being fp16 numbers per group of `group` consecutive elements.
+ * Everything else is specee_predict_ref: the logits are taken against these
+ * weights, nothing is rounded in between.
+ */
+int specee_predict_q4_ref(int d, int V, int K, int H, double eps, float threshold, int B, const uint16_t *hidden,
+                          const uint16_t *gamma, const uint32_t *qweight, const uint16_t *scales,
+                          const uint16_t *zeros, int group, const int32_t *ids, const float *prev_probs,
+                          const uint16_t *W1, const uint16_t *b1, const uint16_t *w2, const uint16_t *b2,
+                          double *logits, double *probs, double *features, double *scores, int32_t *exit_flags) {
+    if (check_dims(d, V, K, H, B)) return REF_EINVAL;
+    if (group < 8 || group % 8 != 0 || d % group != 0) return REF_EINVAL;
+    for (int i = 0; i < B * K; ++i)
+        if (ids[i] < 0 || ids[i] >= V) return REF_EINVAL;
+    const int ng = d / group;
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (int n = 0; n < B; ++n) {
+        const uint16_t *h = hidden + (size_t)n * d;
+        double r = specee_ref_rms_scale(h, d, eps);
+        for (int k = 0; k < K; ++k) {
+            const size_t v = (size_t)ids[n * K + k];
+            double acc = 0.0;
+            for (int i = 0; i < d; ++i) {
+                const uint32_t word = qweight[v * (size_t)(d / 8) + (size_t)(i / 8)];
+                const double code = (double)((word >> (4 * (i % 8))) & 15u);
+                const double w = H2D(scales[v * ng + i / group]) * (code - H2D(zeros[v * ng + i / group]));
+                const double x = H2D(h[i]) * r * H2D(gamma[i]);
+                acc += x * w;
+            }
+            logits[n * K + k] = acc;
+        }
+        score_token(logits + n * K, prev_probs + n * K, K, H, W1, b1, w2, b2, threshold, probs + n * K,
+                    features ? features + (size_t)n * 3 * K : NULL, scores + n, exit_flags + n);
+    }
+    return REF_OK;
+}
+
 int specee_predict_sweep_ref(int d, int V, int K, int H, double eps, float threshold, int L, int B,
                              const uint16_t *hidden, const uint16_t *gamma, const uint16_t *lm_head,
                              const int32_t *ids, const float *prev0, const uint16_t *W1, const uint16_t *b1,

@@ -35,6 +35,34 @@ def lm_head(V: int, d: int, seed: int, std: float = 0.02, chunk_rows: int = 4096
     return out
 
 
+def quantize_q4(w: np.ndarray, group: int = 128, chunk_rows: int = 2048):
+    """4-bit group-quantised copy of an fp16 matrix [V][d], the storage the quantised-rows predictor reads:
+    every run of `group` consecutive elements of a row gets an fp16 scale and an fp16 zero-point (an
+    integer 0..15, the usual asymmetric min/max scheme) and each element a code 0..15.
+    Returns (qweight uint32 [V][d/8], scales fp16 [V][d/group], zeros fp16 [V][d/group]); element i of a row
+    sits in bits 4*(i%8) .. 4*(i%8)+3 of word i//8.  This only prepares inputs; how codes are turned back
+    into weights is the business of the oracle and of the kernels, each on its own."""
+    V, d = w.shape
+    assert d % group == 0 and group % 8 == 0
+    ng = d // group
+    q = np.empty((V, d // 8), dtype=np.uint32)
+    scales = np.empty((V, ng), dtype=np.float16)
+    zeros = np.empty((V, ng), dtype=np.float16)
+    shifts = (4 * np.arange(8, dtype=np.uint32))[None, None, :]
+    for r0 in range(0, V, chunk_rows):
+        blk = w[r0:r0 + chunk_rows].astype(np.float32).reshape(-1, ng, group)
+        lo, hi = blk.min(axis=2), blk.max(axis=2)
+        sc = np.maximum((hi - lo) / 15.0, 1e-8).astype(np.float16)          # what is stored is what is used
+        sc32 = sc.astype(np.float32)
+        zp = np.clip(np.rint(-lo / sc32), 0, 15)
+        code = np.clip(np.rint(blk / sc32[:, :, None] + zp[:, :, None]), 0, 15).astype(np.uint32)
+        words = (code.reshape(blk.shape[0], d // 8, 8) << shifts).sum(axis=2, dtype=np.uint32)
+        q[r0:r0 + chunk_rows] = words
+        scales[r0:r0 + chunk_rows] = sc
+        zeros[r0:r0 + chunk_rows] = zp.astype(np.float16)
+    return q, scales, zeros
+
+
 def gamma(d: int, seed: int) -> np.ndarray:
     return (1.0 + 0.01 * _rng(seed, 2).standard_normal(d)).astype(np.float16)
 

@@ -458,3 +458,115 @@ def test_schedule_brute_force_random(oracle):
         last = seq[max(0, t - Q):t]
         assert counters[t, i] == int(np.sum(np.abs(last - i) <= R))
     assert np.array_equal(active, (counters > 0).astype(np.int32))
+
+
+# ---------------------------------------------------------------- quantised LM-head rows (4-bit, per-group scale / zero)
+def q4_case(seed, d=64, V=11, K=3, H=16, B=4, group=16):
+    rng = np.random.default_rng(seed)
+    t = small(seed, d=d, V=V, K=K, H=H, B=B)
+    codes = rng.integers(0, 16, size=(V, d)).astype(np.uint32)
+    q = (codes.reshape(V, d // 8, 8) << (4 * np.arange(8, dtype=np.uint32))).sum(axis=2, dtype=np.uint32)
+    scales = (0.02 + 0.05 * rng.random((V, d // group))).astype(np.float16)
+    zeros = rng.integers(0, 16, size=(V, d // group)).astype(np.float16)
+    return t, codes, q, scales, zeros, group
+
+
+def run_q4(oracle, t, q, scales, zeros, group, **kw):
+    return oracle.predict_q4(t["hidden"], t["gamma"], q, scales, zeros, group, t["ids"], t["prev_probs"], t["W1"],
+                             t["w2"], t["b1"], t["b2"], **kw)
+
+
+def test_q4_unit_scale_zero_offset_is_the_fp16_predictor_on_the_codes(oracle):
+    """scale 1, zero 0: the weights ARE the codes (0..15, exact in fp16), so every output must equal the
+    already pinned fp16 predictor on a head that holds the codes."""
+    t, codes, q, scales, zeros, group = q4_case(41)
+    ones, nought = np.ones_like(scales), np.zeros_like(zeros)
+    got = run_q4(oracle, t, q, ones, nought, group)
+    ref = oracle.predict(t["hidden"], t["gamma"], codes.astype(np.float16), t["ids"], t["prev_probs"], t["W1"],
+                         t["w2"], t["b1"], t["b2"])
+    for k in ("logits", "probs", "features", "scores"):
+        np.testing.assert_allclose(got[k], ref[k], rtol=1e-12, atol=1e-12)
+    assert np.array_equal(got["exit"], ref["exit"])
+
+
+def test_q4_equals_fp16_predictor_when_the_weights_are_representable(oracle):
+    """Power-of-two scales and integer zero-points give weights that fp16 holds exactly: again the pinned
+    fp16 predictor must agree, now with scale, zero-point and group index all in play."""
+    t, codes, q, scales, zeros, group = q4_case(42, d=96, group=32)
+    rng = np.random.default_rng(1)
+    scales = (2.0 ** rng.integers(-6, -1, size=scales.shape)).astype(np.float16)
+    w = f64(scales).repeat(group, axis=1) * (codes.astype(np.float64) - f64(zeros).repeat(group, axis=1))
+    w16 = w.astype(np.float16)
+    assert np.array_equal(f64(w16), w)
+    got = run_q4(oracle, t, q, scales, zeros, group)
+    ref = oracle.predict(t["hidden"], t["gamma"], w16, t["ids"], t["prev_probs"], t["W1"], t["w2"], t["b1"], t["b2"])
+    np.testing.assert_allclose(got["logits"], ref["logits"], rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(got["scores"], ref["scores"], rtol=1e-12, atol=1e-12)
+
+
+def test_q4_nibble_order_and_group_index_one_hot(oracle):
+    """A single non-zero code at element i (all zero-points 0) leaves logit = x_i * scale[group of i] * code:
+    wrong nibble order, word index or group index each move it."""
+    d, group, V = 64, 16, 3
+    rng = np.random.default_rng(3)
+    t = small(43, d=d, V=V, K=1, H=8, B=1)
+    t["ids"][:] = 1
+    x = np_normed(t["hidden"], t["gamma"], 1e-5)[0]
+    scales = (0.5 + rng.random((V, d // group))).astype(np.float16)
+    zeros = np.zeros((V, d // group), np.float16)
+    for i in (0, 1, 7, 8, 15, 16, 37, 63):
+        codes = np.zeros((V, d), np.uint32)
+        codes[1, i] = 1 + i % 15
+        q = (codes.reshape(V, d // 8, 8) << (4 * np.arange(8, dtype=np.uint32))).sum(axis=2, dtype=np.uint32)
+        got = run_q4(oracle, t, q, scales, zeros, group)
+        want = x[i] * float(scales[1, i // group]) * codes[1, i]
+        assert math.isclose(got["logits"][0, 0], want, rel_tol=1e-12, abs_tol=1e-15), i
+
+
+def test_q4_zero_point_shift_closed_form_and_dead_groups(oracle):
+    t, codes, q, scales, zeros, group = q4_case(44, d=64, group=16)
+    base = run_q4(oracle, t, q, scales, zeros, group)["logits"]
+    # raising every zero-point by c lowers logit k by c * sum_g scale[id_k][g] * sum_{i in g} x_i
+    x = np_normed(t["hidden"], t["gamma"], 1e-5)
+    xg = x.reshape(x.shape[0], -1, group).sum(axis=2)                       # [B][groups]
+    c = 3.0
+    shifted = run_q4(oracle, t, q, scales, (f64(zeros) + c).astype(np.float16), group)["logits"]
+    want = base - c * np.einsum("bg,bkg->bk", xg, f64(scales)[t["ids"]])
+    np.testing.assert_allclose(shifted, want, rtol=1e-11, atol=1e-11)
+    # a group whose scale is 0 contributes nothing, whatever its codes are
+    s0 = scales.copy(); s0[:, 2] = 0
+    a = run_q4(oracle, t, q, s0, zeros, group)["logits"]
+    codes2 = codes.copy(); codes2[:, 2 * group:3 * group] = 15 - codes2[:, 2 * group:3 * group]
+    q2 = (codes2.reshape(codes.shape[0], -1, 8) << (4 * np.arange(8, dtype=np.uint32))).sum(axis=2, dtype=np.uint32)
+    b = run_q4(oracle, t, q2, s0, zeros, group)["logits"]
+    assert np.array_equal(a, b)
+    assert not np.array_equal(a, base)
+
+
+def test_q4_generator_reconstructs_within_half_a_step(oracle):
+    """The synthetic quantiser (input preparation) and the oracle's reading of the format agree: the weights
+    the oracle sees differ from the fp16 originals by at most half a quantisation step per element, hence the
+    logits by a bound that follows from it."""
+    rng = np.random.default_rng(9)
+    d, V, group = 256, 7, 128
+    w = (0.02 * rng.standard_normal((V, d))).astype(np.float16)
+    q, scales, zeros = synth.quantize_q4(w, group)
+    assert q.dtype == np.uint32 and q.shape == (V, d // 8) and scales.shape == (V, d // group)
+    t = small(45, d=d, V=V, K=2, H=8, B=3)
+    got = run_q4(oracle, t, q, scales, zeros, group)["logits"]
+    ref = oracle.predict(t["hidden"], t["gamma"], w, t["ids"], t["prev_probs"], t["W1"], t["w2"], t["b1"],
+                         t["b2"])["logits"]
+    x = np.abs(np_normed(t["hidden"], t["gamma"], 1e-5)).reshape(3, -1, group).sum(axis=2)      # [B][groups]
+    bound = 0.5 * 1.01 * np.einsum("bg,bkg->bk", x, f64(scales)[t["ids"]]) + 1e-9
+    assert np.all(np.abs(got - ref) <= bound)
+    assert np.abs(got - ref).max() > 0
+
+
+def test_q4_rejects_bad_arguments(oracle):
+    t, codes, q, scales, zeros, group = q4_case(46)
+    with pytest.raises(ValueError):
+        run_q4(oracle, dict(t, ids=np.full_like(t["ids"], 11)), q, scales, zeros, group)
+    t2, _, q2, _, _, _ = q4_case(47, d=48, group=8)
+    s12 = np.ones((q2.shape[0], 4), np.float16)
+    with pytest.raises(ValueError):                     # group must be a multiple of 8
+        run_q4(oracle, t2, q2, s12, s12, 12)
