@@ -59,7 +59,7 @@ def main():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--sets", type=int, default=64, help="rotating input sets")
-    ap.add_argument("--only", default="", help="comma-separated sections: sweep,single,batch,tree,lmhead,loop,c4,c5,copy")
+    ap.add_argument("--only", default="", help="comma-separated sections: sweep,single,batch,tree,lmhead,q4,loop,c4,c5,copy")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-extra", action="store_true", help="only the headline step")
     args = ap.parse_args()
@@ -318,6 +318,44 @@ def main():
                                             "bytes_with_rows_counted_per_tree": bytsT,
                                             "frac_of_8TBps_rows_per_tree": bytsT / us / 1e3 / HBM_PEAK_GBS,
                                             "traffic": MEASURED_TRAFFIC.get(f"tree_c3_batch_G{G}")}
+
+    # ------------------------------------------------------------------ 4-bit group-quantised LM-head rows
+    if want("q4") and not args.no_extra:
+        group = 128
+        qh, sh, zh = synth.quantize_q4(lm_h, group)
+        qd, sd, zd = up(qh.view(np.int32)), up(sh), up(zh)
+        t1 = synth.make("C1", lm=lm_h)
+        w1_1, w2_1 = up(t1["W1"]), up(t1["w2"])
+        row_bytes = d // 2 + 2 * (d // group) * 2
+
+        def q4_bytes(B, rows):
+            return B * d * 2 + d * 2 + rows * row_bytes + (3 * K * H + H) * 2 + B * (K * 4 + K * 4 + 2 * K * 4 + 8)
+        R1 = 256
+        hid = up(synth.hidden(R1, d, 223))
+        ids = up(synth.ids_uniform_distinct(R1, K, V, 224))
+        prev = up(synth.prob_rows(R1, K, 225))
+        o1 = sp.predict_q4(hid[:1], gamma, qd, sd, zd, group, ids[:1], prev[:1], w1_1, w2_1)
+        g = capture(lambda: [sp.predict_q4(hid[r:r + 1], gamma, qd, sd, zd, group, ids[r:r + 1], prev[r:r + 1], w1_1,
+                                           w2_1, out=o1) for r in range(R1)])
+        res = {"group": group, "row_bytes": row_bytes, "fp16_row_bytes": 2 * d,
+               "us_per_call_rotated_ids": ev_time(g.replay, 20, 3) * 1e3 / R1,
+               "algorithmic_bytes_one_token": q4_bytes(1, K)}
+        for B in (8000, 16384):
+            rng = np.random.default_rng(B)
+            hb = up(rng.standard_normal((B, d), dtype=np.float32).astype(np.float16))
+            ids_h = (rng.permutation(V)[:B * K].reshape(B, K) if B * K <= V
+                     else rng.integers(0, V, size=(B, K))).astype(np.int32)
+            ib, pb = up(ids_h), up(synth.prob_rows(B, K, 9))
+            o = sp.predict_q4(hb, gamma, qd, sd, zd, group, ib, pb, w1_1, w2_1)
+            reps = 8
+            g = capture(lambda: [sp.predict_q4(hb, gamma, qd, sd, zd, group, ib, pb, w1_1, w2_1, out=o)
+                                 for _ in range(reps)])
+            us = ev_time(g.replay, 20, 3) * 1e3 / reps
+            byts = q4_bytes(B, len(np.unique(ids_h)))
+            res[f"B={B}"] = {"us_per_launch": us, "evals_per_s": B / us * 1e6, "algorithmic_bytes": byts,
+                             "achieved_GBps": byts / us / 1e3, "frac_of_8TBps": byts / us / 1e3 / HBM_PEAK_GBS}
+        extra["q4_predict_7b"] = res
+        del qd, sd, zd
 
     # ------------------------------------------------------------------ layer loop with device-side control (one token)
     if want("loop") and not args.no_extra:

@@ -106,6 +106,24 @@ int specee_predict(const specee_dims *dims, int B, const specee_half *hidden, co
                    float *logits, float *probs, float *scores, int32_t *exit_flags, void *stream);
 
 /*
+ * specee_predict on a 4-bit group-quantised LM head (the paper runs SpecEE on
+ * top of a weight-quantised model in its cloud evaluation, Sec. 7.1
+ * "Quantization" and Sec. 7.3; it fixes no storage format, this one is the
+ * library's reading).  Element i of row v is a code c in 0..15, stored in bits
+ * 4*(i%8) .. 4*(i%8)+3 of 32-bit word i/8 of the row, and stands for the weight
+ *     scales[v][i/group] * (c - zeros[v][i/group]).
+ *   qweight [V][d/8] uint32, scales and zeros [V][d/group] fp16 (device);
+ *   group: a multiple of 8 that divides d.  Everything else, including `done`,
+ *   is as for specee_predict.  A speculative row is d/2 bytes instead of 2d.
+ * Needs no workspace.
+ */
+int specee_predict_q4(const specee_dims *dims, int B, const specee_half *hidden, const specee_half *gamma,
+                      const uint32_t *qweight, const specee_half *scales, const specee_half *zeros, int group,
+                      const int32_t *ids, const float *prev_probs, const specee_mlp *mlp,
+                      const int32_t *done /* [B] or NULL */, float *logits, float *probs, float *scores,
+                      int32_t *exit_flags, void *stream);
+
+/*
  * All L layers of B tokens in one call: layer l uses hidden[l], predictor l and
  * the local probabilities of the nearest earlier active layer (prev0, or zeros
  * if NULL, before the first).  Used when every layer's hidden state already

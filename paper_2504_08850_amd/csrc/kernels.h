@@ -22,11 +22,17 @@ struct PredictParams {
     const half_t *W1, *b1, *w2, *b2;  // leading layer dimension L
     const int32_t *active;  // [L] or null (sweep only)
     const int32_t *done;    // [B] or null (single layer only): tokens to skip
+    // 4-bit group-quantised head (predict_q4 only; lm_head is then null): codes, per-group scale and zero-point
+    const uint32_t *qweight;  // [V][d/8], element i in bits 4*(i%8).. of word i/8
+    const half_t *qscales;    // [V][d/group]
+    const half_t *qzeros;     // [V][d/group]
+    int group;
     float *logits, *probs, *scores;
     int32_t *exit_flags;
 };
 
 hipError_t launch_predict(const PredictParams &p, hipStream_t s);
+hipError_t launch_predict_q4(const PredictParams &p, hipStream_t s);
 hipError_t launch_predict_sweep(const PredictParams &p, int32_t *first_exit, hipStream_t s);
 
 #define SPECEE_KMAX_INTERNAL 16

@@ -242,6 +242,180 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(PredictParams 
     }
 }
 
+// The predictor on a 4-bit group-quantised LM head (the quantised setting of the paper's cloud
+// evaluation, Sec. 7.1 / 7.3; the storage format is this library's reading): element i of a row is a
+// code c in 0..15 in bits 4*(i%8).. of 32-bit word i/8 and stands for scale[g] * (c - zero[g]),
+// g = i / group.  A speculative row is then d/2 bytes instead of 2d, and the dequantisation never
+// materialises: a thread owns eight consecutive elements (one word per row, all in one group), forms
+//     sum_e x_e * c_e   and   sum_e x_e          (x = h * gamma, fp32)
+// and adds scale * (first - zero * second) to the row's dot product -- one multiply-add per element
+// plus three per word.  Same two dependent trips to memory and the same reductions and tail as
+// predict_kernel; one workgroup per token.
+// EXACT: K == KC at compile time (see predict_kernel).  Every load is unconditional on a clamped, valid
+// address -- a load under a branch would make the compiler wait for all outstanding loads at the join
+// and turn the K rows into K serial trips to memory; unused data is zeroed by selects instead.
+template <int KC, int VPT, bool EXACT>
+__global__ __launch_bounds__(kPredictThreads) void predict_q4_kernel(PredictParams p) {
+    __shared__ float red[kPredictWaves][KC + 1];
+    __shared__ float red_u[kPredictWaves];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    const int b = blockIdx.x;
+    const int K = EXACT ? KC : p.K, H = p.H, d = p.d;
+    const int nv = d >> 3, ng = d / p.group;
+
+    // ---- requests that do not depend on the ids
+    MlpRow<KC> row0;
+    mlp_row_load<KC>(row0, p.W1, p.b1, p.w2, K, H, tid);
+    const half_t *hrow = p.hidden + (size_t)b * d;
+    half8 hv[VPT], gv[VPT];
+    int vc[VPT];
+#pragma unroll
+    for (int u = 0; u < VPT; ++u) {
+        const int v = tid + u * kPredictThreads;
+        vc[u] = min(v, nv - 1);
+        const half8 h8 = load_half8(hrow + vc[u] * 8), g8 = load_half8(p.gamma + vc[u] * 8);
+        hv[u] = v < nv ? h8 : zero_half8();  // a zero hidden state silences the clamped duplicate
+        gv[u] = g8;
+    }
+    float prev[KC];
+#pragma unroll
+    for (int k = 0; k < KC; ++k) {
+        const float pv = p.prev[(size_t)b * K + min(k, K - 1)];
+        prev[k] = (k < K) ? pv : 0.f;
+    }
+    const int32_t *donep = p.done ? p.done + b : p.ids;  // always a valid address
+    const int dn_raw = *donep;
+    const int dn = p.done ? dn_raw : 0;
+
+    // ---- the K speculative rows: one word of codes per row and vector, with its group's scale and zero-point
+    int rowi[KC];
+    bool bad_id = false;
+#pragma unroll
+    for (int k = 0; k < KC; ++k) {
+        const int id = p.ids[(size_t)b * K + min(k, K - 1)];
+        const bool ok = id >= 0 && id < p.V;
+        if (k < K && !ok) bad_id = true;
+        rowi[k] = ok ? id : 0;
+    }
+    if (dn != 0) {  // uniform over the workgroup: the token already left the model
+        if (tid < K) {
+            p.logits[(size_t)b * K + tid] = 0.f;
+            p.probs[(size_t)b * K + tid] = p.prev[(size_t)b * K + tid];
+        }
+        if (tid == 0) {
+            p.scores[b] = 0.f;
+            p.exit_flags[b] = 0;
+        }
+        return;
+    }
+    uint32_t qw[KC][VPT];
+    half_t qs[KC][VPT], qz[KC][VPT];
+#pragma unroll
+    for (int k = 0; k < KC; ++k)
+#pragma unroll
+        for (int u = 0; u < VPT; ++u) {
+            const size_t gi = (size_t)rowi[k] * ng + (vc[u] * 8) / p.group;
+            qw[k][u] = p.qweight[(size_t)rowi[k] * nv + vc[u]];
+            qs[k][u] = p.qscales[gi];
+            qz[k][u] = p.qzeros[gi];
+        }
+
+    float ssq = 0.f, acc[KC];
+#pragma unroll
+    for (int k = 0; k < KC; ++k) acc[k] = 0.f;
+    auto dot8 = [&](const half8 &h8, const half8 &g8, const uint32_t (&w)[KC], const half_t (&sc)[KC],
+                    const half_t (&zp)[KC]) {
+        float x[8], xs = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float hf = (float)h8[e];
+            x[e] = hf * (float)g8[e];
+            ssq += hf * hf;
+            xs += x[e];
+        }
+#pragma unroll
+        for (int k = 0; k < KC; ++k) {
+            const uint32_t even = w[k] & 0x0f0f0f0fu, odd = (w[k] >> 4) & 0x0f0f0f0fu;  // elements 0,2,4,6 / 1,3,5,7
+            float pd = 0.f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                pd += x[2 * j] * (float)((even >> (8 * j)) & 0xffu);
+                pd += x[2 * j + 1] * (float)((odd >> (8 * j)) & 0xffu);
+            }
+            acc[k] += (float)sc[k] * (pd - (float)zp[k] * xs);
+        }
+    };
+#pragma unroll
+    for (int u = 0; u < VPT; ++u) {
+        uint32_t w[KC];
+        half_t sc[KC], zp[KC];
+#pragma unroll
+        for (int k = 0; k < KC; ++k) {
+            w[k] = qw[k][u];
+            sc[k] = qs[k][u];
+            zp[k] = qz[k][u];
+        }
+        dot8(hv[u], gv[u], w, sc, zp);
+    }
+    // d larger than VPT * 512 vectors: remaining tiles, same arithmetic
+    for (int v = tid + VPT * kPredictThreads; v < nv; v += kPredictThreads) {
+        const half8 h8 = load_half8(hrow + v * 8), g8 = load_half8(p.gamma + v * 8);
+        uint32_t w[KC];
+        half_t sc[KC], zp[KC];
+#pragma unroll
+        for (int k = 0; k < KC; ++k) {
+            const size_t gi = (size_t)rowi[k] * ng + (v * 8) / p.group;
+            w[k] = p.qweight[(size_t)rowi[k] * nv + v];
+            sc[k] = p.qscales[gi];
+            zp[k] = p.qzeros[gi];
+        }
+        dot8(h8, g8, w, sc, zp);
+    }
+
+    // ---- wavefront reduction, then fixed-order combination of the eight wave partials
+    ssq = wave_sum_to_last_row(ssq);
+#pragma unroll
+    for (int k = 0; k < KC; ++k) acc[k] = wave_sum_to_last_row(acc[k]);
+    if (lane == kWave - 1) {
+        red[wave][0] = ssq;
+#pragma unroll
+        for (int k = 0; k < KC; ++k) red[wave][1 + k] = acc[k];
+    }
+    __syncthreads();
+    ssq = 0.f;
+#pragma unroll
+    for (int k = 0; k < KC; ++k) acc[k] = 0.f;
+#pragma unroll
+    for (int w = 0; w < kPredictWaves; ++w) {
+        ssq += red[w][0];
+#pragma unroll
+        for (int k = 0; k < KC; ++k) acc[k] += red[w][1 + k];
+    }
+    float z[KC], pr[KC];
+    const float r = 1.0f / sqrtf(ssq * (1.0f / (float)d) + p.eps);
+#pragma unroll
+    for (int k = 0; k < KC; ++k) z[k] = bad_id ? quiet_nan() : acc[k] * r;
+    local_softmax<KC>(z, K, pr);
+    float part = mlp_partial<KC, kPredictThreads>(row0, p.W1, p.b1, p.w2, K, H, tid, z, pr, prev);
+    part = wave_sum_to_last_row(part);
+    if (lane == kWave - 1) red_u[wave] = part;
+    __syncthreads();
+    if (tid == 0) {
+        float u = p.b2 ? (float)p.b2[0] : 0.f;
+#pragma unroll
+        for (int w = 0; w < kPredictWaves; ++w) u += red_u[w];
+        const float sc = sigmoidf(u);
+        p.scores[b] = sc;
+        p.exit_flags[b] = (sc > p.threshold) ? 1 : 0;
+#pragma unroll
+        for (int k = 0; k < KC; ++k)
+            if (k < K) {
+                p.logits[(size_t)b * K + k] = z[k];
+                p.probs[(size_t)b * K + k] = pr[k];
+            }
+    }
+}
+
 // first_exit[b] = first layer with exit flag 1 (inactive layers carry 0), else -1
 __global__ void first_exit_kernel(const int32_t *exit_flags, int L, int B, int32_t *first_exit) {
     int b = blockIdx.x * blockDim.x + threadIdx.x;
@@ -280,6 +454,25 @@ static hipError_t launch_kc(const PredictParams &p, hipStream_t s) {
 
 hipError_t launch_predict(const PredictParams &p, hipStream_t s) {
     return launch_kc<false>(p, s);
+}
+
+template <int KC, bool EXACT>
+static hipError_t launch_q4_kc(const PredictParams &p, hipStream_t s) {
+    const dim3 grid(p.B), block(kPredictThreads);
+    const int nv = p.d >> 3;
+    if (nv <= kPredictThreads)
+        hipLaunchKernelGGL((predict_q4_kernel<KC, 1, EXACT>), grid, block, 0, s, p);
+    else
+        hipLaunchKernelGGL((predict_q4_kernel<KC, 2, EXACT>), grid, block, 0, s, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_predict_q4(const PredictParams &p, hipStream_t s) {
+    if (p.K == 4) return launch_q4_kc<4, true>(p, s);
+    if (p.K == 8) return launch_q4_kc<8, true>(p, s);
+    if (p.K < 4) return launch_q4_kc<4, false>(p, s);
+    if (p.K < 8) return launch_q4_kc<8, false>(p, s);
+    return launch_q4_kc<16, false>(p, s);
 }
 
 hipError_t launch_predict_sweep(const PredictParams &p, int32_t *first_exit, hipStream_t s) {

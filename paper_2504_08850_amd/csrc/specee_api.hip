@@ -146,6 +146,33 @@ int specee_predict(const specee_dims *dm, int B, const specee_half *hidden, cons
     return launch_predict(p, static_cast<hipStream_t>(stream)) == hipSuccess ? SPECEE_OK : SPECEE_EHIP;
 }
 
+int specee_predict_q4(const specee_dims *dm, int B, const specee_half *hidden, const specee_half *gamma,
+                      const uint32_t *qweight, const specee_half *scales, const specee_half *zeros, int group,
+                      const int32_t *ids, const float *prev_probs, const specee_mlp *mlp, const int32_t *done,
+                      float *logits, float *probs, float *scores, int32_t *exit_flags, void *stream) {
+    int rc = check_dims(dm, true);
+    if (rc) return rc;
+    if (B < 0 || group < 8 || group % 8 != 0 || dm->d % group != 0) return SPECEE_EINVAL;
+    if (B == 0) return SPECEE_OK;
+    if ((rc = check_mlp(mlp))) return rc;
+    if (!hidden || !gamma || !qweight || !scales || !zeros || !ids || !prev_probs || !logits || !probs || !scores ||
+        !exit_flags)
+        return SPECEE_EINVAL;
+    if (probs == prev_probs) return SPECEE_EINVAL;
+    if (misaligned(hidden) || misaligned(gamma) || (reinterpret_cast<uintptr_t>(qweight) & 3) != 0)
+        return SPECEE_EALIGN;
+    PredictParams p{};
+    p.d = dm->d; p.V = dm->V; p.K = dm->K; p.H = dm->H; p.eps = dm->eps; p.threshold = dm->threshold;
+    p.B = B; p.L = 1;
+    p.hidden = H(hidden); p.gamma = H(gamma); p.lm_head = nullptr; p.ids = ids; p.prev = prev_probs;
+    p.qweight = qweight; p.qscales = H(scales); p.qzeros = H(zeros); p.group = group;
+    p.W1 = H(mlp->W1); p.b1 = H(mlp->b1); p.w2 = H(mlp->w2); p.b2 = H(mlp->b2);
+    p.active = nullptr;
+    p.done = done;
+    p.logits = logits; p.probs = probs; p.scores = scores; p.exit_flags = exit_flags;
+    return launch_predict_q4(p, static_cast<hipStream_t>(stream)) == hipSuccess ? SPECEE_OK : SPECEE_EHIP;
+}
+
 int specee_predict_sweep(const specee_dims *dm, int L, int B, const specee_half *hidden, const specee_half *gamma,
                          const specee_half *lm_head, const int32_t *ids, const float *prev0, const specee_mlp *mlp,
                          const int32_t *active, float *logits, float *probs, float *scores, int32_t *exit_flags,

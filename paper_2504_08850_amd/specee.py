@@ -118,6 +118,35 @@ def predict(hidden, gamma, lm_head, ids, prev_probs, W1, w2, b1=None, b2=None, e
     return out
 
 
+def predict_q4(hidden, gamma, qweight, scales, zeros, group, ids, prev_probs, W1, w2, b1=None, b2=None, eps=1e-5,
+               threshold=0.5, out=None, stream=None, done=None):
+    """specee_predict_q4: specee_predict against a 4-bit group-quantised LM head (qweight int32/uint32 words
+    [V][d/8], scales / zeros fp16 [V][d/group])."""
+    B, d = hidden.shape
+    V = qweight.shape[0]
+    K = ids.shape[1]
+    H = w2.shape[0]
+    dev = hidden.device
+    assert qweight.shape == (V, d // 8) and qweight.dtype == torch.int32, "codes travel as int32 words"
+    assert scales.shape == (V, d // group) and zeros.shape == scales.shape
+    if out is None:
+        out = dict(logits=torch.empty((B, K), dtype=torch.float32, device=dev),
+                   probs=torch.empty((B, K), dtype=torch.float32, device=dev),
+                   scores=torch.empty((B,), dtype=torch.float32, device=dev),
+                   exit=torch.empty((B,), dtype=torch.int32, device=dev))
+    dims = _dims(d, V, K, H, eps, threshold)
+    mlp = _mlp(W1, w2, b1, b2)
+    f16 = torch.float16
+    rc = lib().specee_predict_q4(C.byref(dims), C.c_int(B), _ptr(hidden, f16), _ptr(gamma, f16),
+                                 _ptr(qweight, torch.int32), _ptr(scales, f16), _ptr(zeros, f16), C.c_int(group),
+                                 _ptr(ids, torch.int32), _ptr(prev_probs, torch.float32), C.byref(mlp),
+                                 _ptr(done, torch.int32), _ptr(out["logits"]), _ptr(out["probs"]),
+                                 _ptr(out["scores"]), _ptr(out["exit"]), _stream(stream))
+    if rc:
+        raise SpeceeError("specee_predict_q4", rc)
+    return out
+
+
 def predict_sweep(hidden, gamma, lm_head, ids, W1, w2, b1=None, b2=None, prev0=None, active=None, eps=1e-5,
                   threshold=0.5, out=None, stream=None):
     """specee_predict_sweep: hidden [L][B][d], one predictor per layer."""

@@ -85,6 +85,13 @@ def test_host_side_validation_without_a_gpu(sp):
     assert predict(C.byref(ok), probs=fake, prev=fake) == -1          # probs aliases prev_probs
     assert lib.specee_predict(C.byref(ok), 0, None, None, None, None, None, None, None, None, None, None, None,
                               None) == 0
+    # quantised rows: group must be a multiple of 8 that divides d; code words 4-byte aligned
+    def q4(group=128, B=1, q=fake, probs=other):
+        return lib.specee_predict_q4(C.byref(ok), B, fake, fake, q, fake, fake, group, fake, fake, C.byref(mlp), None,
+                                     fake, probs, fake, fake, None)
+    assert q4(group=12) == -1 and q4(group=4) == -1 and q4(group=4096 * 2) == -1 and q4(B=-1) == -1
+    assert q4(q=None) == -1 and q4(probs=fake) == -1 and q4(q=C.c_void_p(fake.value + 2)) == -2
+    assert q4(B=0, q=None) == 0
     # tree: limits and workspace
     args = (fake,) * 3 + (fake, None, fake, C.byref(mlp)) + (fake,) * 4 + (other,) + (fake,) * 2 + (None,)
     assert lib.specee_predict_tree(C.byref(ok), 1, 2000, 64, *args, fake, C.c_size_t(1 << 30), None) == -1  # N*K>4096
