@@ -62,6 +62,12 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(PredictParams 
             }
     }
 
+    // ---- the ids (and the token's done flag) are requested before anything else: the LM-head rows, the
+    // longest chain of the kernel, hang on them
+    int idv[KC];
+#pragma unroll
+    for (int k = 0; k < KC; ++k) idv[k] = (k < K) ? p.ids[(size_t)(SWEEP ? b : tok) * K + k] : 0;
+
     // ---- requests that do not depend on the ids
     const half_t *W1 = p.W1 + (size_t)l * H * 3 * K;
     const half_t *w2 = p.w2 + (size_t)l * H;
@@ -91,14 +97,14 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(PredictParams 
     }
 
     // ---- the K speculative LM-head rows
-    // The token's done flag travels with the ids (same trip to memory), so looking at it costs the
-    // live tokens nothing; a token that already left the model stops here, before the rows are read.
+    // The token's done flag travels with the ids, so looking at it costs the live tokens nothing; a
+    // token that already left the model stops here, before the rows are read.
     const int dn = (!SWEEP && p.done) ? p.done[b] : 0;
     const half_t *rows[KC];
     bool bad_id = false;
 #pragma unroll
     for (int k = 0; k < KC; ++k) {
-        int id = (k < K) ? p.ids[(size_t)(SWEEP ? b : tok) * K + k] : 0;
+        int id = idv[k];
         bool ok = id >= 0 && id < p.V;
         if (k < K && !ok) bad_id = true;
         rows[k] = p.lm_head + (size_t)(ok ? id : 0) * d;

@@ -38,7 +38,8 @@ __device__ __forceinline__ void local_softmax(const float (&z)[KC], int K, float
 template <int KC>
 struct MlpRow {
     uint2 w1[(3 * KC + 3) / 4];  // 3*KC halves of W1[j][:], valid when K == KC
-    float w2, b1;
+    half_t w2, b1;               // as loaded; widened where they are used, so that requesting a row never waits
+    bool has_b1;
 };
 
 // Request hidden unit `j`'s weights.  Vector loads need K == KC (row length
@@ -46,24 +47,24 @@ struct MlpRow {
 template <int KC>
 __device__ __forceinline__ void mlp_row_load(MlpRow<KC> &r, const half_t *W1, const half_t *b1, const half_t *w2,
                                              int K, int H, int j) {
-    r.w2 = 0.f;
-    r.b1 = 0.f;
-    if (j < H) {
-        if (K == KC) {
-            const uint2 *src = reinterpret_cast<const uint2 *>(W1 + (size_t)j * 3 * KC);
+    // Nothing here consumes what it loads and no load sits under a per-lane branch: the index is
+    // clamped (callers ignore units j >= H) and an absent bias reads w2 instead, masked at use.
+    const int jj = min(j, H - 1);
+    if (K == KC) {
+        const uint2 *src = reinterpret_cast<const uint2 *>(W1 + (size_t)jj * 3 * KC);
 #pragma unroll
-            for (int q = 0; q < (3 * KC) / 4; ++q) r.w1[q] = src[q];
-        }
-        r.w2 = (float)w2[j];
-        if (b1) r.b1 = (float)b1[j];
+        for (int q = 0; q < (3 * KC) / 4; ++q) r.w1[q] = src[q];
     }
+    r.w2 = w2[jj];
+    r.b1 = (b1 ? b1 : w2)[jj];
+    r.has_b1 = b1 != nullptr;
 }
 
 // w2[j] * relu(b1[j] + W1[j] . [z | p | p - prev]) for one hidden unit
 template <int KC>
 __device__ __forceinline__ float mlp_unit(const MlpRow<KC> &r, const half_t *W1, int K, int j, const float (&z)[KC],
                                           const float (&pr)[KC], const float (&prev)[KC]) {
-    float a = r.b1;
+    float a = r.has_b1 ? (float)r.b1 : 0.f;
     if (K == KC) {
         float f[3 * KC];
 #pragma unroll
@@ -90,7 +91,7 @@ __device__ __forceinline__ float mlp_unit(const MlpRow<KC> &r, const half_t *W1,
         for (int k = 0; k < KC; ++k)
             if (k < K) a += (float)src[2 * K + k] * (pr[k] - prev[k]);
     }
-    float v = r.w2 * fmaxf(a, 0.f);
+    float v = (float)r.w2 * fmaxf(a, 0.f);
     return (a != a) ? quiet_nan() : v;  // fmaxf drops NaN; keep invalid ids visible
 }
 
