@@ -22,7 +22,8 @@ template <int KC>
 struct FinishRows {
     MlpRow<KC> rows[KC <= 8 ? kFinishUnits : 1];
     bool regs;
-    float b2;
+    half_t b2;  // as loaded (widened at use, so that requesting it never waits); 0 when has_b2 is false
+    bool has_b2;
 };
 
 template <int KC>
@@ -33,7 +34,8 @@ __device__ __forceinline__ void finish_load_rows(FinishRows<KC> &fr, const TreeF
         for (int u = 0; u < kFinishUnits; ++u)
             mlp_row_load<KC>(fr.rows[u], p.W1, p.b1, p.w2, p.K, p.H, lane + u * kWave);
     }
-    fr.b2 = p.b2 ? (float)p.b2[0] : 0.f;
+    fr.b2 = (p.b2 ? p.b2 : p.w2)[0];  // always a valid address; masked at use
+    fr.has_b2 = p.b2 != nullptr;
 }
 
 // One wavefront scores node gn from its normalised logits z (NaN = invalid) and previous
@@ -70,7 +72,7 @@ __device__ __forceinline__ int finish_score_node(FinishRows<KC> &fr, const TreeF
         }
     }
     part = wave_sum_to_last_row(part);
-    const float sc = sigmoidf(fr.b2 + part);
+    const float sc = sigmoidf((fr.has_b2 ? (float)fr.b2 : 0.f) + part);
     const int ex = (sc > p.threshold) ? 1 : 0;
     if (lane == kWave - 1) {
         p.scores[gn] = sc;

@@ -85,11 +85,24 @@ __global__ __launch_bounds__(WHOLE ? 512 : 256) void tree_finish_kernel(TreeFini
         size_t off = ((size_t)N * (K + 1) + (size_t)N * K + N + 8 * 16 * kMlpFeat) * sizeof(float);
         off = (off + 15) & ~(size_t)15;
         pl = stage_mlp_to_lds(reinterpret_cast<half_t *>(reinterpret_cast<char *>(finish_lds) + off), p, tid, THREADS);
-    } else {
-        finish_load_rows<KC>(fr, p, lane);
     }
     const int M = p.M_out[g];
     const size_t pstride = (size_t)p.Npad * p.Mpad;
+    // WHOLE = false: the chain columns -> partial sums -> logits is the long one, so the first node's
+    // ids, columns and previous probabilities are requested before the predictor rows, which are
+    // not needed until the MLP (clamped lane index: the loads are unconditional)
+    int id_next = 0, col_next = 0;
+    float prev_next[KC];
+    auto request_node = [&](int n) {
+        const size_t gn = (size_t)g * N + min(n, N - 1);
+        const int kk = min(lane, K - 1);
+        id_next = p.ids[gn * K + kk];
+        col_next = p.cols[gn * K + kk];
+#pragma unroll
+        for (int k = 0; k < KC; ++k) prev_next[k] = p.prev[gn * K + min(k, K - 1)];
+    };
+    if (!WHOLE) request_node(n_begin + wave);
+    if (!use_mfma) finish_load_rows<KC>(fr, p, lane);
 
     if (WHOLE) {
         const int total = N * (K + 1);
@@ -174,14 +187,11 @@ __global__ __launch_bounds__(WHOLE ? 512 : 256) void tree_finish_kernel(TreeFini
                 prev[k] = (k < K) ? prevl[n * K + k] : 0.f;
             }
         } else {
-            // independent requests first: this node's ids, columns and previous probabilities
-            int id = 0, col = 0;
-            if (lane < K) {
-                id = p.ids[gn * K + lane];
-                col = p.cols[gn * K + lane];
-            }
+            // this node's ids, columns and previous probabilities were requested a round ago
+            const int id = id_next;
+            int col = col_next;
 #pragma unroll
-            for (int k = 0; k < KC; ++k) prev[k] = (k < K) ? p.prev[gn * K + k] : 0.f;
+            for (int k = 0; k < KC; ++k) prev[k] = (k < K) ? prev_next[k] : 0.f;
             // lanes 0..K-1: one logit each; lane K: the sum of squares
             float a = 0.f;
             bool bad = M > p.Mcap;
@@ -200,6 +210,7 @@ __global__ __launch_bounds__(WHOLE ? 512 : 256) void tree_finish_kernel(TreeFini
                 z[k] = (k < K) ? (bad ? quiet_nan() : v * r) : 0.f;
             }
         }
+        if (!WHOLE && n + kWaves < n_end) request_node(n + kWaves);
         const int ex = finish_score_node<KC>(fr, p, gn, z, prev, lane);
         if (WHOLE && lane == kWave - 1) exit_lds[n] = ex;
     }
