@@ -27,10 +27,16 @@ constexpr int kPredictWaves = kPredictThreads / kWave;
 // EXACT: K == KC is known at compile time (the common K = 4 and K = 8): every `k < K` predicate and
 // the generic MLP path fold away, which shortens the serial instruction stream of this latency-bound
 // kernel.
-template <int KC, int VPT, bool SWEEP, bool EXACT>
-__global__ __launch_bounds__(kPredictThreads) void predict_kernel(PredictParams p) {
-    __shared__ float red[kPredictWaves][2 * KC + 2];
-    __shared__ float red_u[kPredictWaves];
+// T: threads per workgroup.  512 gives the shortest single call (one vector of a 4096-wide row and one
+// hidden unit per thread).  With thousands of tokens per launch 256 is faster: twice as many
+// workgroups fit on a CU, so more independent chains of the two memory trips are in flight, and the
+// redundant feature arithmetic and the barriers halve; a thread then owns MU = 2 hidden units, both
+// requested up front.
+template <int KC, int VPT, bool SWEEP, bool EXACT, int T = kPredictThreads, int MU = 1>
+__global__ __launch_bounds__(T) void predict_kernel(PredictParams p) {
+    constexpr int kWaves = T / kWave;
+    __shared__ float red[kWaves][2 * KC + 2];
+    __shared__ float red_u[kWaves];
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -72,15 +78,16 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(PredictParams 
     const half_t *W1 = p.W1 + (size_t)l * H * 3 * K;
     const half_t *w2 = p.w2 + (size_t)l * H;
     const half_t *b1 = p.b1 ? p.b1 + (size_t)l * H : nullptr;
-    MlpRow<KC> row0;
-    mlp_row_load<KC>(row0, W1, b1, w2, K, H, tid);
+    MlpRow<KC> rowm[MU];
+#pragma unroll
+    for (int m = 0; m < MU; ++m) mlp_row_load<KC>(rowm[m], W1, b1, w2, K, H, tid + m * T);
 
     const half_t *hrow = p.hidden + tok * d;
     const half_t *hprow = (SWEEP && lprev >= 0) ? p.hidden + ((size_t)lprev * p.B + b) * d : nullptr;
     half8 hv[VPT], gv[VPT], hp[VPT];
 #pragma unroll
     for (int u = 0; u < VPT; ++u) {
-        int v = tid + u * kPredictThreads;
+        int v = tid + u * T;
         bool in = v < nv;
         hv[u] = in ? load_half8(hrow + v * 8) : zero_half8();
         gv[u] = in ? load_half8(p.gamma + v * 8) : zero_half8();
@@ -125,7 +132,7 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(PredictParams 
     for (int k = 0; k < KC; ++k)
 #pragma unroll
         for (int u = 0; u < VPT; ++u) {
-            int v = tid + u * kPredictThreads;
+            int v = tid + u * T;
             wv[k][u] = (k < K && v < nv) ? load_half8(rows[k] + v * 8) : zero_half8();
         }
 
@@ -155,7 +162,7 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(PredictParams 
             }
         }
     // d larger than VPT * 512 vectors: remaining tiles, same arithmetic
-    for (int v = tid + VPT * kPredictThreads; v < nv; v += kPredictThreads) {
+    for (int v = tid + VPT * T; v < nv; v += T) {
         half8 h8 = load_half8(hrow + v * 8), g8 = load_half8(p.gamma + v * 8);
         half8 hp8 = (SWEEP && hprow) ? load_half8(hprow + v * 8) : zero_half8();
         half8 w8[KC];
@@ -199,7 +206,7 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(PredictParams 
 #pragma unroll
     for (int k = 0; k < KC; ++k) acc[k] = acc_p[k] = 0.f;
 #pragma unroll
-    for (int w = 0; w < kPredictWaves; ++w) {
+    for (int w = 0; w < kWaves; ++w) {
         ssq += red[w][0];
         if (SWEEP) ssq_p += red[w][1];
 #pragma unroll
@@ -227,7 +234,7 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(PredictParams 
     }
 
     // ---- MLP: thread j owns hidden unit j (+512, ...); f = [z | p | p - prev]
-    float part = mlp_partial<KC, kPredictThreads>(row0, W1, b1, w2, K, H, tid, z, pr, prev);
+    float part = mlp_partial<KC, T, MU>(rowm, W1, b1, w2, K, H, tid, z, pr, prev);
     part = wave_sum_to_last_row(part);
     if (lane == kWave - 1) red_u[wave] = part;
     __syncthreads();
@@ -235,7 +242,7 @@ __global__ __launch_bounds__(kPredictThreads) void predict_kernel(PredictParams 
     if (tid == 0) {
         float u = p.b2 ? (float)p.b2[l] : 0.f;
 #pragma unroll
-        for (int w = 0; w < kPredictWaves; ++w) u += red_u[w];
+        for (int w = 0; w < kWaves; ++w) u += red_u[w];
         float s = sigmoidf(u);
         p.scores[tok] = s;
         p.exit_flags[tok] = (s > p.threshold) ? 1 : 0;
@@ -270,8 +277,8 @@ __global__ __launch_bounds__(kPredictThreads) void predict_q4_kernel(PredictPara
     const int nv = d >> 3, ng = d / p.group;
 
     // ---- requests that do not depend on the ids
-    MlpRow<KC> row0;
-    mlp_row_load<KC>(row0, p.W1, p.b1, p.w2, K, H, tid);
+    MlpRow<KC> rowm[1];
+    mlp_row_load<KC>(rowm[0], p.W1, p.b1, p.w2, K, H, tid);
     const half_t *hrow = p.hidden + (size_t)b * d;
     half8 hv[VPT], gv[VPT];
     int vc[VPT];
@@ -402,7 +409,7 @@ __global__ __launch_bounds__(kPredictThreads) void predict_q4_kernel(PredictPara
 #pragma unroll
     for (int k = 0; k < KC; ++k) z[k] = bad_id ? quiet_nan() : acc[k] * r;
     local_softmax<KC>(z, K, pr);
-    float part = mlp_partial<KC, kPredictThreads>(row0, p.W1, p.b1, p.w2, K, H, tid, z, pr, prev);
+    float part = mlp_partial<KC, kPredictThreads, 1>(rowm, p.W1, p.b1, p.w2, K, H, tid, z, pr, prev);
     part = wave_sum_to_last_row(part);
     if (lane == kWave - 1) red_u[wave] = part;
     __syncthreads();
@@ -435,10 +442,23 @@ __global__ void first_exit_kernel(const int32_t *exit_flags, int L, int B, int32
     first_exit[b] = f;
 }
 
+constexpr int kBatchMinTokens = 1024;  // tokens per launch from which the 256-thread shape is used
+
 template <int KC, bool SWEEP, bool EXACT>
 static hipError_t launch_vpt(const PredictParams &p, hipStream_t s) {
     dim3 grid(p.B, p.L), block(kPredictThreads);
     const int nv = p.d >> 3;
+    if constexpr (!SWEEP && EXACT && KC <= 8) {
+        // throughput shape: K in {4, 8}, many tokens, rows of at most 4 * 256 vectors (d <= 8192)
+        if (p.B >= kBatchMinTokens && nv <= 2 * 256 * (KC == 4 ? 2 : 1)) {
+            const dim3 blk(256);
+            if (nv <= 2 * 256)
+                hipLaunchKernelGGL((predict_kernel<KC, 2, false, true, 256, 2>), grid, blk, 0, s, p);
+            else
+                hipLaunchKernelGGL((predict_kernel<KC, 4, false, true, 256, 2>), grid, blk, 0, s, p);
+            return hipGetLastError();
+        }
+    }
     const int vpt = (nv + kPredictThreads - 1) / kPredictThreads;
     if (vpt <= 1)
         hipLaunchKernelGGL((predict_kernel<KC, 1, SWEEP, EXACT>), grid, block, 0, s, p);

@@ -96,14 +96,17 @@ __device__ __forceinline__ float mlp_unit(const MlpRow<KC> &r, const half_t *W1,
 }
 
 // This thread's share of the output pre-activation: units tid, tid+T, ...
-// `first` holds the prefetched row of unit tid.
-template <int KC, int T>
-__device__ __forceinline__ float mlp_partial(const MlpRow<KC> &first, const half_t *W1, const half_t *b1,
+// `first[0..MU)` hold the prefetched rows of units tid, tid+T, ..., tid+(MU-1)*T; further units (H
+// larger than MU*T) are fetched here.
+template <int KC, int T, int MU>
+__device__ __forceinline__ float mlp_partial(const MlpRow<KC> (&first)[MU], const half_t *W1, const half_t *b1,
                                              const half_t *w2, int K, int H, int tid, const float (&z)[KC],
                                              const float (&pr)[KC], const float (&prev)[KC]) {
     float part = 0.f;
-    if (tid < H) part = mlp_unit<KC>(first, W1, K, tid, z, pr, prev);
-    for (int j = tid + T; j < H; j += T) {
+#pragma unroll
+    for (int m = 0; m < MU; ++m)
+        if (tid + m * T < H) part += mlp_unit<KC>(first[m], W1, K, tid + m * T, z, pr, prev);
+    for (int j = tid + MU * T; j < H; j += T) {
         MlpRow<KC> r;
         mlp_row_load<KC>(r, W1, b1, w2, K, H, j);
         part += mlp_unit<KC>(r, W1, K, j, z, pr, prev);
