@@ -267,24 +267,26 @@ __global__ __launch_bounds__(T) void predict_kernel(PredictParams p) {
 // EXACT: K == KC at compile time (see predict_kernel).  Every load is unconditional on a clamped, valid
 // address -- a load under a branch would make the compiler wait for all outstanding loads at the join
 // and turn the K rows into K serial trips to memory; unused data is zeroed by selects instead.
-template <int KC, int VPT, bool EXACT>
-__global__ __launch_bounds__(kPredictThreads) void predict_q4_kernel(PredictParams p) {
-    __shared__ float red[kPredictWaves][KC + 1];
-    __shared__ float red_u[kPredictWaves];
+template <int KC, int VPT, bool EXACT, int T = kPredictThreads, int MU = 1>
+__global__ __launch_bounds__(T) void predict_q4_kernel(PredictParams p) {
+    constexpr int kWaves = T / kWave;
+    __shared__ float red[kWaves][KC + 1];
+    __shared__ float red_u[kWaves];
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
     const int b = blockIdx.x;
     const int K = EXACT ? KC : p.K, H = p.H, d = p.d;
     const int nv = d >> 3, ng = d / p.group;
 
     // ---- requests that do not depend on the ids
-    MlpRow<KC> rowm[1];
-    mlp_row_load<KC>(rowm[0], p.W1, p.b1, p.w2, K, H, tid);
+    MlpRow<KC> rowm[MU];
+#pragma unroll
+    for (int m = 0; m < MU; ++m) mlp_row_load<KC>(rowm[m], p.W1, p.b1, p.w2, K, H, tid + m * T);
     const half_t *hrow = p.hidden + (size_t)b * d;
     half8 hv[VPT], gv[VPT];
     int vc[VPT];
 #pragma unroll
     for (int u = 0; u < VPT; ++u) {
-        const int v = tid + u * kPredictThreads;
+        const int v = tid + u * T;
         vc[u] = min(v, nv - 1);
         const half8 h8 = load_half8(hrow + vc[u] * 8), g8 = load_half8(p.gamma + vc[u] * 8);
         hv[u] = v < nv ? h8 : zero_half8();  // a zero hidden state silences the clamped duplicate
@@ -371,7 +373,7 @@ __global__ __launch_bounds__(kPredictThreads) void predict_q4_kernel(PredictPara
         dot8(hv[u], gv[u], w, sc, zp);
     }
     // d larger than VPT * 512 vectors: remaining tiles, same arithmetic
-    for (int v = tid + VPT * kPredictThreads; v < nv; v += kPredictThreads) {
+    for (int v = tid + VPT * T; v < nv; v += T) {
         const half8 h8 = load_half8(hrow + v * 8), g8 = load_half8(p.gamma + v * 8);
         uint32_t w[KC];
         half_t sc[KC], zp[KC];
@@ -399,7 +401,7 @@ __global__ __launch_bounds__(kPredictThreads) void predict_q4_kernel(PredictPara
 #pragma unroll
     for (int k = 0; k < KC; ++k) acc[k] = 0.f;
 #pragma unroll
-    for (int w = 0; w < kPredictWaves; ++w) {
+    for (int w = 0; w < kWaves; ++w) {
         ssq += red[w][0];
 #pragma unroll
         for (int k = 0; k < KC; ++k) acc[k] += red[w][1 + k];
@@ -409,14 +411,14 @@ __global__ __launch_bounds__(kPredictThreads) void predict_q4_kernel(PredictPara
 #pragma unroll
     for (int k = 0; k < KC; ++k) z[k] = bad_id ? quiet_nan() : acc[k] * r;
     local_softmax<KC>(z, K, pr);
-    float part = mlp_partial<KC, kPredictThreads, 1>(rowm, p.W1, p.b1, p.w2, K, H, tid, z, pr, prev);
+    float part = mlp_partial<KC, T, MU>(rowm, p.W1, p.b1, p.w2, K, H, tid, z, pr, prev);
     part = wave_sum_to_last_row(part);
     if (lane == kWave - 1) red_u[wave] = part;
     __syncthreads();
     if (tid == 0) {
         float u = p.b2 ? (float)p.b2[0] : 0.f;
 #pragma unroll
-        for (int w = 0; w < kPredictWaves; ++w) u += red_u[w];
+        for (int w = 0; w < kWaves; ++w) u += red_u[w];
         const float sc = sigmoidf(u);
         p.scores[b] = sc;
         p.exit_flags[b] = (sc > p.threshold) ? 1 : 0;
@@ -442,7 +444,10 @@ __global__ void first_exit_kernel(const int32_t *exit_flags, int L, int B, int32
     first_exit[b] = f;
 }
 
-constexpr int kBatchMinTokens = 1024;  // tokens per launch from which the 256-thread shape is used
+constexpr int kBatchMinTokens = 1024;
+#ifndef Q4T
+#define Q4T 128
+#endif  // tokens per launch from which the 256-thread shape is used
 
 template <int KC, bool SWEEP, bool EXACT>
 static hipError_t launch_vpt(const PredictParams &p, hipStream_t s) {
@@ -486,6 +491,19 @@ template <int KC, bool EXACT>
 static hipError_t launch_q4_kc(const PredictParams &p, hipStream_t s) {
     const dim3 grid(p.B), block(kPredictThreads);
     const int nv = p.d >> 3;
+    if constexpr (EXACT && KC == 4) {
+        // throughput shape (see predict_kernel): a quantised row is a quarter of the bytes, so the fixed
+        // cost per workgroup weighs more and small workgroups pay: 128 threads per token, four words per
+        // row and thread, four hidden units per thread (B=8000 at d=4096: 51 -> 37 us)
+        if (p.B >= kBatchMinTokens && nv <= 4 * 128) {
+            hipLaunchKernelGGL((predict_q4_kernel<4, 4, true, 128, 4>), grid, dim3(128), 0, s, p);
+            return hipGetLastError();
+        }
+        if (p.B >= kBatchMinTokens && nv <= 4 * 256) {
+            hipLaunchKernelGGL((predict_q4_kernel<4, 4, true, 256, 2>), grid, dim3(256), 0, s, p);
+            return hipGetLastError();
+        }
+    }
     if (nv <= kPredictThreads)
         hipLaunchKernelGGL((predict_q4_kernel<KC, 1, EXACT>), grid, block, 0, s, p);
     else

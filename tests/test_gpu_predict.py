@@ -88,6 +88,32 @@ def test_predict_c1_llama7b_shape(sp, oracle):
     assert 0 < exits < 8
 
 
+@pytest.mark.parametrize("d,K,B,bias", [(8192, 4, 1100, True), (4096, 8, 1030, False), (2056, 4, 1500, True),
+                                        (8192, 8, 1024, False)])
+def test_predict_large_batch_shapes(sp, oracle, d, K, B, bias):
+    """More than a thousand tokens per launch take the 256-thread shape where it exists (K in {4, 8}, two or
+    four vectors per thread, two hidden units per thread); every path must agree with the oracle, with done
+    flags and with an invalid id."""
+    t = custom(d + K + B, d, 700, K, 512, B, bias)
+    lm_d = dev(t["lm_head"])
+    got = run_predict(sp, t, lm_d)
+    pick = np.array([0, 1, 255, 256, 1023, B - 1])
+    sub = dict(t, hidden=t["hidden"][pick], ids=t["ids"][pick], prev_probs=t["prev_probs"][pick])
+    check_scored({k: v[pick] for k, v in got.items()}, oracle.predict(**sub, eps=1e-5, threshold=0.5), 0.5,
+                 f"large batch d={d} K={K}")
+    assert np.all(np.isfinite(got["scores"]))
+    done = (np.arange(B) % 5 == 0).astype(np.int32)
+    bad = dict(t, ids=t["ids"].copy())
+    bad["ids"][7, K - 1] = 700
+    got_d = run_predict(sp, bad, lm_d, done=dev(done))
+    on = done == 0
+    on[7] = False
+    for k in ("logits", "probs", "scores", "exit"):
+        assert np.array_equal(got_d[k][on], got[k][on]), k
+    assert np.all(got_d["scores"][done != 0] == 0) and np.isnan(got_d["scores"][7])
+    assert np.array_equal(got_d["probs"][done != 0], t["prev_probs"][done != 0])
+
+
 def test_predict_throughput_configuration_sampled_tokens(sp, oracle):
     """The batched launch the benchmark times (8000 tokens, ids distinct across the batch): every output of
     a sample of tokens against the oracle, and cheap whole-batch properties."""

@@ -118,6 +118,16 @@ def test_q4_batch_of_8000_sampled_tokens(sp, oracle):
     assert np.all(np.isfinite(got["scores"])) and np.allclose(got["probs"].sum(axis=1), 1, atol=1e-5)
 
 
+def test_q4_large_batch_wide_rows(sp, oracle):
+    """d = 8192 with more than a thousand tokens takes the 256-thread shape (four words per row and thread)."""
+    t = case(77, 8192, 600, 4, 512, 1100, 128, True)
+    got = run(sp, t)
+    pick = np.array([0, 1, 511, 1023, 1024, 1099])
+    sub = dict(t, hidden=t["hidden"][pick], ids=t["ids"][pick], prev_probs=t["prev_probs"][pick])
+    check_scored({k: v[pick] for k, v in got.items()}, ref(oracle, sub), 0.5, "q4 d=8192 B=1100")
+    assert np.all(np.isfinite(got["scores"]))
+
+
 def test_q4_argument_errors(sp):
     t = case(1, 64, 20, 2, 8, 2, 16, False)
     qd = (words(t["q"]), dev(t["scales"]), dev(t["zeros"]))
