@@ -65,7 +65,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (--gpus 1); the predictor shards by token with no "
-              "communication, see DESIGN.md", file=sys.stderr)
+              "communication", file=sys.stderr)
         sys.exit(2)
 
     import torch
@@ -168,7 +168,7 @@ def main():
             "config": {"workload": "C2: 32-layer exit sweep for one token, d=4096 V=32000 K=4, MLP 12->512->1, "
                                    "32 dependent specee_predict launches per step (HIP graph replay), "
                                    f"{R} rotating input sets", "batch": 1, "layers": L},
-            "roofline": {"bound": "hbm", "kernel": "predict_kernel<4,1,false>", "achieved": achieved,
+            "roofline": {"bound": "hbm", "kernel": "predict_kernel<4,1,false,true>", "achieved": achieved,
                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                          "algorithmic_bytes_per_launch": alg,
                          "traffic": MEASURED_TRAFFIC.get("predict_c2"),
@@ -519,6 +519,16 @@ def main():
     if result is None:
         result = {"metric": "section run", "value": None, "unit": "", "n_gpus": 1, "steps": args.steps,
                   "warmup": args.warmup, "config": {"workload": ",".join(sorted(only))}}
+    # the same kernel where bandwidth, not latency, is the bound: thousands of tokens per launch
+    tp8 = extra.get("throughput_predict_7b", {}).get("B=8000")
+    if tp8 and "roofline" in result:
+        result["roofline_throughput"] = {
+            "bound": "hbm", "kernel": "predict_kernel<4,2,false,true,256,2>, 8000 tokens per launch (distinct ids)",
+            "achieved": tp8["achieved_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": tp8["frac_of_8TBps"],
+            "algorithmic_bytes_per_launch": tp8["algorithmic_bytes"], "us_per_launch": tp8["us_per_launch"],
+            "traffic": MEASURED_TRAFFIC.get("predict_B8000"),
+            "note": "random gathers of 8 KB rows with no dependent trip reach 86 % of 8 TB/s on this chip "
+                    "(streaming probe); the predictor makes two dependent trips per token"}
     result["extra"] = extra
     result["cpu_baseline"] = cpu
     result["setup_s"] = time.time() - t_setup

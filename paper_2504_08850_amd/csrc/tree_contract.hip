@@ -128,12 +128,14 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     constexpr int kPrevPt = MODE == 3 ? kTcFusedMax / kTcThreads : 1;
     float prev_r[kPrevPt];
     int par_r = -1;
+    half_t b2_r = (half_t)0.f;  // output bias, widened where it is used
     if (MODE == 3) {
         const int n_ids = p.N * p.K;
 #pragma unroll
         for (int e = 0; e < kPrevPt; ++e) prev_r[e] = f.prev[(size_t)g * n_ids + min(tid + e * kTcThreads, n_ids - 1)];
         const int32_t *pp = f.path_exit ? f.parent + (size_t)g * p.N + min(tid, p.N - 1) : p.ids;
         par_r = *pp;
+        b2_r = *(f.b2 ? f.b2 : p.gamma);
         if (tid < 64) bad_lds[tid] = 0;
     }
 
@@ -480,7 +482,38 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
         const size_t gn = (size_t)g * N + n;
         bool poisoned = false;
         float z[KC], pr[KC];
-        if (q == 0 && kh == 0) {
+        float zq = 0.f, pq = 0.f;  // KC <= 4: this lane's own slot k = q
+        if (KC <= 4 && kh == 0) {
+            // one slot per lane group: lane (c, q) handles slot k = q of node c, and the softmax over the
+            // K slots runs across the four lanes c, c+16, c+32, c+48
+            const int k = q;
+            const bool slot = k < K;
+            const float r = 1.0f / sqrtf(ssq_lds[n] / (float)d + p.eps);
+            const bool bad = overflow || (n < N && bad_lds[n] != 0);
+            float v = 0.f;
+            if (slot && n < N) {
+                int col = cols_lds[n * K + k];
+                col = (col >= 0 && col < ROWS) ? col : 0;
+                v = bad ? quiet_nan() : Zl[n * ROWS + col] * r;
+            }
+            float zm = slot ? v : -INFINITY;  // fmaxf drops NaN; the sums below carry it to every lane
+            zm = fmaxf(zm, __shfl_xor(zm, 16, kWave));
+            zm = fmaxf(zm, __shfl_xor(zm, 32, kWave));
+            float e = slot ? __expf(v - zm) : 0.f;
+            float es = e + __shfl_xor(e, 16, kWave);
+            es += __shfl_xor(es, 32, kWave);
+            zq = v;
+            pq = e * __frcp_rn(es);
+            poisoned = bad;
+            if (slot) {
+                const float pv = n < N ? prev_lds[n * K + k] : 0.f;
+                F[c * kMlpFeat + k] = zq;
+                F[c * kMlpFeat + K + k] = pq;
+                F[c * kMlpFeat + 2 * K + k] = pq - pv;
+            }
+            for (int t = 3 * K + q; t < kMlpFeat; t += 4) F[c * kMlpFeat + t] = 0.f;
+            if (kPadded && mlp_in_lds && q == 0) F[c * kMlpFeat + 3 * K] = 1.f;  // same lane as the zero fill of that slot
+        } else if (q == 0 && kh == 0) {
             const float r = 1.0f / sqrtf(ssq_lds[n] / (float)d + p.eps);
             const bool bad = overflow || (n < N && bad_lds[n] != 0);
 #pragma unroll
@@ -520,20 +553,26 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
             __syncthreads();
             if (kh == 0) u += ssq_lds[n];
         }
+        if (KC <= 4 && kh == 0 && q < K && n < N) {
+            f.logits[gn * K + q] = zq;
+            f.probs[gn * K + q] = pq;
+        }
         if (q == 0 && kh == 0 && n < N) {
-            const float b2 = f.b2 ? (float)f.b2[0] : 0.f;
+            const float b2 = f.b2 ? (float)b2_r : 0.f;
             float sc = sigmoidf(b2 + u);
             if (poisoned) sc = quiet_nan();
             const int ex = (sc > f.threshold) ? 1 : 0;
             f.scores[gn] = sc;
             f.exit_flags[gn] = ex;
             exit_lds[n] = ex;
+            if (KC > 4) {
 #pragma unroll
-            for (int k = 0; k < KC; ++k)
-                if (k < K) {
-                    f.logits[gn * K + k] = z[k];
-                    f.probs[gn * K + k] = pr[k];
-                }
+                for (int k = 0; k < KC; ++k)
+                    if (k < K) {
+                        f.logits[gn * K + k] = z[k];
+                        f.probs[gn * K + k] = pr[k];
+                    }
+            }
         }
     } else {
         FinishRows<KC> fr;

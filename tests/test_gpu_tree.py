@@ -266,19 +266,20 @@ def test_tree_many_trees_c3_batch(sp, oracle):
     assert np.array_equal(got["merged"][5], single["merged"]) and np.array_equal(got["cols"][5], single["cols"])
 
 
-def test_tree_sliced_batch_is_reproducible(sp):
-    """With a few workgroups per tree, whichever finishes last adds the d-slices up -- in slice order, so
-    repeated launches give identical bits."""
+@pytest.mark.parametrize("G", [24, 64, 100])
+def test_tree_sliced_batch_is_reproducible(sp, G):
+    """With a few workgroups per tree (eight, four, two here), whichever finishes last adds the d-slices up
+    -- in slice order, so repeated launches give identical bits."""
     c = synth.CONFIGS["C3"]
     lm_h, lm_d = lm_for(c)
-    ts = [synth.make("C3", seed=300 + s, lm=lm_h) for s in range(64)]
+    ts = [synth.make("C3", seed=300 + s, lm=lm_h) for s in range(G)]
     tb = stack_trees(ts)
     first = run_tree(sp, tb, lm_d, c.Mcap)
     for _ in range(4):
         again = run_tree(sp, tb, lm_d, c.Mcap)
         for k in ("logits", "probs", "scores", "exit", "path_exit", "merged", "cols", "M"):
             assert np.array_equal(first[k], again[k], equal_nan=(first[k].dtype.kind == "f")), k
-    for g_ in (0, 31, 63):      # and the same answers as a launch of that tree alone (different path)
+    for g_ in (0, G // 2, G - 1):      # and the same answers as a launch of that tree alone (different path)
         one = dict(ts[0], hidden=ts[g_]["hidden"], ids=ts[g_]["ids"], prev_probs=ts[g_]["prev_probs"],
                    parent=ts[g_]["parent"])   # the batch shares tree 0's norm weight and predictor
         single = run_tree(sp, one, lm_d, c.Mcap)
