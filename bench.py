@@ -266,6 +266,23 @@ def main():
             byts = predict_bytes(d, K, B, distinct_rows=len(np.unique(ids_h)))
             tp[f"B={B}"] = {"us_per_launch": us, "evals_per_s": B / us * 1e6, "algorithmic_bytes": byts,
                             "achieved_GBps": byts / us / 1e3, "frac_of_8TBps": byts / us / 1e3 / HBM_PEAK_GBS}
+        # B=8000 touches every row of the 262 MB head, most of which the 256 MB last-level cache can keep from
+        # one launch to the next; alternating between two different heads takes that help away
+        lm_b = up(synth.lm_head(V, d, synth.lm_seed(c2) + 1))
+        B = 8000
+        rng = np.random.default_rng(B)
+        hid = up(rng.standard_normal((B, d), dtype=np.float32).astype(np.float16))
+        ids_h = rng.permutation(V)[:B * K].reshape(B, K).astype(np.int32)
+        ids, prev = up(ids_h), up(synth.prob_rows(B, K, 9))
+        o = sp.predict(hid, gamma, lm, ids, prev, w1_1, w2_1)
+        g = capture(lambda: [sp.predict(hid, gamma, lm if r % 2 == 0 else lm_b, ids, prev, w1_1, w2_1, out=o)
+                             for r in range(8)])
+        us = ev_time(g.replay, 20, 3) * 1e3 / 8
+        byts = predict_bytes(d, K, B, distinct_rows=B * K)
+        tp["B=8000_two_heads_alternating"] = {"us_per_launch": us, "evals_per_s": B / us * 1e6,
+                                              "algorithmic_bytes": byts, "achieved_GBps": byts / us / 1e3,
+                                              "frac_of_8TBps": byts / us / 1e3 / HBM_PEAK_GBS}
+        del lm_b
         tp["traffic_B8000"] = MEASURED_TRAFFIC.get("predict_B8000")
         extra["throughput_predict_7b"] = tp
 
@@ -520,15 +537,20 @@ def main():
         result = {"metric": "section run", "value": None, "unit": "", "n_gpus": 1, "steps": args.steps,
                   "warmup": args.warmup, "config": {"workload": ",".join(sorted(only))}}
     # the same kernel where bandwidth, not latency, is the bound: thousands of tokens per launch
-    tp8 = extra.get("throughput_predict_7b", {}).get("B=8000")
+    tp_all = extra.get("throughput_predict_7b", {})
+    tp8 = tp_all.get("B=8000_two_heads_alternating") or tp_all.get("B=8000")
     if tp8 and "roofline" in result:
         result["roofline_throughput"] = {
-            "bound": "hbm", "kernel": "predict_kernel<4,2,false,true,256,2>, 8000 tokens per launch (distinct ids)",
+            "bound": "hbm", "kernel": "predict_kernel<4,2,false,true,256,2>, 8000 tokens per launch (distinct ids), launches "
+                                     "alternating between two LM heads so that the last-level cache cannot keep one",
             "achieved": tp8["achieved_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": tp8["frac_of_8TBps"],
             "algorithmic_bytes_per_launch": tp8["algorithmic_bytes"], "us_per_launch": tp8["us_per_launch"],
             "traffic": MEASURED_TRAFFIC.get("predict_B8000"),
             "note": "random gathers of 8 KB rows with no dependent trip reach 86 % of 8 TB/s on this chip "
-                    "(streaming probe); the predictor makes two dependent trips per token"}
+                    "(streaming probe); the predictor makes two dependent trips per token; with one head "
+                    "re-used by every launch the same kernel reads " +
+                    (f"{tp_all['B=8000']['frac_of_8TBps'] * 100:.0f} %" if "B=8000" in tp_all else "more") +
+                    " because most of the 262 MB head stays in the 256 MB last-level cache"}
     result["extra"] = extra
     result["cpu_baseline"] = cpu
     result["setup_s"] = time.time() - t_setup
