@@ -75,9 +75,12 @@ __global__ __launch_bounds__(T) void predict_kernel(PredictParams p) {
 
     // ---- the ids (and the token's done flag) are requested before anything else: the LM-head rows, the
     // longest chain of the kernel, hang on them
+    // (single layer only: in the sweep the compiler would wait for them before requesting anything else)
     int idv[KC];
+    if (!SWEEP) {
 #pragma unroll
-    for (int k = 0; k < KC; ++k) idv[k] = (k < K) ? p.ids[(size_t)(SWEEP ? b : tok) * K + k] : 0;
+        for (int k = 0; k < KC; ++k) idv[k] = (k < K) ? p.ids[(size_t)tok * K + k] : 0;
+    }
 
     // ---- requests that do not depend on the ids
     const half_t *W1 = p.W1 + (size_t)l * H * 3 * K;
@@ -116,7 +119,7 @@ __global__ __launch_bounds__(T) void predict_kernel(PredictParams p) {
     bool bad_id = false;
 #pragma unroll
     for (int k = 0; k < KC; ++k) {
-        int id = idv[k];
+        int id = SWEEP ? ((k < K) ? p.ids[(size_t)b * K + k] : 0) : idv[k];
         bool ok = id >= 0 && id < p.V;
         if (k < K && !ok) bad_id = true;
         rows[k] = p.lm_head + (size_t)(ok ? id : 0) * d;
