@@ -18,7 +18,6 @@
 namespace specee {
 
 constexpr int kPredictThreads = 512;
-constexpr int kPredictWaves = kPredictThreads / kWave;
 
 // KC: speculative rows held in flight (K <= KC).  VPT: 16-byte vectors per
 // thread per row (d/8 <= VPT * 512 * tiles).  SWEEP: the previous layer's local
@@ -263,6 +262,59 @@ __global__ __launch_bounds__(T) void predict_kernel(PredictParams p) {
     }
 }
 
+// Shared tail of the quantised-row kernels: wavefront and workgroup sums (fixed order), RMSNorm scale,
+// features, MLP, sigmoid, threshold, outputs.  All threads of the workgroup must call.
+template <int KC, int T, int MU>
+__device__ __forceinline__ void q4_tail(const PredictParams &p, int b, int K, float ssq, float (&acc)[KC], bool bad_id,
+                                        const MlpRow<KC> (&rowm)[MU], const float (&prev)[KC],
+                                        float (*red)[KC + 1], float *red_u) {
+    constexpr int kWaves = T / kWave;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    const int H = p.H, d = p.d;
+    // ---- wavefront reduction, then fixed-order combination of the eight wave partials
+    ssq = wave_sum_to_last_row(ssq);
+#pragma unroll
+    for (int k = 0; k < KC; ++k) acc[k] = wave_sum_to_last_row(acc[k]);
+    if (lane == kWave - 1) {
+        red[wave][0] = ssq;
+#pragma unroll
+        for (int k = 0; k < KC; ++k) red[wave][1 + k] = acc[k];
+    }
+    __syncthreads();
+    ssq = 0.f;
+#pragma unroll
+    for (int k = 0; k < KC; ++k) acc[k] = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        ssq += red[w][0];
+#pragma unroll
+        for (int k = 0; k < KC; ++k) acc[k] += red[w][1 + k];
+    }
+    float z[KC], pr[KC];
+    const float r = 1.0f / sqrtf(ssq * (1.0f / (float)d) + p.eps);
+#pragma unroll
+    for (int k = 0; k < KC; ++k) z[k] = bad_id ? quiet_nan() : acc[k] * r;
+    local_softmax<KC>(z, K, pr);
+    float part = mlp_partial<KC, T, MU>(rowm, p.W1, p.b1, p.w2, K, H, tid, z, pr, prev);
+    part = wave_sum_to_last_row(part);
+    if (lane == kWave - 1) red_u[wave] = part;
+    __syncthreads();
+    if (tid == 0) {
+        float u = p.b2 ? (float)p.b2[0] : 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) u += red_u[w];
+        const float sc = sigmoidf(u);
+        p.scores[b] = sc;
+        p.exit_flags[b] = (sc > p.threshold) ? 1 : 0;
+#pragma unroll
+        for (int k = 0; k < KC; ++k)
+            if (k < K) {
+                p.logits[(size_t)b * K + k] = z[k];
+                p.probs[(size_t)b * K + k] = pr[k];
+            }
+    }
+}
+
 // The predictor on a 4-bit group-quantised LM head (the quantised setting of the paper's cloud
 // evaluation, Sec. 7.1 / 7.3; the storage format is this library's reading): element i of a row is a
 // code c in 0..15 in bits 4*(i%8).. of 32-bit word i/8 and stands for scale[g] * (c - zero[g]),
@@ -280,7 +332,7 @@ __global__ __launch_bounds__(T) void predict_q4_kernel(PredictParams p) {
     constexpr int kWaves = T / kWave;
     __shared__ float red[kWaves][KC + 1];
     __shared__ float red_u[kWaves];
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    const int tid = threadIdx.x;
     const int b = blockIdx.x;
     const int K = EXACT ? KC : p.K, H = p.H, d = p.d;
     const int nv = d >> 3, ng = d / p.group;
@@ -395,48 +447,127 @@ __global__ __launch_bounds__(T) void predict_q4_kernel(PredictParams p) {
         dot8(h8, g8, w, sc, zp);
     }
 
-    // ---- wavefront reduction, then fixed-order combination of the eight wave partials
-    ssq = wave_sum_to_last_row(ssq);
+    q4_tail<KC, T, MU>(p, b, K, ssq, acc, bad_id, rowm, prev, red, red_u);
+}
+
+// Throughput shape of predict_q4_kernel (thousands of tokens per launch).  A thread owns chunks of 32
+// consecutive elements = four consecutive words of codes: one 16-byte load per row brings its codes, and
+// because a chunk lies inside one quantisation group (group % 32 == 0) one scale and one zero-point per
+// row serve all 32 elements.  Per token that is a third of the load instructions of the word-per-thread
+// layout (the small scale / zero-point loads dominate there), and the vector memory path, not HBM, is
+// what a CU runs out of first with rows this short.  CPT: chunks per thread (d <= 32 * T * CPT).
+template <int KC, int T, int CPT, int MU>
+__global__ __launch_bounds__(T) void predict_q4_wide_kernel(PredictParams p) {
+    constexpr int kWaves = T / kWave;
+    constexpr int K = KC;
+    __shared__ float red[kWaves][KC + 1];
+    __shared__ float red_u[kWaves];
+    const int tid = threadIdx.x;
+    const int b = blockIdx.x;
+    const int H = p.H, d = p.d;
+    const int nc = d >> 5, nv = d >> 3, ng = d / p.group;
+
+    // ---- requests that do not depend on the ids
+    MlpRow<KC> rowm[MU];
 #pragma unroll
-    for (int k = 0; k < KC; ++k) acc[k] = wave_sum_to_last_row(acc[k]);
-    if (lane == kWave - 1) {
-        red[wave][0] = ssq;
+    for (int m = 0; m < MU; ++m) mlp_row_load<KC>(rowm[m], p.W1, p.b1, p.w2, K, H, tid + m * T);
+    const half_t *hrow = p.hidden + (size_t)b * d;
+    half8 hv[CPT][4], gv[CPT][4];
+    int cc[CPT], gofs[CPT];
 #pragma unroll
-        for (int k = 0; k < KC; ++k) red[wave][1 + k] = acc[k];
+    for (int u = 0; u < CPT; ++u) {
+        const int c = tid + u * T;
+        cc[u] = min(c, nc - 1);
+        gofs[u] = (cc[u] * 32) / p.group;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const half8 h8 = load_half8(hrow + cc[u] * 32 + i * 8);
+            hv[u][i] = c < nc ? h8 : zero_half8();  // a zero hidden state silences the clamped duplicate
+            gv[u][i] = load_half8(p.gamma + cc[u] * 32 + i * 8);
+        }
     }
-    __syncthreads();
-    ssq = 0.f;
+    float prev[KC];
+#pragma unroll
+    for (int k = 0; k < KC; ++k) prev[k] = p.prev[(size_t)b * K + k];
+    const int32_t *donep = p.done ? p.done + b : p.ids;  // always a valid address
+    const int dn_raw = *donep;
+    const int dn = p.done ? dn_raw : 0;
+
+    // ---- the K speculative rows
+    int rowi[KC];
+    bool bad_id = false;
+#pragma unroll
+    for (int k = 0; k < KC; ++k) {
+        const int id = p.ids[(size_t)b * K + k];
+        const bool ok = id >= 0 && id < p.V;
+        if (!ok) bad_id = true;
+        rowi[k] = ok ? id : 0;
+    }
+    if (dn != 0) {  // uniform over the workgroup: the token already left the model
+        if (tid < K) {
+            p.logits[(size_t)b * K + tid] = 0.f;
+            p.probs[(size_t)b * K + tid] = p.prev[(size_t)b * K + tid];
+        }
+        if (tid == 0) {
+            p.scores[b] = 0.f;
+            p.exit_flags[b] = 0;
+        }
+        return;
+    }
+    uintx4 qw[KC][CPT];
+    half_t qs[KC][CPT], qz[KC][CPT];
+#pragma unroll
+    for (int k = 0; k < KC; ++k)
+#pragma unroll
+        for (int u = 0; u < CPT; ++u) {
+            const size_t gi = (size_t)rowi[k] * ng + gofs[u];
+            qw[k][u] = *reinterpret_cast<const uintx4 *>(p.qweight + (size_t)rowi[k] * nv + cc[u] * 4);
+            qs[k][u] = p.qscales[gi];
+            qz[k][u] = p.qzeros[gi];
+        }
+
+    float ssq = 0.f, acc[KC];
 #pragma unroll
     for (int k = 0; k < KC; ++k) acc[k] = 0.f;
+    // Byte j of a word holds elements 2j (low nibble) and 2j+1 (high nibble).  With a = x[2j] - x[2j+1]/16
+    // and bq = x[2j+1]/16 (computed once, shared by the K rows),
+    //     x[2j]*lo + x[2j+1]*hi = a*lo + bq*(lo + 16*hi) = a*lo + bq*byte,
+    // so a row costs one mask per word and one byte-to-float conversion plus one FMA per nibble; the
+    // high nibbles are never extracted.  This arithmetic, not memory, bounds the kernel.
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-        ssq += red[w][0];
+    for (int u = 0; u < CPT; ++u) {
+        float xs = 0.f, pd[KC];
 #pragma unroll
-        for (int k = 0; k < KC; ++k) acc[k] += red[w][1 + k];
-    }
-    float z[KC], pr[KC];
-    const float r = 1.0f / sqrtf(ssq * (1.0f / (float)d) + p.eps);
+        for (int k = 0; k < KC; ++k) pd[k] = 0.f;
 #pragma unroll
-    for (int k = 0; k < KC; ++k) z[k] = bad_id ? quiet_nan() : acc[k] * r;
-    local_softmax<KC>(z, K, pr);
-    float part = mlp_partial<KC, T, MU>(rowm, p.W1, p.b1, p.w2, K, H, tid, z, pr, prev);
-    part = wave_sum_to_last_row(part);
-    if (lane == kWave - 1) red_u[wave] = part;
-    __syncthreads();
-    if (tid == 0) {
-        float u = p.b2 ? (float)p.b2[0] : 0.f;
+        for (int i = 0; i < 4; ++i) {
+            float a[4], bq[4];
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) u += red_u[w];
-        const float sc = sigmoidf(u);
-        p.scores[b] = sc;
-        p.exit_flags[b] = (sc > p.threshold) ? 1 : 0;
-#pragma unroll
-        for (int k = 0; k < KC; ++k)
-            if (k < K) {
-                p.logits[(size_t)b * K + k] = z[k];
-                p.probs[(size_t)b * K + k] = pr[k];
+            for (int j = 0; j < 4; ++j) {
+                const half2_t hh = {hv[u][i][2 * j], hv[u][i][2 * j + 1]};
+                ssq = __builtin_amdgcn_fdot2(hh, hh, ssq, false);
+                const float x0 = (float)hh[0] * (float)gv[u][i][2 * j];
+                const float x1 = (float)hh[1] * (float)gv[u][i][2 * j + 1];
+                xs += x0 + x1;
+                bq[j] = x1 * 0.0625f;
+                a[j] = x0 - bq[j];
             }
+#pragma unroll
+            for (int k = 0; k < KC; ++k) {
+                const uint32_t w = qw[k][u][i];
+                uint32_t lo = w & 0x0f0f0f0fu;
+                asm("" : "+v"(lo));  // keeps the mask a mask: the byte selects below then fold into the conversions
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    pd[k] += a[j] * (float)((lo >> (8 * j)) & 0xffu);
+                    pd[k] += bq[j] * (float)((w >> (8 * j)) & 0xffu);
+                }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < KC; ++k) acc[k] += (float)qs[k][u] * (pd[k] - (float)qz[k][u] * xs);
     }
+    q4_tail<KC, T, MU>(p, b, K, ssq, acc, bad_id, rowm, prev, red, red_u);
 }
 
 // first_exit[b] = first layer with exit flag 1 (inactive layers carry 0), else -1
@@ -452,10 +583,7 @@ __global__ void first_exit_kernel(const int32_t *exit_flags, int L, int B, int32
     first_exit[b] = f;
 }
 
-constexpr int kBatchMinTokens = 1024;
-#ifndef Q4T
-#define Q4T 128
-#endif  // tokens per launch from which the 256-thread shape is used
+constexpr int kBatchMinTokens = 1024;  // tokens per launch from which the throughput shapes are used
 
 template <int KC, bool SWEEP, bool EXACT>
 static hipError_t launch_vpt(const PredictParams &p, hipStream_t s) {
@@ -503,6 +631,17 @@ static hipError_t launch_q4_kc(const PredictParams &p, hipStream_t s) {
         // throughput shape (see predict_kernel): a quantised row is a quarter of the bytes, so the fixed
         // cost per workgroup weighs more and small workgroups pay: 128 threads per token, four words per
         // row and thread, four hidden units per thread (B=8000 at d=4096: 51 -> 37 us)
+        // chunks of 32 elements per thread when the format allows it (group % 32 == 0, rows 16-byte aligned):
+        // B=8000 at d=4096: 37 -> 29 us, at d=8192: 71 -> 58 us
+        const bool wide_ok = p.group % 32 == 0 && p.d % 32 == 0 && (reinterpret_cast<uintptr_t>(p.qweight) & 15) == 0;
+        if (wide_ok && p.B >= kBatchMinTokens && p.d <= 32 * 128) {
+            hipLaunchKernelGGL((predict_q4_wide_kernel<4, 128, 1, 4>), grid, dim3(128), 0, s, p);
+            return hipGetLastError();
+        }
+        if (wide_ok && p.B >= kBatchMinTokens && p.d <= 32 * 256) {
+            hipLaunchKernelGGL((predict_q4_wide_kernel<4, 256, 1, 2>), grid, dim3(256), 0, s, p);
+            return hipGetLastError();
+        }
         if (p.B >= kBatchMinTokens && nv <= 4 * 128) {
             hipLaunchKernelGGL((predict_q4_kernel<4, 4, true, 128, 4>), grid, dim3(128), 0, s, p);
             return hipGetLastError();

@@ -118,14 +118,56 @@ def test_q4_batch_of_8000_sampled_tokens(sp, oracle):
     assert np.all(np.isfinite(got["scores"])) and np.allclose(got["probs"].sum(axis=1), 1, atol=1e-5)
 
 
-def test_q4_large_batch_wide_rows(sp, oracle):
-    """d = 8192 with more than a thousand tokens takes the 256-thread shape (four words per row and thread)."""
-    t = case(77, 8192, 600, 4, 512, 1100, 128, True)
+@pytest.mark.parametrize("d,V,group", [
+    (8192, 600, 128),   # 32-element chunks, 256 threads
+    (4096, 500, 32),    # 32-element chunks, 128 threads, smallest group that allows them
+    (2080, 400, 32),    # 65 chunks: half of the threads hold a clamped, silenced duplicate
+    (8192, 300, 64),
+    (4096, 500, 8),     # group too small for chunks: one word per thread and row
+    (1040, 300, 104),   # group not a multiple of 32
+])
+def test_q4_large_batch_formats(sp, oracle, d, V, group):
+    """More than a thousand tokens per launch take the throughput shapes, whichever the format allows."""
+    t = case(d + group, d, V, 4, 512, 1100, group, True)
     got = run(sp, t)
     pick = np.array([0, 1, 511, 1023, 1024, 1099])
     sub = dict(t, hidden=t["hidden"][pick], ids=t["ids"][pick], prev_probs=t["prev_probs"][pick])
-    check_scored({k: v[pick] for k, v in got.items()}, ref(oracle, sub), 0.5, "q4 d=8192 B=1100")
+    check_scored({k: v[pick] for k, v in got.items()}, ref(oracle, sub), 0.5, f"q4 d={d} group={group} B=1100")
     assert np.all(np.isfinite(got["scores"]))
+
+
+def test_q4_large_batch_done_invalid_ids_and_unaligned_codes(sp, oracle):
+    t = case(5, 4096, 300, 4, 512, 1100, 128, True)
+    qd = (words(t["q"]), dev(t["scales"]), dev(t["zeros"]))
+    got = run(sp, t, qd)
+    # the same codes at an address that is only 4-byte aligned: the word-per-thread shape takes over
+    flat = torch.empty(t["q"].size + 1, dtype=torch.int32, device="cuda")
+    flat[1:] = qd[0].reshape(-1)
+    shifted = flat[1:].reshape(qd[0].shape)
+    assert shifted.data_ptr() % 16 == 4
+    got_s = run(sp, t, (shifted, qd[1], qd[2]))
+    pick = np.array([0, 3, 600, 1099])
+    sub = dict(t, hidden=t["hidden"][pick], ids=t["ids"][pick], prev_probs=t["prev_probs"][pick])
+    r = ref(oracle, sub)
+    check_scored({k: v[pick] for k, v in got.items()}, r, 0.5, "q4 B=1100 aligned")
+    check_scored({k: v[pick] for k, v in got_s.items()}, r, 0.5, "q4 B=1100 codes at a 4-byte-aligned address")
+    assert np.allclose(got_s["logits"], got["logits"], rtol=1e-4, atol=1e-4)  # same values up to summation order
+    # done tokens are skipped, the rest unchanged
+    done = (np.arange(1100) % 5 == 0).astype(np.int32)
+    got_d = run(sp, t, qd, done=dev(done))
+    on = done == 0
+    for k in ("logits", "probs", "scores", "exit"):
+        assert np.array_equal(got_d[k][on], got[k][on]), k
+    assert np.all(got_d["logits"][~on] == 0) and np.all(got_d["scores"][~on] == 0) and np.all(got_d["exit"][~on] == 0)
+    assert np.array_equal(got_d["probs"][~on], t["prev_probs"][~on])
+    # an id outside the vocabulary poisons its token only
+    bad = dict(t, ids=t["ids"].copy())
+    bad["ids"][7, 2] = 300
+    bad["ids"][1024, 0] = -1
+    got_b = run(sp, bad, qd)
+    assert np.isnan(got_b["scores"][7]) and np.isnan(got_b["scores"][1024]) and got_b["exit"][7] == 0
+    keep = np.ones(1100, bool); keep[[7, 1024]] = False
+    assert np.array_equal(got_b["scores"][keep], got["scores"][keep])
 
 
 def test_q4_argument_errors(sp):
