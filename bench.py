@@ -557,6 +557,20 @@ def main():
         orc.lm_head_rows(hid[0], base["gamma"], lm_h, rows)
         dt = time.perf_counter() - t0
         cpu["lm_head_gemv_us_extrapolated_from_4000_rows"] = dt * 8 * 1e6
+        # context: the same oracle over independent tokens on all host cores it may use (its outer loop is
+        # an OpenMP loop over tokens); a sample of the batched workload
+        ncores = max(1, min(len(os.sched_getaffinity(0)), int(os.environ.get("OMP_NUM_THREADS", "16"))))
+        orc.set_threads(ncores)
+        Bc = 4096
+        hid_b = synth.hidden(Bc, d, 70_000)
+        ids_b = synth.ids_uniform_distinct(Bc, K, V, 70_001)
+        prev_b = synth.prob_rows(Bc, K, 70_002)
+        t0 = time.perf_counter()
+        orc.predict(hid_b, base["gamma"], lm_h, ids_b, prev_b, base["W1"][0], base["w2"][0])
+        dt = time.perf_counter() - t0
+        cpu["batched_all_cores"] = {"value": Bc / dt, "unit": "evals/s", "cores": orc.get_threads(),
+                                    "sample": f"{Bc} independent tokens (distinct ids), one layer, in {dt:.2f} s"}
+        orc.set_threads(1)
 
     if result is None:
         result = {"metric": "section run", "value": None, "unit": "", "n_gpus": 1, "steps": args.steps,
