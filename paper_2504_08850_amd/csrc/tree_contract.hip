@@ -314,48 +314,46 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
             }
         }
     } else {
-    half8 bhi[JN], blo[JN];
-    tile_to_lds(0, 0, 0);
+        half8 bhi[JN], blo[JN];
+        tile_to_lds(0, 0, 0);
 #pragma unroll
-    for (int j = 0; j < JN; ++j) build_b(0, 0, j, bhi[j], blo[j]);
-    issue_a(PD, 0);
-    issue_b(PD, 0);
-    __syncthreads();
-    int buf = 0;
-    for (int kc0 = 0; kc0 < nstages; kc0 += PD) {
+        for (int j = 0; j < JN; ++j) build_b(0, 0, j, bhi[j], blo[j]);
+        issue_a(PD, 0);
+        issue_b(PD, 0);
+        __syncthreads();
+        int buf = 0;
+        for (int kc0 = 0; kc0 < nstages; kc0 += PD) {
 #pragma unroll
-        for (int u = 0; u < PD; ++u) {
-            const int kc = kc0 + u;
-            constexpr int kDummy = 0;
-            (void)kDummy;
-            const int nslot = (u + 1) % PD;  // folds: u is an unrolled constant
-            half8 nhi[JN], nlo[JN];
-            tile_to_lds(kc + 1, nslot, buf ^ 1);
+            for (int u = 0; u < PD; ++u) {
+                const int kc = kc0 + u;
+                const int nslot = (u + 1) % PD;  // folds: u is an unrolled constant
+                half8 nhi[JN], nlo[JN];
+                tile_to_lds(kc + 1, nslot, buf ^ 1);
 #pragma unroll
-            for (int j = 0; j < JN; ++j) {
-                half8 a[MT];
+                for (int j = 0; j < JN; ++j) {
+                    half8 a[MT];
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-                    a[mt] = *reinterpret_cast<const half8 *>(&a_lds[buf][mt * 16 + c][koff(j)]);
-                build_b(kc + 1, nslot, j, nhi[j], nlo[j]);
+                    for (int mt = 0; mt < MT; ++mt)
+                        a[mt] = *reinterpret_cast<const half8 *>(&a_lds[buf][mt * 16 + c][koff(j)]);
+                    build_b(kc + 1, nslot, j, nhi[j], nlo[j]);
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-                    acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], bhi[j], acc[mt], 0, 0, 0);
+                    for (int mt = 0; mt < MT; ++mt)
+                        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], bhi[j], acc[mt], 0, 0, 0);
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-                    acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], blo[j], acc[mt], 0, 0, 0);
+                    for (int mt = 0; mt < MT; ++mt)
+                        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], blo[j], acc[mt], 0, 0, 0);
+                }
+                issue_a(kc + 1 + PD, nslot);
+                issue_b(kc + 1 + PD, nslot);
+                __syncthreads();
+#pragma unroll
+                for (int j = 0; j < JN; ++j) {
+                    bhi[j] = nhi[j];
+                    blo[j] = nlo[j];
+                }
+                buf ^= 1;
             }
-            issue_a(kc + 1 + PD, nslot);
-            issue_b(kc + 1 + PD, nslot);
-            __syncthreads();
-#pragma unroll
-            for (int j = 0; j < JN; ++j) {
-                bhi[j] = nhi[j];
-                blo[j] = nlo[j];
-            }
-            buf ^= 1;
         }
-    }
     }
     // sum of squares of node c over this k-range: combine the four k-slot groups
     ssq += __shfl_xor(ssq, 16, kWave);
