@@ -517,6 +517,36 @@ def main():
                                                 "achieved_GBps": b1 / us1 / 1e3,
                                                 "frac_of_8TBps": b1 / us1 / 1e3 / HBM_PEAK_GBS}
         extra["c5_tree_N64_V128256"]["speedup_vs_full_head_N64"] = us64 / us_tree
+        # throughput mode for this shape: G trees per launch (merged sets of ~140 rows: sixteen row tiles per
+        # workgroup, d-slices by ticket below 256 trees), two batches in rotation
+        for G in (64, 256):
+            batches, bytes_tree = [], 0
+            for b in range(2):
+                gen = torch.Generator(device=dev)
+                gen.manual_seed(9000 + 10 * G + b)
+                hid = torch.randn((G, c5.N, c5.d), device=dev, dtype=torch.float16, generator=gen)
+                ids_h = np.stack([synth.make("C5", seed=500 + b * G + i, lm=np.zeros((1, 1), np.float16))["ids"]
+                                  for i in range(G)])
+                prev = up(synth.prob_rows(G * c5.N, c5.K, 77 + b).reshape(G, c5.N, c5.K))
+                par = up(np.tile(ts[0]["parent"], (G, 1)))
+                ids_d = up(ids_h)
+                if b == 0:
+                    bytes_tree = G * c5.N * c5.d * 2 + sum(len(np.unique(x)) for x in ids_h) * c5.d * 2
+                o = sp.predict_tree(hid, g5, lm5, ids_d, prev, tw1, tw2, parent=par, Mcap=c5.Mcap)
+                wsb = o.pop("_workspace")
+                batches.append((hid, ids_d, prev, par, o, wsb))
+
+            def c5_batch():
+                for _ in range(2):
+                    for (hid, ids_d, prev, par, o, wsb) in batches:
+                        sp.predict_tree(hid, g5, lm5, ids_d, prev, tw1, tw2, parent=par, Mcap=c5.Mcap, out=o,
+                                        workspace=wsb)
+            g = capture(c5_batch)
+            us = ev_time(g.replay, 10, 2) * 1e3 / 4
+            extra[f"c5_tree_batch_G{G}"] = {"us_per_launch": us, "node_evals_per_s": G * c5.N / us * 1e6,
+                                            "bytes_with_rows_counted_per_tree": bytes_tree,
+                                            "frac_of_8TBps_rows_per_tree": bytes_tree / us / 1e3 / HBM_PEAK_GBS}
+            del batches
         del lm5
         torch.cuda.empty_cache()
 

@@ -89,6 +89,7 @@ bool tree_gemm_can_fuse_merge(int n_ids);
 hipError_t launch_tree_gemm(const GemmParams &p, int G, hipStream_t st);
 hipError_t launch_tree_finish(const TreeFinishParams &p, int G, hipStream_t st);
 bool tree_whole_supported(int N, int K, int Mcap);
+int tree_whole_row_tiles(int Mcap);
 hipError_t launch_tree_whole(const GemmParams &p, const TreeFinishParams &f, int G, hipStream_t st);
 // Full-vocabulary head for several hidden states on the matrix cores
 hipError_t launch_lm_head_gemm(int d, int V, float eps, int N, const half_t *hidden, const half_t *gamma,

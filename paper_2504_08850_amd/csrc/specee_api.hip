@@ -271,7 +271,7 @@ int specee_predict_tree(const specee_dims *dm, int G, int N, int Mcap, const spe
         if (S < 1) S = 1;
         int dslice = (((dm->d + S - 1) / S + 127) / 128) * 128;
         S = (dm->d + dslice - 1) / dslice;
-        const size_t quads = (size_t)256 * (Mcap > 64 ? 8 : 4);
+        const size_t quads = (size_t)256 * tree_whole_row_tiles(Mcap);
         const size_t part_bytes = align256((size_t)G * S * quads * 16);
         const size_t ssq_bytes = align256((size_t)G * S * 64 * sizeof(float));
         const size_t tick_bytes = align256((size_t)G * sizeof(int32_t));

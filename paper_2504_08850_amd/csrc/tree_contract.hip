@@ -29,6 +29,12 @@
 #include "tree_finish.h"
 
 namespace specee {
+#ifndef WHOLE16_PD
+#define WHOLE16_PD 4
+#endif
+#ifndef WHOLE16_T
+#define WHOLE16_T 512
+#endif
 
 constexpr int kTcFusedMax = kMergePerThread * 256;  // ids per tree when the merge is fused
 constexpr int kWholeWideMaxWgs = 256;               // one 512-thread workgroup per CU
@@ -57,7 +63,12 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     constexpr int ROWS = 16 * MT;            // LM-head rows per workgroup
     constexpr int APT = ROWS * VPR / kTcThreads;  // 16-byte A vectors per thread per stage
     constexpr int kALdsHalves = 2 * ROWS * kTcRow;
-    __shared__ __attribute__((aligned(16))) half_t smem[kALdsHalves];
+    // the row tile buffers: static up to 64 KB; sixteen row tiles need 72 KB, which only dynamic LDS offers
+    // (the launcher raises the kernel's limit)
+    constexpr bool kDynLds = MT == 16;
+    extern __shared__ __attribute__((aligned(16))) half_t dyn_smem[];
+    __shared__ __attribute__((aligned(16))) half_t static_smem[kDynLds ? 8 : kALdsHalves];
+    half_t *smem = kDynLds ? dyn_smem : static_smem;
     __shared__ int32_t cols_lds[MODE == 3 ? kTcFusedMax : 1];
     __shared__ float prev_lds[MODE == 3 ? kTcFusedMax : 1];
     __shared__ float feat_lds[MODE == 3 ? 4 * 16 * kMlpFeat : 1];
@@ -67,7 +78,7 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     __shared__ int32_t par_lds[MODE == 3 ? 64 : 1];
     __shared__ int32_t last_lds;
     __shared__ __attribute__((aligned(16))) half_t gam_lds[GL ? kGammaLds : 8];
-    static_assert(MT == 4 || MT == 8, "row tiles per workgroup");
+    static_assert(MT == 4 || MT == 8 || MT == 16, "row tiles per workgroup");
     static_assert(sizeof(half_t) * kALdsHalves >= sizeof(int32_t) * merge_lds_ints(kTcFusedMax),
                   "merge scratch must fit in the row tile buffers");
     static_assert(sizeof(half_t) * kALdsHalves >= sizeof(float) * 64 * ROWS, "whole-tree logits must fit");
@@ -314,6 +325,7 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
             }
         }
     } else {
+        const int live_tiles = __builtin_amdgcn_readfirstlane((M + 15) >> 4);  // row tiles that hold merged rows
         half8 bhi[JN], blo[JN];
         tile_to_lds(0, 0, 0);
 #pragma unroll
@@ -331,17 +343,38 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
                 tile_to_lds(kc + 1, nslot, buf ^ 1);
 #pragma unroll
                 for (int j = 0; j < JN; ++j) {
-                    half8 a[MT];
+                    if constexpr (MT == 16) {
+                        // sixteen row tiles are a capacity: groups of four tiles beyond the merged rows of
+                        // this tree are skipped (uniform over the workgroup)
+                        build_b(kc + 1, nslot, j, nhi[j], nlo[j]);
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt)
-                        a[mt] = *reinterpret_cast<const half8 *>(&a_lds[buf][mt * 16 + c][koff(j)]);
-                    build_b(kc + 1, nslot, j, nhi[j], nlo[j]);
+                        for (int gq = 0; gq < MT; gq += 4) {
+                            if (gq < live_tiles) {
+                                half8 a[4];
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt)
-                        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], bhi[j], acc[mt], 0, 0, 0);
+                                for (int mt = 0; mt < 4; ++mt)
+                                    a[mt] = *reinterpret_cast<const half8 *>(&a_lds[buf][(gq + mt) * 16 + c][koff(j)]);
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt)
-                        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], blo[j], acc[mt], 0, 0, 0);
+                                for (int mt = 0; mt < 4; ++mt)
+                                    acc[gq + mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], bhi[j], acc[gq + mt], 0, 0, 0);
+#pragma unroll
+                                for (int mt = 0; mt < 4; ++mt)
+                                    acc[gq + mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], blo[j], acc[gq + mt], 0, 0, 0);
+                            }
+                        }
+                    } else {
+                        half8 a[MT];
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt)
+                            a[mt] = *reinterpret_cast<const half8 *>(&a_lds[buf][mt * 16 + c][koff(j)]);
+                        build_b(kc + 1, nslot, j, nhi[j], nlo[j]);
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt)
+                            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], bhi[j], acc[mt], 0, 0, 0);
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt)
+                            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], blo[j], acc[mt], 0, 0, 0);
+                    }
                 }
                 issue_a(kc + 1 + PD, nslot);
                 issue_b(kc + 1 + PD, nslot);
@@ -377,10 +410,27 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     // ---- MODE 3: score the whole tree here
     __syncthreads();  // every wavefront is done with the row tiles: reuse them for the logits
     float *Zl = reinterpret_cast<float *>(smem);  // [64 nodes][ROWS]
-    if (KH == 2) {
+    if (KH == 2 && MT == 16) {
+        // the two wavefronts of a node tile hold complementary k-shares: add them in a fixed order, through
+        // the cells of the logit array that the sum goes to anyway (a separate staging area would not fit)
+        if (kh == 1) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                *reinterpret_cast<floatx4 *>(&Zl[(nt_w * 16 + c) * ROWS + mt * 16 + q * 4]) = acc[mt];
+            if (q == 0) ssq_lds[nt_w * 16 + c] = ssq;
+        }
+        __syncthreads();
+        if (kh == 0) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                acc[mt] += *reinterpret_cast<const floatx4 *>(&Zl[(nt_w * 16 + c) * ROWS + mt * 16 + q * 4]);
+            ssq += ssq_lds[nt_w * 16 + c];
+        }
+        __syncthreads();
+    } else if (KH == 2) {
         // the two wavefronts of a node tile hold complementary k-shares: add them in a fixed order
         float *tmp = Zl + 64 * ROWS;  // [4 tiles][64 lanes][MT quads]
-        static_assert(KH == 1 || sizeof(half_t) * kALdsHalves >= sizeof(float) * 2 * 64 * ROWS,
+        static_assert(KH == 1 || MT == 16 || sizeof(half_t) * kALdsHalves >= sizeof(float) * 2 * 64 * ROWS,
                       "room for the second wavefront's accumulators");
         if (kh == 1) {
 #pragma unroll
@@ -428,27 +478,36 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
             ssq = 0.f;
+            constexpr int MC = MT < 4 ? MT : 4;  // row tiles per batch of loads (bounds the registers held)
             for (int s0 = 0; s0 < p.S; s0 += 4) {
-                floatx4 v[4][MT];
                 float sq[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int ss = min(s0 + u, p.S - 1);  // clamped: always in bounds, masked below
+                for (int u = 0; u < 4; ++u)
+                    sq[u] = __hip_atomic_load(ssq_part + (size_t)min(s0 + u, p.S - 1) * 64, __ATOMIC_RELAXED,
+                                              __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt)
+                for (int m0c = 0; m0c < MT; m0c += MC) {
+                    floatx4 v[4][MC];
 #pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            v[u][mt][r] = __hip_atomic_load(part + ss * sstride + (mt * 4 + r) * 256, __ATOMIC_RELAXED,
-                                                            __HIP_MEMORY_SCOPE_AGENT);
-                    sq[u] = __hip_atomic_load(ssq_part + (size_t)ss * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    for (int u = 0; u < 4; ++u) {
+                        const int ss = min(s0 + u, p.S - 1);  // clamped: always in bounds, masked below
+#pragma unroll
+                        for (int mt = 0; mt < MC; ++mt)
+#pragma unroll
+                            for (int r = 0; r < 4; ++r)
+                                v[u][mt][r] = __hip_atomic_load(part + ss * sstride + ((m0c + mt) * 4 + r) * 256,
+                                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (s0 + u < p.S) {
+#pragma unroll
+                            for (int mt = 0; mt < MC; ++mt) acc[m0c + mt] += v[u][mt];
+                        }
                 }
 #pragma unroll
                 for (int u = 0; u < 4; ++u)
-                    if (s0 + u < p.S) {
-#pragma unroll
-                        for (int mt = 0; mt < MT; ++mt) acc[mt] += v[u][mt];
-                        ssq += sq[u];
-                    }
+                    if (s0 + u < p.S) ssq += sq[u];
             }
         }
     }
@@ -620,9 +679,14 @@ hipError_t launch_tree_gemm(const GemmParams &p, int G, hipStream_t st) {
     return hipGetLastError();
 }
 
+// Row tiles of 16 merged rows that a whole-tree workgroup holds: 4, 8 or 16.
+int tree_whole_row_tiles(int Mcap) {
+    return Mcap <= 64 ? 4 : (Mcap <= 128 ? 8 : 16);
+}
+
 // Whole tree per workgroup: one launch does merge, contraction, scoring and the path rule.
 bool tree_whole_supported(int N, int K, int Mcap) {
-    return N <= 64 && N * K <= kTcFusedMax && Mcap <= 128;
+    return N <= 64 && N * K <= kTcFusedMax && Mcap <= 256;
 }
 
 // Variants of the whole-tree kernel.  Up to 64 merged rows: 512 threads (two wavefronts share a
@@ -637,8 +701,22 @@ static void launch_whole(const GemmParams &p, const TreeFinishParams &f, int G, 
             hipLaunchKernelGGL((tree_contract_kernel<4, 3, true, 2, KC, 128, 512, GL>), grid, dim3(512), 0, st, p, f);
         else
             hipLaunchKernelGGL((tree_contract_kernel<4, 3, true, 4, KC, 64, 256, GL>), grid, dim3(256), 0, st, p, f);
-    } else {
+    } else if constexpr (MT == 8) {
         hipLaunchKernelGGL((tree_contract_kernel<8, 3, true, 4, KC, 64, 256, GL>), grid, dim3(256), 0, st, p, f);
+    } else {
+        // 129..256 merged rows: sixteen row tiles; the two tile buffers (72 KB) are dynamic LDS, one
+        // workgroup per CU
+        constexpr int kLds = 2 * 16 * MT * (64 + 8) * (int)sizeof(half_t);
+        auto kern = tree_contract_kernel<MT, 3, true, WHOLE16_PD, KC, 64, WHOLE16_T, GL>;
+        static bool raised[16] = {false};
+        int dev = 0;
+        if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 16 && !raised[dev]) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    kLds) != hipSuccess)
+                return;  // the launch below would fail the same way; the caller sees hipGetLastError()
+            raised[dev] = true;
+        }
+        hipLaunchKernelGGL(kern, grid, dim3(WHOLE16_T), kLds, st, p, f);
     }
 }
 
@@ -649,13 +727,19 @@ static void launch_whole_gl(const GemmParams &p, const TreeFinishParams &f, int 
 }
 
 hipError_t launch_tree_whole(const GemmParams &p, const TreeFinishParams &f, int G, hipStream_t st) {
-    const bool wide = p.Mcap > 64;
+    const int mt = tree_whole_row_tiles(p.Mcap);
     if (f.K <= 4) {
-        if (wide) launch_whole_gl<8, 4>(p, f, G, st); else launch_whole_gl<4, 4>(p, f, G, st);
+        if (mt == 16) launch_whole_gl<16, 4>(p, f, G, st);
+        else if (mt == 8) launch_whole_gl<8, 4>(p, f, G, st);
+        else launch_whole_gl<4, 4>(p, f, G, st);
     } else if (f.K <= 8) {
-        if (wide) launch_whole_gl<8, 8>(p, f, G, st); else launch_whole_gl<4, 8>(p, f, G, st);
+        if (mt == 16) launch_whole_gl<16, 8>(p, f, G, st);
+        else if (mt == 8) launch_whole_gl<8, 8>(p, f, G, st);
+        else launch_whole_gl<4, 8>(p, f, G, st);
     } else {
-        if (wide) launch_whole_gl<8, 16>(p, f, G, st); else launch_whole_gl<4, 16>(p, f, G, st);
+        if (mt == 16) launch_whole_gl<16, 16>(p, f, G, st);
+        else if (mt == 8) launch_whole_gl<8, 16>(p, f, G, st);
+        else launch_whole_gl<4, 16>(p, f, G, st);
     }
     return hipGetLastError();
 }

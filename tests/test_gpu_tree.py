@@ -224,6 +224,33 @@ def test_tree_many_trees_shapes(sp, oracle, d, V, K, H, N, Mcap, G):
     check_tree(got, ref, 0.5, f"{G} trees d={d} K={K} N={N}")
 
 
+@pytest.mark.parametrize("d,V,K,H,N,Mcap,G", [
+    (520, 777, 8, 512, 64, 256, 33),     # 129..256 merged rows: sixteen row tiles, seven d-slices per tree by ticket
+    (520, 777, 8, 512, 64, 256, 130),    # one d-slice
+    (520, 777, 8, 512, 61, 256, 260),    # more trees than CUs, ragged node count
+    (1032, 900, 4, 512, 60, 200, 40),    # K = 4, capacity not a multiple of 16
+    (8192, 700, 8, 512, 64, 256, 24),    # the large-vocabulary tree shape's d, eight d-slices of 1024
+    (256, 5000, 16, 1024, 16, 256, 21),  # K = KMAX: every node fills the capacity on its own
+])
+def test_tree_many_trees_wide_merged_sets(sp, oracle, d, V, K, H, N, Mcap, G):
+    ts = []
+    for gidx in range(G):
+        t = make_tree(77 * gidx + d, d, V, K, H, N, bias=True)
+        # between 129 and Mcap distinct ids in most trees, fewer in every fifth (its upper row tiles stay empty)
+        width = Mcap if gidx % 5 else 90
+        pool = np.random.default_rng(gidx).permutation(V)[:width]
+        t["ids"] = pool[np.random.default_rng(300 + gidx).integers(0, width, size=(N, K))].astype(np.int32)
+        ts.append(t)
+    for t in ts[1:]:
+        for k in ("gamma", "lm_head", "W1", "w2", "b1", "b2"):
+            t[k] = ts[0][k]
+    tb = stack_trees(ts)
+    ref = ref_tree(oracle, tb, Mcap)
+    assert ref["M"].max() > 128 or N * K <= 128
+    got = run_tree(sp, tb, dev(tb["lm_head"]), Mcap)
+    check_tree(got, ref, 0.5, f"{G} trees d={d} K={K} N={N} Mcap={Mcap}")
+
+
 @pytest.mark.parametrize("G", [16, 24])
 def test_tree_many_trees_overflow_invalid_ids_and_no_parent(sp, oracle, G):
     ts = [synth.make("T3", seed=s) for s in range(G)]
