@@ -29,16 +29,12 @@
 #include "tree_finish.h"
 
 namespace specee {
-#ifndef WHOLE16_PD
-#define WHOLE16_PD 4
-#endif
-#ifndef WHOLE16_T
-#define WHOLE16_T 512
-#endif
 
 constexpr int kTcFusedMax = kMergePerThread * 256;  // ids per tree when the merge is fused
 constexpr int kWholeWideMaxWgs = 256;               // one 512-thread workgroup per CU
 constexpr int kGammaLds = 4096;                     // elements of the RMSNorm weight a workgroup may stage in LDS
+// shape of the sixteen-row-tile whole-tree variant: stages in flight, threads, k elements per stage
+constexpr int kWide16Pd = 2, kWide16Threads = 512, kWide16Kch = 128;
 
 // KCH: k elements per stage (64 or 128).  A stage is one barrier and one LDS write -> read -> matrix
 // instruction dependency chain, so longer stages amortise that latency; 128 needs the row tile to
@@ -704,19 +700,19 @@ static void launch_whole(const GemmParams &p, const TreeFinishParams &f, int G, 
     } else if constexpr (MT == 8) {
         hipLaunchKernelGGL((tree_contract_kernel<8, 3, true, 4, KC, 64, 256, GL>), grid, dim3(256), 0, st, p, f);
     } else {
-        // 129..256 merged rows: sixteen row tiles; the two tile buffers (72 KB) are dynamic LDS, one
-        // workgroup per CU
-        constexpr int kLds = 2 * 16 * MT * (64 + 8) * (int)sizeof(half_t);
-        auto kern = tree_contract_kernel<MT, 3, true, WHOLE16_PD, KC, 64, WHOLE16_T, GL>;
+        // 129..256 merged rows: sixteen row tiles in stages of 128 elements.  The two tile buffers (136 KB)
+        // are dynamic LDS, so one workgroup per CU; the staged RMSNorm weight does not fit beside them.
+        constexpr int kLds = 2 * 16 * MT * (kWide16Kch + 8) * (int)sizeof(half_t);
+        auto kern = tree_contract_kernel<MT, 3, true, kWide16Pd, KC, kWide16Kch, kWide16Threads, GL && kWide16Kch == 64>;
         static bool raised[16] = {false};
         int dev = 0;
         if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 16 && !raised[dev]) {
+            // on failure the launch below fails too, and the caller sees that error
             if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    kLds) != hipSuccess)
-                return;  // the launch below would fail the same way; the caller sees hipGetLastError()
-            raised[dev] = true;
+                                    kLds) == hipSuccess)
+                raised[dev] = true;
         }
-        hipLaunchKernelGGL(kern, grid, dim3(WHOLE16_T), kLds, st, p, f);
+        hipLaunchKernelGGL(kern, grid, dim3(kWide16Threads), kLds, st, p, f);
     }
 }
 
