@@ -271,6 +271,57 @@ def test_sweep_c2_llama7b_32_layers(sp, oracle):
         prev = one["probs"]
 
 
+def test_c2_as_the_benchmark_launches_it_graph_of_32_dependent_calls(sp, oracle):
+    """The headline step: 32 dependent specee_predict launches, each reading the previous layer's probabilities
+    from device memory, captured once in a HIP graph and replayed.  Every replay must match the oracle's sweep."""
+    c = synth.CONFIGS["C2"]
+    lm_h, lm_d = lm_for(c)
+    gamma = None
+    sets = []
+    for r in range(2):  # two input sets, as the benchmark rotates over several
+        hid_h = synth.hidden_drift(c.L, 1, c.d, 50_000 + r)
+        ids_h = synth.ids_uniform_distinct(1, c.K, c.V, 60_000 + r)
+        base = synth.make("C2", lm=lm_h)
+        gamma = dev(base["gamma"])
+        W1, w2 = dev(base["W1"]), dev(base["w2"])
+        out = dict(logits=torch.empty((c.L, 1, c.K), device="cuda"), probs=torch.empty((c.L, 1, c.K), device="cuda"),
+                   scores=torch.empty((c.L, 1), device="cuda"),
+                   exit=torch.empty((c.L, 1), dtype=torch.int32, device="cuda"))
+        ref = oracle.predict_sweep(hid_h, base["gamma"], lm_h, ids_h, base["W1"], base["w2"])
+        sets.append((dev(hid_h), dev(ids_h), W1, w2, out, torch.zeros((1, c.K), device="cuda"), ref))
+
+    def calls(r):
+        hid, ids, W1, w2, out, zero, _ = sets[r]
+        for l in range(c.L):
+            o = dict(logits=out["logits"][l], probs=out["probs"][l], scores=out["scores"][l], exit=out["exit"][l])
+            sp.predict(hid[l], gamma, lm_d, ids, zero if l == 0 else out["probs"][l - 1], W1[l], w2[l], out=o)
+
+    graphs = []
+    stream = torch.cuda.Stream()
+    for r in range(2):
+        with torch.cuda.stream(stream):
+            calls(r)  # eager once: nothing lazy is left to happen under capture
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                calls(r)
+        graphs.append(g)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for r in range(2):
+            out, ref = sets[r][4], sets[r][6]
+            for v in out.values():
+                v.zero_()  # eager work between replays; the graph must rewrite every output
+            graphs[r].replay()
+            torch.cuda.synchronize()
+            got = {k: host(v) for k, v in out.items()}
+            close(got["logits"], ref["logits"], 1.0, f"graph replay {rep} set {r} logits")
+            close(got["probs"], ref["probs"], 1e-3, f"graph replay {rep} set {r} probs")
+            close(got["scores"], ref["scores"], 1e-3, f"graph replay {rep} set {r} scores")
+            near = np.abs(ref["scores"].astype(np.float64) - c.threshold) < 1e-4
+            assert np.array_equal(got["exit"][~near], ref["exit"][~near])
+
+
 def test_sweep_c4_llama13b_16_sequences_40_layers(sp, oracle):
     c = synth.CONFIGS["C4"]
     lm_h, lm_d = lm_for(c)
