@@ -457,3 +457,22 @@ def test_c5_large_vocab_tree_and_full_head(sp, oracle):
     idx = t["ids"]
     close(got["logits"], np.take_along_axis(full, idx, axis=1), 1.0, "tree logits vs full head")
     print("C5 lm_head worst", w)
+    # throughput mode at full size, as the benchmark launches it: 256 trees (one workgroup each) and 64 trees
+    # (d-slices by ticket) of this shape per launch; sampled trees against the oracle, integer outputs of all
+    oracle.set_threads(8)
+    for G in (256, 64):
+        ts = [synth.make("C5", seed=900 + i, lm=np.zeros((1, 1), np.float16)) for i in range(G)]
+        for x in ts:
+            for k in ("gamma", "W1", "w2", "b1", "b2"):
+                x[k] = t[k]
+        tb = stack_trees(ts)
+        gotb = run_tree(sp, tb, lm_d, c.Mcap)
+        assert np.all(np.isfinite(gotb["scores"]))
+        for gi in (0, G // 2 + 1, G - 1):
+            one = dict(ts[gi], lm_head=lm_h)
+            r1 = ref_tree(oracle, one, c.Mcap)
+            check_tree({k: v[gi] for k, v in gotb.items()}, r1, c.threshold, f"C5 batch of {G}, tree {gi}")
+        for gi in range(G):  # merged sets of every tree: integer work, exact
+            u = np.unique(ts[gi]["ids"])
+            assert gotb["M"][gi] == len(u) and np.array_equal(gotb["merged"][gi][:len(u)], u)
+    oracle.set_threads(1)
