@@ -23,6 +23,8 @@
 //         operand, the 16 nodes' hi/lo-split features the B operand) -- then applies the
 //         path rule.  Only inputs are read and only outputs written.
 // FUSED: the merge of the tree's ids runs in the prologue (N*K <= 1024).
+#include <type_traits>
+
 #include "device_utils.h"
 #include "kernels.h"
 #include "merge_block.h"
@@ -215,9 +217,14 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     }
     if (FUSED) __syncthreads();  // the merge scratch becomes the row tile buffers
     half8 a_buf[PD][APT];
-    auto issue_a = [&](int kc, int slot) {
+    // LA (a compile-time constant wrapped in a type): slices of the row tile -- kTcThreads / VPR rows each --
+    // that are loaded and written to LDS.  All of them, except in the sixteen-tile variant, whose stage loop
+    // exists in a few versions for trees that fill less of the capacity (see below); within a version every
+    // load is unconditional, so the compiler's count of outstanding loads stays exact.
+    typedef std::integral_constant<int, APT> all_slices;
+    auto issue_a = [&](int kc, int slot, auto la) {
 #pragma unroll
-        for (int i = 0; i < APT; ++i) {
+        for (int i = 0; i < decltype(la)::value; ++i) {
             const int ko = min(k_begin + kc * kTcKC + a_v[i] * 8, k_end - 8);
             a_buf[slot][i] = load_half8(arow[i] + ko);
         }
@@ -226,7 +233,7 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
         return arow_ok[i] && k_begin + kc * kTcKC + a_v[i] * 8 < k_end;
     };
 #pragma unroll
-    for (int u = 0; u < PD; ++u) issue_a(u, u);
+    for (int u = 0; u < PD; ++u) issue_a(u, u, all_slices{});
 
     // MODE 3: for the matrix-core MLP the predictor goes to LDS after the contraction, as a padded
     // image in the part of the row-tile buffers that the logits leave free (when it fits).  Up to
@@ -261,9 +268,9 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     // into the next B operand and the next row tile (a_lds[buf ^ 1]), and that slot's registers are
     // re-used for the loads of stage kc+1+PD.  One barrier per stage publishes the next tile and
     // retires the reads of the current one.
-    auto tile_to_lds = [&](int kc, int slot, int b) {
+    auto tile_to_lds = [&](int kc, int slot, int b, auto la) {
 #pragma unroll
-        for (int i = 0; i < APT; ++i)
+        for (int i = 0; i < decltype(la)::value; ++i)
             *reinterpret_cast<half8 *>(&a_lds[b][a_r[i]][a_v[i] * 8]) =
                 a_valid(kc, i) ? a_buf[slot][i] : zero_half8();
     };
@@ -298,11 +305,11 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
             for (int u = 0; u < PD; ++u) {
                 const int kc = kc0 + u;
                 half8 bhi[JN], blo[JN];
-                tile_to_lds(kc, u, buf);
+                tile_to_lds(kc, u, buf, all_slices{});
 #pragma unroll
                 for (int j = 0; j < JN; ++j) build_b(kc, u, j, bhi[j], blo[j]);
                 __syncthreads();
-                issue_a(kc + PD, u);
+                issue_a(kc + PD, u, all_slices{});
                 issue_b(kc + PD, u);
 #pragma unroll
                 for (int j = 0; j < JN; ++j) {
@@ -321,67 +328,86 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
             }
         }
     } else {
-        const int live_tiles = __builtin_amdgcn_readfirstlane((M + 15) >> 4);  // row tiles that hold merged rows
-        half8 bhi[JN], blo[JN];
-        tile_to_lds(0, 0, 0);
+        // The stage loop as a function of LA live slices of the row tile and LG live groups of four row
+        // tiles (compile-time constants).  Rows between the two granularities hold stale LDS contents and
+        // only feed logit columns that no node refers to.
+        auto stage_loop = [&](auto la, auto lg) {
+            half8 bhi[JN], blo[JN];
+            tile_to_lds(0, 0, 0, la);
 #pragma unroll
-        for (int j = 0; j < JN; ++j) build_b(0, 0, j, bhi[j], blo[j]);
-        issue_a(PD, 0);
-        issue_b(PD, 0);
-        __syncthreads();
-        int buf = 0;
-        for (int kc0 = 0; kc0 < nstages; kc0 += PD) {
+            for (int j = 0; j < JN; ++j) build_b(0, 0, j, bhi[j], blo[j]);
+            issue_a(PD, 0, la);
+            issue_b(PD, 0);
+            __syncthreads();
+            int buf = 0;
+            for (int kc0 = 0; kc0 < nstages; kc0 += PD) {
 #pragma unroll
-            for (int u = 0; u < PD; ++u) {
-                const int kc = kc0 + u;
-                const int nslot = (u + 1) % PD;  // folds: u is an unrolled constant
-                half8 nhi[JN], nlo[JN];
-                tile_to_lds(kc + 1, nslot, buf ^ 1);
+                for (int u = 0; u < PD; ++u) {
+                    const int kc = kc0 + u;
+                    const int nslot = (u + 1) % PD;  // folds: u is an unrolled constant
+                    half8 nhi[JN], nlo[JN];
+                    tile_to_lds(kc + 1, nslot, buf ^ 1, la);
 #pragma unroll
-                for (int j = 0; j < JN; ++j) {
-                    if constexpr (MT == 16) {
-                        // sixteen row tiles are a capacity: groups of four tiles beyond the merged rows of
-                        // this tree are skipped (uniform over the workgroup)
-                        build_b(kc + 1, nslot, j, nhi[j], nlo[j]);
+                    for (int j = 0; j < JN; ++j) {
+                        if constexpr (MT == 16) {
+                            // sixteen row tiles are a capacity: groups of four tiles beyond the merged rows of
+                            // this version of the loop are not multiplied
+                            build_b(kc + 1, nslot, j, nhi[j], nlo[j]);
 #pragma unroll
-                        for (int gq = 0; gq < MT; gq += 4) {
-                            if (gq < live_tiles) {
-                                half8 a[4];
+                            for (int gq = 0; gq < MT; gq += 4) {
+                                if (gq < 4 * decltype(lg)::value) {
+                                    half8 a[4];
 #pragma unroll
-                                for (int mt = 0; mt < 4; ++mt)
-                                    a[mt] = *reinterpret_cast<const half8 *>(&a_lds[buf][(gq + mt) * 16 + c][koff(j)]);
+                                    for (int mt = 0; mt < 4; ++mt)
+                                        a[mt] = *reinterpret_cast<const half8 *>(&a_lds[buf][(gq + mt) * 16 + c][koff(j)]);
 #pragma unroll
-                                for (int mt = 0; mt < 4; ++mt)
-                                    acc[gq + mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], bhi[j], acc[gq + mt], 0, 0, 0);
+                                    for (int mt = 0; mt < 4; ++mt)
+                                        acc[gq + mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], bhi[j], acc[gq + mt], 0, 0, 0);
 #pragma unroll
-                                for (int mt = 0; mt < 4; ++mt)
-                                    acc[gq + mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], blo[j], acc[gq + mt], 0, 0, 0);
+                                    for (int mt = 0; mt < 4; ++mt)
+                                        acc[gq + mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], blo[j], acc[gq + mt], 0, 0, 0);
+                                }
                             }
+                        } else {
+                            half8 a[MT];
+#pragma unroll
+                            for (int mt = 0; mt < MT; ++mt)
+                                a[mt] = *reinterpret_cast<const half8 *>(&a_lds[buf][mt * 16 + c][koff(j)]);
+                            build_b(kc + 1, nslot, j, nhi[j], nlo[j]);
+#pragma unroll
+                            for (int mt = 0; mt < MT; ++mt)
+                                acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], bhi[j], acc[mt], 0, 0, 0);
+#pragma unroll
+                            for (int mt = 0; mt < MT; ++mt)
+                                acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], blo[j], acc[mt], 0, 0, 0);
                         }
-                    } else {
-                        half8 a[MT];
-#pragma unroll
-                        for (int mt = 0; mt < MT; ++mt)
-                            a[mt] = *reinterpret_cast<const half8 *>(&a_lds[buf][mt * 16 + c][koff(j)]);
-                        build_b(kc + 1, nslot, j, nhi[j], nlo[j]);
-#pragma unroll
-                        for (int mt = 0; mt < MT; ++mt)
-                            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], bhi[j], acc[mt], 0, 0, 0);
-#pragma unroll
-                        for (int mt = 0; mt < MT; ++mt)
-                            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], blo[j], acc[mt], 0, 0, 0);
                     }
-                }
-                issue_a(kc + 1 + PD, nslot);
-                issue_b(kc + 1 + PD, nslot);
-                __syncthreads();
+                    issue_a(kc + 1 + PD, nslot, la);
+                    issue_b(kc + 1 + PD, nslot);
+                    __syncthreads();
 #pragma unroll
-                for (int j = 0; j < JN; ++j) {
-                    bhi[j] = nhi[j];
-                    blo[j] = nlo[j];
+                    for (int j = 0; j < JN; ++j) {
+                        bhi[j] = nhi[j];
+                        blo[j] = nlo[j];
+                    }
+                    buf ^= 1;
                 }
-                buf ^= 1;
             }
+        };
+        if constexpr (MT == 16) {
+            // sixteen row tiles are a capacity (129..256 merged rows): a tree that fills less of it takes a
+            // version of the loop that leaves the empty slices alone
+            constexpr int kSliceRows = kTcThreads / VPR;
+            const int slices = __builtin_amdgcn_readfirstlane((M + kSliceRows - 1) / kSliceRows);
+            static_assert(APT * kSliceRows == ROWS && ROWS == 256 && (APT == 8 || APT == 4), "slice arithmetic below");
+            if (APT == 8 && slices <= 5)
+                stage_loop(std::integral_constant<int, APT == 8 ? 5 : APT>{}, std::integral_constant<int, 3>{});
+            else if (slices * kSliceRows <= 192)
+                stage_loop(std::integral_constant<int, (3 * APT) / 4>{}, std::integral_constant<int, 3>{});
+            else
+                stage_loop(all_slices{}, std::integral_constant<int, 4>{});
+        } else {
+            stage_loop(all_slices{}, std::integral_constant<int, (MT + 3) / 4>{});
         }
     }
     // sum of squares of node c over this k-range: combine the four k-slot groups

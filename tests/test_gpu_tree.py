@@ -236,8 +236,9 @@ def test_tree_many_trees_wide_merged_sets(sp, oracle, d, V, K, H, N, Mcap, G):
     ts = []
     for gidx in range(G):
         t = make_tree(77 * gidx + d, d, V, K, H, N, bias=True)
-        # between 129 and Mcap distinct ids in most trees, fewer in every fifth (its upper row tiles stay empty)
-        width = Mcap if gidx % 5 else 90
+        # merged sets of different sizes within the capacity (each size class takes its own version of the
+        # kernel's stage loop; the smallest leaves the upper row tiles empty)
+        width = [Mcap, min(Mcap, 180), min(Mcap, 150), 90][gidx % 4]
         pool = np.random.default_rng(gidx).permutation(V)[:width]
         t["ids"] = pool[np.random.default_rng(300 + gidx).integers(0, width, size=(N, K))].astype(np.int32)
         ts.append(t)
@@ -247,6 +248,9 @@ def test_tree_many_trees_wide_merged_sets(sp, oracle, d, V, K, H, N, Mcap, G):
     tb = stack_trees(ts)
     ref = ref_tree(oracle, tb, Mcap)
     assert ref["M"].max() > 128 or N * K <= 128
+    if N * K >= 512 and Mcap == 256:
+        ms = ref["M"]
+        assert (ms > 192).any() and ((ms > 160) & (ms <= 192)).any() and ((ms > 128) & (ms <= 160)).any() and (ms <= 128).any()
     got = run_tree(sp, tb, dev(tb["lm_head"]), Mcap)
     check_tree(got, ref, 0.5, f"{G} trees d={d} K={K} N={N} Mcap={Mcap}")
 
