@@ -105,6 +105,10 @@ __device__ __forceinline__ half8 zero_half8() {
     return z;
 }
 
+// s_waitcnt operand (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8) that waits
+// for every outstanding vector-memory operation of the wavefront, stores included, and for nothing else.
+constexpr int kWaitVmcnt0 = 0x0F70;
+
 __device__ __forceinline__ float quiet_nan() {
     return __builtin_bit_cast(float, 0x7fc00000);
 }

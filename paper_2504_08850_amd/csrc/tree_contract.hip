@@ -476,7 +476,12 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
         // The accumulators travel as relaxed device-scope atomics: such stores are written through to
         // the level all XCDs share and such loads are served from there, so no cache has to be flushed
         // or invalidated around the ticket (a device-scope fence would walk this XCD's whole L2).
-        // __syncthreads() waits for every outstanding store of the workgroup before the ticket is drawn.
+        // What orders them before the ticket: every storing thread waits until its own stores have
+        // been acknowledged (the vector-memory counter reaches zero only when written-through stores
+        // have arrived at that shared level), then the barrier, then thread 0 draws the ticket.  The
+        // barrier alone would not do: its fences are workgroup scope and wait for no global store.
+        // On the other side the winner's loads are issued after the ticket's value has come back
+        // (it travels through LDS and a barrier), and they bypass the caches that are not coherent.
         const int t256 = tid & 255;  // kh == 0 wavefronts are threads 0..255
         // [G][S][row-tile quad element][256 threads]: a wavefront's accesses are contiguous
         float *part = p.out + (size_t)g * p.S * (256 * MT * 4) + t256;
@@ -491,9 +496,11 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
                                        __HIP_MEMORY_SCOPE_AGENT);
             if (q == 0)
                 __hip_atomic_store(ssq_part + (size_t)s * 64, ssq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);  // this thread's stores have landed
         }
         __syncthreads();
-        if (tid == 0) last_lds = atomicAdd(&p.tickets[g], 1) == p.S - 1;
+        if (tid == 0)
+            last_lds = __hip_atomic_fetch_add(&p.tickets[g], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == p.S - 1;
         __syncthreads();
         if (!last_lds) return;  // uniform over the workgroup
         if (kh == 0) {
@@ -730,14 +737,9 @@ static void launch_whole(const GemmParams &p, const TreeFinishParams &f, int G, 
         // are dynamic LDS, so one workgroup per CU; the staged RMSNorm weight does not fit beside them.
         constexpr int kLds = 2 * 16 * MT * (kWide16Kch + 8) * (int)sizeof(half_t);
         auto kern = tree_contract_kernel<MT, 3, true, kWide16Pd, KC, kWide16Kch, kWide16Threads, GL && kWide16Kch == 64>;
-        static bool raised[16] = {false};
-        int dev = 0;
-        if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 16 && !raised[dev]) {
-            // on failure the launch below fails too, and the caller sees that error
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    kLds) == hipSuccess)
-                raised[dev] = true;
-        }
+        // the limit is a property of the loaded kernel, set again at every launch: the library keeps no state
+        // (on failure the launch below fails too, and the caller sees that error)
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
         hipLaunchKernelGGL(kern, grid, dim3(kWide16Threads), kLds, st, p, f);
     }
 }

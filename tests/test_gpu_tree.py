@@ -36,19 +36,39 @@ def run_tree(sp, t, lm_d, Mcap, parent="auto", **kw):
     out = sp.predict_tree(dev(t["hidden"]), dev(t["gamma"]), lm_d, dev(t["ids"]), dev(t["prev_probs"]),
                           dev(t["W1"]), dev(t["w2"]), dev(t["b1"]), dev(t["b2"]), parent=dev(par), Mcap=Mcap, **kw)
     torch.cuda.synchronize()
-    return {k: host(v) for k, v in out.items() if k != "_workspace"}
+    res = {k: host(v) for k, v in out.items() if k != "_workspace"}
+    res["parent"] = None if par is None else np.asarray(par)
+    return res
 
 
-def check_tree(got, ref, thr, what):
+def path_and(flags, parent):
+    """AND of per-node flags from every node up to its root (parents precede children); [N] or [G][N]."""
+    ex = np.asarray(flags).astype(bool)
+    ex2, par2 = np.atleast_2d(ex), np.atleast_2d(np.asarray(parent))
+    out = np.zeros_like(ex2)
+    rows = np.arange(ex2.shape[0])
+    for n in range(ex2.shape[1]):
+        p = par2[:, n]
+        assert np.all(p < n)
+        out[:, n] = ex2[:, n] & np.where(p >= 0, out[rows, np.maximum(p, 0)], True)
+    return out.reshape(ex.shape)
+
+
+def check_tree(got, ref, thr, what, min_compared=0.5):
     # integer outputs: bit-exact
     assert np.array_equal(got["M"], ref["M"]), what + " M"
     assert np.array_equal(got["merged"], ref["merged"]), what + " merged ids"
     assert np.array_equal(got["cols"], ref["cols"]), what + " cols"
     e = check_scored(got, ref, thr, what)
     if ref.get("path_exit") is not None:
-        decided = np.abs(ref["scores"] - thr) > 1e-4
-        if decided.all():
-            assert np.array_equal(got["path_exit"], ref["path_exit"]), what + " path_exit"
+        parent = got["parent"]          # what run_tree passed to the library
+        # the path rule applied to the GPU's own exit flags: every node, no exemption
+        assert np.array_equal(got["path_exit"], path_and(got["exit"], parent).astype(np.int32)), \
+            what + " path_exit is not the AND of the exit flags up to the root"
+        # against the oracle: every node whose whole root path lies outside the band around the threshold
+        decided = path_and(np.abs(ref["scores"] - thr) > 1e-4, parent)
+        assert decided.mean() >= min_compared, (what, "too few nodes have a decided root path", decided.mean())
+        assert np.array_equal(got["path_exit"][decided], ref["path_exit"][decided]), what + " path_exit"
     return e
 
 
@@ -253,6 +273,34 @@ def test_tree_many_trees_wide_merged_sets(sp, oracle, d, V, K, H, N, Mcap, G):
         assert (ms > 192).any() and ((ms > 160) & (ms <= 192)).any() and ((ms > 128) & (ms <= 160)).any() and (ms <= 128).any()
     got = run_tree(sp, tb, dev(tb["lm_head"]), Mcap)
     check_tree(got, ref, 0.5, f"{G} trees d={d} K={K} N={N} Mcap={Mcap}")
+
+
+@pytest.mark.parametrize("d,V,K,H,N,Mcap,G", [
+    (1032, 900, 4, 512, 60, 64, 300),    # the 60-node, 64-row shape: matrix-core MLP from the padded predictor image
+    (2048, 900, 8, 512, 30, 64, 300),    # K = 8
+    (520, 777, 3, 100, 64, 48, 270),     # K odd: vector-unit MLP; ragged d
+    (4096, 600, 4, 512, 60, 64, 520),    # full hidden size, two workgroups per CU and more than one round
+])
+def test_tree_more_trees_than_cus_narrow_merged_sets(sp, oracle, d, V, K, H, N, Mcap, G):
+    """More than 256 trees with at most 64 merged rows each: one 256-thread workgroup per tree with four
+    row tiles (below 257 trees the same shape takes 512 threads per tree)."""
+    ts = []
+    for gidx in range(G):
+        t = make_tree(31 * gidx + d, d, V, K, H, N, bias=(gidx == 0 and K == 8))
+        width = [Mcap, Mcap - 7, 33, 16][gidx % 4]
+        pool = np.random.default_rng(gidx).permutation(V)[:width]
+        t["ids"] = pool[np.random.default_rng(700 + gidx).integers(0, width, size=(N, K))].astype(np.int32)
+        ts.append(t)
+    for t in ts[1:]:
+        for k in ("gamma", "lm_head", "W1", "w2", "b1", "b2"):
+            t[k] = ts[0][k]
+    tb = stack_trees(ts)
+    oracle.set_threads(8)
+    ref = ref_tree(oracle, tb, Mcap)
+    oracle.set_threads(1)
+    got = run_tree(sp, tb, dev(tb["lm_head"]), Mcap)
+    check_tree(got, ref, 0.5, f"{G} trees d={d} K={K} N={N} Mcap={Mcap}")
+    assert 0 < ref["path_exit"].sum() < ref["exit"].sum()
 
 
 @pytest.mark.parametrize("G", [16, 24])
