@@ -435,6 +435,75 @@ int specee_verify_ref(int d, int V, int K, double eps, int N, const uint16_t *hi
 }
 
 /*
+ * The early-exit decode loop of one token down the layer stack (dataflow of
+ * Sec. 4.3.3 with the active-predictor set of Sec. 5.3): at every layer whose
+ * predictor is active the features are computed and scored; a positive
+ * prediction is followed by verification on the full vocabulary; the token
+ * leaves the model at the first layer where the verification accepts one of
+ * the speculative tokens, and nothing is evaluated after that layer.
+ *   hidden [L][B][d], ids [B][K] (fixed per token), prev0 [B][K] or NULL (= 0),
+ *   W1 [L][H][3K], b1 [L][H] or NULL, w2 [L][H], b2 [L] or NULL,
+ *   active [L] or NULL (= every layer).
+ * Outputs per layer and token ([L][B]...; zero for layers that were not
+ * evaluated -- inactive, or after the token's exit; ver_token is -1 where no
+ * verification ran): logits, probs [L][B][K], scores, exit_flags, ver_token,
+ * hit [L][B]; per token: exit_layer [B] (-1: the token ran the whole stack),
+ * token [B] (the accepted token, or -1).
+ * The probabilities carried to the next active layer are rounded to float, as
+ * in the layer-by-layer sweep above.
+ */
+int specee_layer_loop_ref(int d, int V, int K, int H, double eps, float threshold, int L, int B,
+                          const uint16_t *hidden, const uint16_t *gamma, const uint16_t *lm_head, const int32_t *ids,
+                          const float *prev0, const uint16_t *W1, const uint16_t *b1, const uint16_t *w2,
+                          const uint16_t *b2, const int32_t *active, double *logits, double *probs, double *scores,
+                          int32_t *exit_flags, int32_t *ver_token, int32_t *hit, int32_t *exit_layer,
+                          int32_t *token) {
+    if (check_dims(d, V, K, H, B) || L < 0) return REF_EINVAL;
+    for (size_t i = 0; i < (size_t)L * B * K; ++i) logits[i] = probs[i] = 0.0;
+    for (size_t i = 0; i < (size_t)L * B; ++i) {
+        scores[i] = 0.0;
+        exit_flags[i] = 0;
+        ver_token[i] = -1;
+        hit[i] = 0;
+    }
+    int rc_all = REF_OK;
+#pragma omp parallel for num_threads(g_threads) schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        float carry[64];
+        for (int k = 0; k < K; ++k) carry[k] = prev0 ? prev0[b * K + k] : 0.0f;
+        exit_layer[b] = -1;
+        token[b] = -1;
+        for (int l = 0; l < L; ++l) {
+            if (active && !active[l]) continue;
+            const size_t o = (size_t)l * B + b;
+            int rc = specee_predict_ref(d, V, K, H, eps, threshold, 1, hidden + o * d, gamma, lm_head, ids + b * K,
+                                        carry, W1 + (size_t)l * H * 3 * K, b1 ? b1 + (size_t)l * H : NULL,
+                                        w2 + (size_t)l * H, b2 ? b2 + l : NULL, logits + o * K, probs + o * K, NULL,
+                                        scores + o, exit_flags + o);
+            if (rc != REF_OK) {
+                rc_all = rc;
+                break;
+            }
+            for (int k = 0; k < K; ++k) carry[k] = (float)probs[o * K + k];
+            if (!exit_flags[o]) continue;
+            double mx;
+            rc = specee_verify_ref(d, V, K, eps, 1, hidden + o * d, gamma, lm_head, ids + b * K, ver_token + o, &mx,
+                                   hit + o);
+            if (rc != REF_OK) {
+                rc_all = rc;
+                break;
+            }
+            if (hit[o]) {
+                exit_layer[b] = l;
+                token[b] = ver_token[o];
+                break;
+            }
+        }
+    }
+    return rc_all;
+}
+
+/*
  * Online scheduling (Sec. 5.3): a circular queue holds the exit layers of the
  * last Q tokens; counter[i] is the number of queued exit layers within
  * `radius` of layer i (itself included).  A layer's predictor is active when

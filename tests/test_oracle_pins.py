@@ -424,6 +424,116 @@ def test_verification_tie_goes_to_lowest_id(oracle):
     assert v["token"][0] == 2 and v["hit"][0] == 0
 
 
+# ---------------------------------------------------------------- early-exit loop down the layer stack
+def loop_case(seed, L=6, B=5, d=24, V=23, K=3, H=16):
+    rng = np.random.default_rng(seed)
+    return dict(
+        hidden=rng.standard_normal((L, B, d)).astype(np.float16),
+        gamma=(1 + 0.1 * rng.standard_normal(d)).astype(np.float16),
+        lm_head=(0.3 * rng.standard_normal((V, d))).astype(np.float16),
+        ids=np.stack([rng.choice(V, K, replace=False) for _ in range(B)]).astype(np.int32),
+        W1=(0.5 * rng.standard_normal((L, H, 3 * K))).astype(np.float16),
+        w2=(0.5 * rng.standard_normal((L, H))).astype(np.float16),
+        b1=(0.5 * rng.standard_normal((L, H))).astype(np.float16),
+        b2=(0.5 * rng.standard_normal(L)).astype(np.float16))
+
+
+def numpy_loop(t, threshold, active=None, eps=1e-5):
+    """The decode loop written with numpy / scipy library routines only (float64)."""
+    L, B, _ = t["hidden"].shape
+    K = t["ids"].shape[1]
+    W = f64(t["lm_head"])
+    out = dict(scores=np.zeros((L, B)), exit=np.zeros((L, B), np.int32), ver_token=np.full((L, B), -1, np.int32),
+               hit=np.zeros((L, B), np.int32), exit_layer=np.full(B, -1, np.int32), token=np.full(B, -1, np.int32),
+               probs=np.zeros((L, B, K)))
+    for b in range(B):
+        prev = np.zeros(K, np.float32)
+        for l in range(L):
+            if active is not None and not active[l]:
+                continue
+            y = W @ np_normed(t["hidden"][l, b], t["gamma"], eps)        # every vocabulary logit
+            z = y[t["ids"][b]]
+            p = softmax(z)
+            feat = np.concatenate([z, p, p - f64(prev)])
+            a = np.maximum(f64(t["W1"][l]) @ feat + f64(t["b1"][l]), 0.0)
+            s = expit(f64(t["w2"][l]) @ a + float(t["b2"][l]))
+            out["scores"][l, b], out["probs"][l, b] = s, p
+            prev = p.astype(np.float32)
+            if np.float32(s) > np.float32(threshold):
+                out["exit"][l, b] = 1
+                tok = int(np.argmax(y))
+                out["ver_token"][l, b] = tok
+                if tok in t["ids"][b]:
+                    out["hit"][l, b] = 1
+                    out["exit_layer"][b], out["token"][b] = l, tok
+                    break
+    return out
+
+
+def plant_hits(t, layers):
+    """Token b's first id becomes the arg-max token of layer layers[b] (None: left alone)."""
+    W = f64(t["lm_head"])
+    for b, l in enumerate(layers):
+        if l is None:
+            continue
+        tok = int(np.argmax(W @ np_normed(t["hidden"][l, b], t["gamma"], 1e-5)))
+        others = [i for i in t["ids"][b] if i != tok][: t["ids"].shape[1] - 1]
+        t["ids"][b] = [tok] + others
+    return t
+
+
+@pytest.mark.parametrize("threshold", [0.3, 0.5, -1.0])
+def test_layer_loop_matches_numpy_decode_loop(oracle, threshold):
+    t = plant_hits(loop_case(41), [4, 0, None, 2, 5])
+    ref = numpy_loop(t, threshold)
+    got = oracle.layer_loop(t["hidden"], t["gamma"], t["lm_head"], t["ids"], t["W1"], t["w2"], t["b1"], t["b2"],
+                            threshold=threshold)
+    assert np.all(np.abs(ref["scores"][ref["scores"] != 0] - threshold) > 1e-6)
+    for k in ("exit", "ver_token", "hit", "exit_layer", "token"):
+        assert np.array_equal(got[k], ref[k]), k
+    np.testing.assert_allclose(got["scores"], ref["scores"], rtol=1e-9, atol=1e-12)
+    np.testing.assert_allclose(got["probs"], ref["probs"], rtol=1e-9, atol=1e-12)
+    if threshold < 0:       # every predictor fires: the exit layer is the first layer whose arg-max is speculative
+        assert got["exit_layer"][1] == 0 and got["exit_layer"][3] <= 2 and got["exit_layer"][0] <= 4
+        assert got["hit"].sum() == (got["exit_layer"] >= 0).sum() and (got["exit_layer"] >= 0).sum() >= 4
+
+
+def test_layer_loop_that_never_fires_is_the_layer_sweep(oracle):
+    t = plant_hits(loop_case(42), [1, 2, 3, 4, 5])
+    got = oracle.layer_loop(t["hidden"], t["gamma"], t["lm_head"], t["ids"], t["W1"], t["w2"], t["b1"], t["b2"],
+                            threshold=2.0)
+    sw = oracle.predict_sweep(t["hidden"], t["gamma"], t["lm_head"], t["ids"], t["W1"], t["w2"], t["b1"], t["b2"],
+                              threshold=2.0)
+    for k in ("logits", "probs", "scores", "exit"):
+        assert np.array_equal(got[k], sw[k]), k
+    assert np.all(got["exit_layer"] == -1) and np.all(got["token"] == -1) and np.all(got["ver_token"] == -1)
+    assert not got["hit"].any()
+
+
+def test_layer_loop_nothing_is_evaluated_after_the_exit_or_on_inactive_layers(oracle):
+    t = plant_hits(loop_case(43), [2, 2, 2, 2, 2])
+    kw = dict(threshold=-1.0)
+    a = (t["hidden"], t["gamma"], t["lm_head"], t["ids"], t["W1"], t["w2"], t["b1"], t["b2"])
+    got = oracle.layer_loop(*a, **kw)
+    assert np.all(got["exit_layer"] <= 2) and np.all(got["exit_layer"] >= 0)
+    for b in range(5):
+        e = got["exit_layer"][b]
+        assert not got["scores"][e + 1:, b].any() and not got["probs"][e + 1:, b].any()
+        assert np.all(got["ver_token"][e + 1:, b] == -1) and got["token"][b] == got["ver_token"][e, b]
+    # with layers 0..2 inactive the planted layer cannot be used: same as the loop on the remaining layers
+    active = np.array([0, 0, 0, 1, 1, 1], np.int32)
+    got = oracle.layer_loop(*a, active=active, **kw)
+    ref = numpy_loop(t, -1.0, active=active)
+    assert not got["scores"][:3].any() and np.all(got["ver_token"][:3] == -1)
+    for k in ("exit", "ver_token", "hit", "exit_layer", "token"):
+        assert np.array_equal(got[k], ref[k]), k
+    np.testing.assert_allclose(got["scores"], ref["scores"], rtol=1e-9, atol=1e-12)
+    # the carried probabilities of a token come from its own previous *active* layer: zero before layer 3
+    first = oracle.predict(t["hidden"][3], t["gamma"], t["lm_head"], t["ids"], np.zeros((5, 3), np.float32),
+                           t["W1"][3], t["w2"][3], t["b1"][3], t["b2"][3:4], threshold=-1.0)
+    assert np.array_equal(first["scores"], got["scores"][3])
+
+
 # ---------------------------------------------------------------- online scheduling
 def test_schedule_constant_exit_layer_closed_form(oracle):
     L, Q, e = 12, 5, 7
