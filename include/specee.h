@@ -15,7 +15,8 @@
  *    (a 16-bit pattern); all are row-major and must be 16-byte aligned.
  *  - Unless a parameter says HOST, pointers are DEVICE pointers owned by the
  *    caller.  Inputs are only read, outputs only written; the library never
- *    allocates or frees device memory and keeps no state between calls.
+ *    allocates or frees device memory and keeps no state between calls
+ *    (one documented exception: specee_predict_tree_static).
  *  - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
  *    default stream) and the call returns without synchronising.  Outputs are
  *    valid once the stream has reached the end of the enqueued work.
@@ -51,7 +52,8 @@ typedef enum specee_status {
     SPECEE_EINVAL = -1,     /* bad size, NULL required pointer, aliasing outputs */
     SPECEE_EALIGN = -2,     /* a tensor pointer is not 16-byte aligned */
     SPECEE_EWORKSPACE = -3, /* workspace missing or smaller than specee_workspace_bytes() */
-    SPECEE_EHIP = -4        /* the HIP runtime refused a launch */
+    SPECEE_EHIP = -4,       /* the HIP runtime refused a launch */
+    SPECEE_ESCRATCH = -5    /* the call needs more scratch than specee_predict_tree_static owns */
 } specee_status;
 
 /* Model and predictor shape.  d: hidden size (multiple of 8), V: vocabulary,
@@ -164,6 +166,35 @@ int specee_predict_tree(const specee_dims *dims, int G, int N, int Mcap, const s
                         int32_t *merged_ids, int32_t *M_out, int32_t *cols, float *logits, float *probs,
                         float *scores, int32_t *exit_flags, int32_t *path_exit, void *workspace,
                         size_t workspace_bytes, void *stream);
+
+/*
+ * specee_predict_tree for callers that cannot allocate device memory or hand in a
+ * workspace -- code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, outputs and results as specee_predict_tree,
+ * without `workspace`: partial sums, tickets and the like live in an array of
+ * SPECEE_STATIC_SCRATCH_BYTES that is part of the library's device code (every GPU
+ * the library runs on holds its own copy until the process ends).  The call
+ * allocates and frees nothing, on the host or on the device, and enqueues kernels
+ * only (what must start at zero is cleared by a kernel).
+ * A call whose launch shape needs more scratch than that returns SPECEE_ESCRATCH
+ * and enqueues nothing.  What a call needs: nothing with 20 or more trees of at
+ * most 64 nodes, N*K <= 1024 and Mcap <= 256 when there is no room for d-slices;
+ * otherwise about 4 * ceil(d/256) * G*N * (Mcap rounded up to 16) bytes or less
+ * (one 60-node tree at d = 4096, Mcap = 64: 0.25 MB; one 64-node tree at
+ * d = 8192, Mcap = 256: 2.1 MB).
+ * This is the one entry point with state: the per-device address of that array
+ * is looked up on the first call on a device (that device must be current, as
+ * for any call) and kept.  All calls on one GPU share the array, which keeps the
+ * previous call's contents: calls on the same GPU must not overlap in time (two
+ * streams, two threads), or they race on it.
+ */
+#define SPECEE_STATIC_SCRATCH_BYTES (18u << 20)
+int specee_predict_tree_static(const specee_dims *dims, int G, int N, int Mcap, const specee_half *hidden,
+                               const specee_half *gamma, const specee_half *lm_head, const int32_t *ids,
+                               const int32_t *parent, const float *prev_probs,
+                               const specee_mlp *mlp /* HOST */, int32_t *merged_ids, int32_t *M_out,
+                               int32_t *cols, float *logits, float *probs, float *scores, int32_t *exit_flags,
+                               int32_t *path_exit, void *stream);
 
 /*
  * Full-vocabulary LM head with the final RMSNorm: the search space of earlier

@@ -2,6 +2,8 @@
 // kernel launches.  See include/specee.h for the contract of every entry point.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "../../include/specee.h"
 #include "kernels.h"
 
@@ -72,13 +74,52 @@ struct TreeLayout {
     size_t partial_off, ssq_off, total;
 };
 TreeLayout tree_layout(int S, int n_total, int Mcap) {
-    struct { int S; } ts = {S};
     TreeLayout L;
     L.Mpad = ((Mcap + 15) / 16) * 16;
     L.partial_off = 0;
-    L.ssq_off = align256((size_t)ts.S * n_total * L.Mpad * sizeof(float));
-    L.total = L.ssq_off + align256((size_t)ts.S * n_total * sizeof(float));
+    L.ssq_off = align256((size_t)S * n_total * L.Mpad * sizeof(float));
+    L.total = L.ssq_off + align256((size_t)S * n_total * sizeof(float));
     return L;
+}
+
+// Workspace of the whole-tree kernel when S > 1 workgroups share a tree: accumulators
+// [G][S][256 threads x row tiles] quads, sums of squares [G][S][64], tickets [G].
+size_t whole_tree_part_bytes(int G, int S, int Mcap) {
+    return align256((size_t)G * S * 256 * tree_whole_row_tiles(Mcap) * 16);
+}
+size_t whole_tree_ssq_bytes(int G, int S) {
+    return align256((size_t)G * S * 64 * sizeof(float));
+}
+size_t whole_tree_bytes(int G, int S, int Mcap) {
+    return whole_tree_part_bytes(G, S, Mcap) + whole_tree_ssq_bytes(G, S) + align256((size_t)G * sizeof(int32_t));
+}
+
+}  // namespace
+
+// Scratch memory of specee_predict_tree_static, the entry point for callers that cannot allocate.
+// Every GPU that the library runs on holds its own copy of this array, at its own address, until the
+// process ends.  In host code the array's name is only a handle for hipGetSymbolAddress: the address
+// that kernels may use is looked up once per device, with that device current, and kept below.
+static __device__ __align__(256) unsigned char scratch[SPECEE_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void *scratch_ptr[kMaxDevices] = {nullptr};
+
+// Device address of the current device's scratch array (looked up on the first call per device).
+int static_scratch(void **base) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SPECEE_EHIP;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return SPECEE_EHIP;
+        scratch_ptr[dev] = ptr;
+    }
+    *base = scratch_ptr[dev];
+    return SPECEE_OK;
 }
 
 }  // namespace
@@ -96,6 +137,7 @@ const char *specee_strerror(int status) {
         case SPECEE_EALIGN: return "tensor pointer is not 16-byte aligned";
         case SPECEE_EWORKSPACE: return "workspace missing or too small";
         case SPECEE_EHIP: return "HIP runtime refused the launch";
+        case SPECEE_ESCRATCH: return "the call needs more scratch than the static buffer holds";
         default: return "unknown status";
     }
 }
@@ -115,8 +157,17 @@ size_t specee_workspace_bytes(int op, const specee_dims *dm, int n, int Mcap) {
         }
         case SPECEE_OP_PREDICT_TREE:
             if (check_dims(dm, true) || Mcap < 1 || Mcap > 4096) return (size_t)-1;
+        {
             // the split depends on how n divides into trees: size for the finest one
-            return tree_layout(tree_max_slices(dm->d), n, Mcap).total;
+            size_t need = tree_layout(tree_max_slices(dm->d), n, Mcap).total;
+            // batches of small trees may run as a few d-slice workgroups per tree, at most
+            // kWholeTargetWgs in all, each leaving its accumulators behind, plus one ticket per tree
+            if (n >= kWholeTreeMinTrees && Mcap <= 256) {
+                const size_t whole = whole_tree_bytes(kWholeTargetWgs, 1, Mcap) + align256((size_t)n * sizeof(int32_t));
+                if (whole > need) need = whole;
+            }
+            return need;
+        }
         default:
             return (size_t)-1;
     }
@@ -216,12 +267,13 @@ int lm_head_gemv(const specee_dims *dm, int N, const specee_half *hidden, const 
     return e == hipSuccess ? SPECEE_OK : SPECEE_EHIP;
 }
 
-int specee_predict_tree(const specee_dims *dm, int G, int N, int Mcap, const specee_half *hidden,
-                        const specee_half *gamma, const specee_half *lm_head, const int32_t *ids,
-                        const int32_t *parent, const float *prev_probs, const specee_mlp *mlp, int32_t *merged_ids,
-                        int32_t *M_out, int32_t *cols, float *logits, float *probs, float *scores,
-                        int32_t *exit_flags, int32_t *path_exit, void *workspace, size_t workspace_bytes,
-                        void *stream) {
+// Host-side checks shared by the tree entry points; nothing is dereferenced.
+static int check_tree_args(const specee_dims *dm, int G, int N, int Mcap, const specee_half *hidden,
+                           const specee_half *gamma, const specee_half *lm_head, const int32_t *ids,
+                           const int32_t *parent, const float *prev_probs, const specee_mlp *mlp,
+                           const int32_t *merged_ids, const int32_t *M_out, const int32_t *cols, const float *logits,
+                           const float *probs, const float *scores, const int32_t *exit_flags,
+                           const int32_t *path_exit) {
     int rc = check_dims(dm, true);
     if (rc) return rc;
     if (G < 0 || N < 1 || Mcap < 1 || Mcap > 4096 || (long long)N * dm->K > 4096) return SPECEE_EINVAL;
@@ -233,11 +285,30 @@ int specee_predict_tree(const specee_dims *dm, int G, int N, int Mcap, const spe
         return SPECEE_EINVAL;
     if (path_exit && !parent) return SPECEE_EINVAL;
     if (probs == prev_probs) return SPECEE_EINVAL;
-    if (misaligned(hidden) || misaligned(gamma) || misaligned(lm_head) || misaligned(workspace)) return SPECEE_EALIGN;
+    if (misaligned(hidden) || misaligned(gamma) || misaligned(lm_head)) return SPECEE_EALIGN;
+    return SPECEE_OK;
+}
+
+// Shared body of the two tree entry points.  exact_fit: the workspace only has to hold what the
+// launch shape chosen for this call needs (the static-scratch entry point); otherwise it has to be as
+// large as specee_workspace_bytes() says, which covers every shape.
+static int predict_tree_common(const specee_dims *dm, int G, int N, int Mcap, const specee_half *hidden,
+                               const specee_half *gamma, const specee_half *lm_head, const int32_t *ids,
+                               const int32_t *parent, const float *prev_probs, const specee_mlp *mlp,
+                               int32_t *merged_ids, int32_t *M_out, int32_t *cols, float *logits, float *probs,
+                               float *scores, int32_t *exit_flags, int32_t *path_exit, void *workspace,
+                               size_t workspace_bytes, bool exact_fit, void *stream) {
+    const int rc = check_tree_args(dm, G, N, Mcap, hidden, gamma, lm_head, ids, parent, prev_probs, mlp, merged_ids,
+                                   M_out, cols, logits, probs, scores, exit_flags, path_exit);
+    if (rc) return rc;
+    if (G == 0) return SPECEE_OK;
+    if (misaligned(workspace)) return SPECEE_EALIGN;
     const TreeSplit ts = tree_split(dm->d, G * N, N, Mcap);
     const TreeLayout lay = tree_layout(ts.S, G * N, Mcap);
-    const size_t need = tree_layout(tree_max_slices(dm->d), G * N, Mcap).total;
-    if (!workspace || workspace_bytes < need) return SPECEE_EWORKSPACE;
+    if (!exact_fit) {
+        const size_t need = tree_layout(tree_max_slices(dm->d), G * N, Mcap).total;
+        if (!workspace || workspace_bytes < need) return SPECEE_EWORKSPACE;
+    }
     hipStream_t st = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace);
     float *partial = reinterpret_cast<float *>(ws + lay.partial_off);
@@ -271,22 +342,20 @@ int specee_predict_tree(const specee_dims *dm, int G, int N, int Mcap, const spe
         if (S < 1) S = 1;
         int dslice = (((dm->d + S - 1) / S + 127) / 128) * 128;
         S = (dm->d + dslice - 1) / dslice;
-        const size_t quads = (size_t)256 * tree_whole_row_tiles(Mcap);
-        const size_t part_bytes = align256((size_t)G * S * quads * 16);
-        const size_t ssq_bytes = align256((size_t)G * S * 64 * sizeof(float));
-        const size_t tick_bytes = align256((size_t)G * sizeof(int32_t));
-        if (S > 1 && part_bytes + ssq_bytes + tick_bytes > workspace_bytes) {
-            S = 1;
+        const size_t part_bytes = whole_tree_part_bytes(G, S, Mcap), ssq_bytes = whole_tree_ssq_bytes(G, S);
+        if (S > 1 && (!workspace || whole_tree_bytes(G, S, Mcap) > workspace_bytes)) {
+            S = 1;  // one workgroup per tree over all of d needs no workspace at all
             dslice = ((dm->d + 127) / 128) * 128;
         }
         gp.dslice = dslice; gp.S = S;
         gp.out = reinterpret_cast<float *>(ws);
-        gp.ssq_part = reinterpret_cast<float *>(ws + part_bytes);
-        gp.tickets = reinterpret_cast<int32_t *>(ws + part_bytes + ssq_bytes);
+        gp.ssq_part = S > 1 ? reinterpret_cast<float *>(ws + part_bytes) : nullptr;
+        gp.tickets = S > 1 ? reinterpret_cast<int32_t *>(ws + part_bytes + ssq_bytes) : nullptr;
         if (S > 1 && launch_zero_i32(gp.tickets, G, st) != hipSuccess) return SPECEE_EHIP;
         return launch_tree_whole(gp, fp, G, st) == hipSuccess ? SPECEE_OK : SPECEE_EHIP;
     }
 
+    if (exact_fit && (!workspace || workspace_bytes < lay.total)) return SPECEE_EWORKSPACE;
     // few trees: split d over many workgroups; merge inside the contraction kernel (one launch less on the
     // latency path) unless that would repeat it too often
     const bool fuse = tree_gemm_can_fuse_merge(N * dm->K) && (long long)G * ts.S <= 64;
@@ -297,6 +366,35 @@ int specee_predict_tree(const specee_dims *dm, int G, int N, int Mcap, const spe
     fp.S = ts.S;
     if (launch_tree_finish(fp, G, st) != hipSuccess) return SPECEE_EHIP;
     return SPECEE_OK;
+}
+
+int specee_predict_tree(const specee_dims *dm, int G, int N, int Mcap, const specee_half *hidden,
+                        const specee_half *gamma, const specee_half *lm_head, const int32_t *ids,
+                        const int32_t *parent, const float *prev_probs, const specee_mlp *mlp, int32_t *merged_ids,
+                        int32_t *M_out, int32_t *cols, float *logits, float *probs, float *scores,
+                        int32_t *exit_flags, int32_t *path_exit, void *workspace, size_t workspace_bytes,
+                        void *stream) {
+    return predict_tree_common(dm, G, N, Mcap, hidden, gamma, lm_head, ids, parent, prev_probs, mlp, merged_ids, M_out,
+                               cols, logits, probs, scores, exit_flags, path_exit, workspace, workspace_bytes, false,
+                               stream);
+}
+
+int specee_predict_tree_static(const specee_dims *dm, int G, int N, int Mcap, const specee_half *hidden,
+                               const specee_half *gamma, const specee_half *lm_head, const int32_t *ids,
+                               const int32_t *parent, const float *prev_probs, const specee_mlp *mlp,
+                               int32_t *merged_ids, int32_t *M_out, int32_t *cols, float *logits, float *probs,
+                               float *scores, int32_t *exit_flags, int32_t *path_exit, void *stream) {
+    // argument errors first (they need no GPU), then the address of this device's scratch array
+    int rc = check_tree_args(dm, G, N, Mcap, hidden, gamma, lm_head, ids, parent, prev_probs, mlp, merged_ids, M_out,
+                             cols, logits, probs, scores, exit_flags, path_exit);
+    if (rc) return rc;
+    if (G == 0) return SPECEE_OK;
+    void *base = nullptr;
+    if ((rc = static_scratch(&base))) return rc;
+    const int r = predict_tree_common(dm, G, N, Mcap, hidden, gamma, lm_head, ids, parent, prev_probs, mlp, merged_ids,
+                                      M_out, cols, logits, probs, scores, exit_flags, path_exit, base,
+                                      SPECEE_STATIC_SCRATCH_BYTES, true, stream);
+    return r == SPECEE_EWORKSPACE ? SPECEE_ESCRATCH : r;
 }
 
 int specee_verify(const specee_dims *dm, int N, const specee_half *hidden, const specee_half *gamma,

@@ -215,6 +215,29 @@ def predict_tree(hidden, gamma, lm_head, ids, prev_probs, W1, w2, b1=None, b2=No
     return out
 
 
+def predict_tree_static(hidden, gamma, lm_head, ids, prev_probs, W1, w2, b1=None, b2=None, parent=None, Mcap=64,
+                        eps=1e-5, threshold=0.5, out=None, stream=None):
+    """specee_predict_tree_static: specee_predict_tree on the library's own static scratch array.  `out` must
+    be given (dict with merged, M, cols, logits, probs, scores, exit and, with parent, path_exit): this binding
+    allocates nothing either.  hidden [G][N][d]."""
+    G, N, d = hidden.shape
+    V = lm_head.shape[0]
+    K = ids.shape[2]
+    H = w2.shape[0]
+    dims = _dims(d, V, K, H, eps, threshold)
+    mlp = _mlp(W1, w2, b1, b2)
+    f16 = torch.float16
+    rc = lib().specee_predict_tree_static(C.byref(dims), C.c_int(G), C.c_int(N), C.c_int(Mcap), _ptr(hidden, f16),
+                                          _ptr(gamma, f16), _ptr(lm_head, f16), _ptr(ids, torch.int32),
+                                          _ptr(parent, torch.int32), _ptr(prev_probs, torch.float32), C.byref(mlp),
+                                          _ptr(out["merged"]), _ptr(out["M"]), _ptr(out["cols"]),
+                                          _ptr(out["logits"]), _ptr(out["probs"]), _ptr(out["scores"]),
+                                          _ptr(out["exit"]), _ptr(out.get("path_exit")), _stream(stream))
+    if rc:
+        raise SpeceeError("specee_predict_tree_static", rc)
+    return out
+
+
 def lm_head_gemv(hidden, gamma, lm_head, eps=1e-5, out=None, workspace=None, stream=None):
     """lm_head_gemv: out [N][V] = RMSNorm(hidden) @ lm_head^T."""
     N, d = hidden.shape

@@ -53,7 +53,7 @@ def test_version_and_strerror(sp):
     lib = sp.lib()
     assert lib.specee_version() >= 100
     assert lib.specee_strerror(0) == b"success"
-    for code in (-1, -2, -3, -4):
+    for code in (-1, -2, -3, -4, -5):
         assert lib.specee_strerror(code) not in (b"success", b"unknown status")
     assert lib.specee_strerror(-99) == b"unknown status"
 
@@ -100,6 +100,11 @@ def test_host_side_validation_without_a_gpu(sp):
     assert lib.specee_predict_tree(C.byref(ok), 1, 60, 64, *args, None, C.c_size_t(0), None) == -3
     args_path = (fake,) * 3 + (fake, None, fake, C.byref(mlp)) + (fake,) * 4 + (other,) + (fake,) * 2 + (fake,)
     assert lib.specee_predict_tree(C.byref(ok), 1, 60, 64, *args_path, fake, C.c_size_t(1 << 30), None) == -1
+    # the entry point on static scratch: the same argument checks, made before anything touches a GPU
+    assert lib.specee_predict_tree_static(C.byref(ok), 1, 2000, 64, *args, None) == -1
+    assert lib.specee_predict_tree_static(C.byref(ok), 1, 60, 5000, *args, None) == -1
+    assert lib.specee_predict_tree_static(C.byref(ok), 1, 60, 64, *args_path, None) == -1
+    assert lib.specee_predict_tree_static(C.byref(ok), 0, 60, 64, *args, None) == 0
     assert lib.lm_head_gemv(C.byref(ok), 1, fake, fake, odd, fake, None, C.c_size_t(0), None) == -2
     assert lib.specee_verify(C.byref(ok), 1, fake, fake, fake, fake, None, None, fake, fake, fake, None,
                              C.c_size_t(0), None) == -3
@@ -110,9 +115,11 @@ def test_workspace_sizes(sp):
     assert sp.workspace_bytes(sp.OP_PREDICT, dm, 16) == 0
     assert sp.workspace_bytes(sp.OP_LM_HEAD, dm, 64) == 0
     one = sp.workspace_bytes(sp.OP_PREDICT_TREE, dm, 60, 64)
-    # 16 d-slices of partial sums [60][64] fp32 plus the partial sums of squares
-    assert one >= 16 * 60 * 64 * 4 + 16 * 60 * 4 and one < 2 * 16 * 60 * 64 * 4
-    assert sp.workspace_bytes(sp.OP_PREDICT_TREE, dm, 120, 64) > one
+    # 16 d-slices of partial sums [60][64] fp32 plus the partial sums of squares, or (n could be 60 trees of
+    # one node) 256 d-slice workgroups' accumulators of four row tiles, whichever is larger
+    assert one >= 16 * 60 * 64 * 4 + 16 * 60 * 4 and one >= 256 * 256 * 4 * 16 and one < 5 << 20
+    assert sp.workspace_bytes(sp.OP_PREDICT_TREE, dm, 16, 64) < 2 * 16 * 16 * 64 * 4     # too few nodes for that
+    assert sp.workspace_bytes(sp.OP_PREDICT_TREE, dm, 6000, 64) > 4 * one
     assert sp.workspace_bytes(sp.OP_VERIFY, dm, 1) > 0
     with pytest.raises(sp.SpeceeError):
         sp.workspace_bytes(sp.OP_PREDICT_TREE, dm, 60, 0)
