@@ -82,7 +82,8 @@ typedef enum specee_op {
     SPECEE_OP_PREDICT_SWEEP = 1,
     SPECEE_OP_PREDICT_TREE = 2,
     SPECEE_OP_LM_HEAD = 3,
-    SPECEE_OP_VERIFY = 4
+    SPECEE_OP_VERIFY = 4,
+    SPECEE_OP_LAYER_LOOP = 5
 } specee_op;
 
 /*
@@ -224,6 +225,41 @@ int specee_verify(const specee_dims *dims, int N, const specee_half *hidden, con
                   const specee_half *lm_head, const int32_t *ids, const int32_t *gate /* [N] or NULL */,
                   int32_t *done /* [N] or NULL */, int32_t *token, float *max_logit, int32_t *hit, void *workspace,
                   size_t workspace_bytes, void *stream);
+
+/*
+ * The early-exit decode loop of B tokens down L layers in one launch (Sec. 4.3.3:
+ * a positive prediction is followed by verification, and the token leaves the
+ * model at the first layer whose verification accepts a speculative token;
+ * Sec. 5.3: only the layers of the active set run their predictor).  For each
+ * token, layer by layer: specee_predict with the local probabilities of the
+ * token's previous active layer; if the exit flag is set, specee_verify on the
+ * same hidden state; on a hit the loop ends for that token.  Nothing is
+ * evaluated after a token's exit, and the host takes no part in any decision.
+ *   hidden [L][B][d] (every layer's hidden state exists before the call),
+ *   ids [B][K], prev0 [B][K] or NULL (zeros), mlp with leading L (as for
+ *   specee_predict_sweep), active [L] int32 or NULL (all layers active).
+ *   logits/probs [L][B][K], scores/exit_flags [L][B]: as specee_predict wrote
+ *   them; ver_token/hit [L][B]: arg-max token and hit flag where a verification
+ *   ran, -1 / 0 elsewhere.  Layers that were not evaluated for a token
+ *   (inactive, or after its exit) hold zeros (ver_token -1).
+ *   exit_layer [B]: layer at which the token left the model, -1 if it ran the
+ *   whole stack; token [B]: the accepted token or -1.
+ *   status [B]: 0, or 1 if the token's workgroups could not meet (see below);
+ *   its outputs from the failing layer on are then the not-evaluated values.
+ * One group of workgroups per token stays on the GPU for the whole call and meets
+ * once per verification, so the call needs every one of its workgroups resident
+ * at once: the grid is sized to what the device holds, B must not exceed 64, and
+ * the GPU should not be shared with other kernels while it runs.  Every wait in
+ * the kernel is bounded: spin_limit polls (0: a default worth a few seconds), after
+ * which the token is given up with status 1 -- the call never hangs.
+ * Limits: d <= 8192, B <= 64.  Workspace: SPECEE_OP_LAYER_LOOP with n = B.
+ */
+int specee_layer_loop(const specee_dims *dims, int L, int B, const specee_half *hidden, const specee_half *gamma,
+                      const specee_half *lm_head, const int32_t *ids, const float *prev0,
+                      const specee_mlp *mlp /* HOST */, const int32_t *active, float *logits, float *probs,
+                      float *scores, int32_t *exit_flags, int32_t *ver_token, int32_t *hit, int32_t *exit_layer,
+                      int32_t *token, int32_t *status, long long spin_limit, void *workspace,
+                      size_t workspace_bytes, void *stream);
 
 /* Bytes of device workspace `op` needs for n tokens / nodes (Mcap: tree only).
  * Pure host function; 0 means none; (size_t)-1 means invalid arguments. */

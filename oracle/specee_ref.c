@@ -467,7 +467,8 @@ int specee_layer_loop_ref(int d, int V, int K, int H, double eps, float threshol
         hit[i] = 0;
     }
     int rc_all = REF_OK;
-#pragma omp parallel for num_threads(g_threads) schedule(dynamic, 1)
+    /* threads split the tokens; a single token leaves them to the vocabulary loop of its verifications */
+#pragma omp parallel for num_threads(g_threads) schedule(dynamic, 1) if (B > 1)
     for (int b = 0; b < B; ++b) {
         float carry[64];
         for (int k = 0; k < K; ++k) carry[k] = prev0 ? prev0[b * K + k] : 0.0f;

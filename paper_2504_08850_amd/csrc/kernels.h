@@ -35,6 +35,29 @@ hipError_t launch_predict(const PredictParams &p, hipStream_t s);
 hipError_t launch_predict_q4(const PredictParams &p, hipStream_t s);
 hipError_t launch_predict_sweep(const PredictParams &p, int32_t *first_exit, hipStream_t s);
 
+// Persistent early-exit loop over the layers of B tokens (layer_loop.hip)
+struct LoopParams {
+    int d, V, K, H, L, B;
+    float eps, threshold;
+    const half_t *hidden;   // [L][B][d]
+    const half_t *gamma;    // [d]
+    const half_t *lm_head;  // [V][d]
+    const int32_t *ids;     // [B][K]
+    const float *prev0;     // [B][K] or null
+    const half_t *W1, *b1, *w2, *b2;  // leading layer dimension L
+    const int32_t *active;  // [L] or null
+    float *logits, *probs, *scores;            // [L][B][K], [L][B][K], [L][B]
+    int32_t *exit_flags, *ver_token, *hit;     // [L][B]
+    int32_t *exit_layer, *token, *status;      // [B]
+    int rows_per_wg;        // LM-head rows per workgroup in a verification pass (set by the launcher)
+    int32_t *arrive;        // [B] arrival counters of the groups, zero at launch
+    int32_t *abort;         // [1] zero at launch; set by a group that could not meet
+    float *cand_val;        // [2][B][workgroups per token] arg-max candidates
+    int32_t *cand_idx;
+    long long spin_limit;   // polls of the arrival counter before a meeting is given up
+};
+hipError_t launch_layer_loop(const LoopParams &p, int max_wgs, hipStream_t s);
+
 #define SPECEE_KMAX_INTERNAL 16
 
 // MFMA gather-contraction (gemm_kernels.hip)

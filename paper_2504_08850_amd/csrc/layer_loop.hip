@@ -1,0 +1,361 @@
+// The early-exit decode loop of a token down the layer stack in ONE launch (paper Sec. 4.3.3 dataflow
+// -- predict, verify after a positive prediction, leave the model at the first accepted verification --
+// with the active-predictor set of the scheduler, Sec. 5.3).
+//
+// A launch of one kernel per step costs about two microseconds on this system even when the kernel is
+// empty, which is as much as the predictor itself; and a static sequence of launches cannot stop at the
+// exit.  Here a group of Pg workgroups stays resident for a token and walks the layers:
+//   * the predictor of a layer is evaluated redundantly by every workgroup of the group (62 KB of
+//     reads that hit in L2 after the first workgroup, about a microsecond): all of them reach the same
+//     exit decision with no communication, so a layer that does not fire costs no synchronisation;
+//   * the K speculative LM-head rows and the RMSNorm weight do not change from layer to layer: they are
+//     loaded once and stay in registers, so a layer reads only its hidden state and its predictor;
+//   * when the predictor fires, the group streams the whole LM head once (workgroup w takes a block
+//     of rows), every workgroup leaves its arg-max candidate in the workspace, the group meets at an
+//     arrival counter, and every workgroup combines all candidates itself -- again the same decision
+//     everywhere.  One group-wide meeting per verification, none otherwise;
+//   * after the exit the loop ends: the remaining layers cost nothing.
+// The meeting needs every workgroup of a group to be resident: the host sizes the grid from the
+// occupancy the runtime reports, and every wait is bounded (spin limit), so a group that cannot meet
+// (another kernel holds the CUs) ends with status 1 instead of hanging.
+#include "device_utils.h"
+#include "head_stream.h"
+#include "kernels.h"
+#include "predictor_tail.h"
+
+namespace specee {
+
+constexpr int kLoopThreads = 512;
+constexpr int kLoopWaves = kLoopThreads / kWave;
+
+// KC / EXACT / VPT as in predict_kernel.  KEEP: the K rows stay in registers across layers (up to 64
+// registers of them; wider shapes read their rows again at every layer, from L2).
+template <int KC, int VPT, bool EXACT, bool STREAM>
+__global__ __launch_bounds__(kLoopThreads) void layer_loop_kernel(LoopParams p) {
+    constexpr bool KEEP = KC * VPT <= 16 && KC <= 8;
+    extern __shared__ float4 loop_lds_x[];  // verification: x = h * gamma as two float4 planes, [2][d/8]
+    __shared__ float red[kLoopWaves][KC + 1];
+    __shared__ float red_u[kLoopWaves];
+    __shared__ float cv[kLoopWaves];
+    __shared__ int ci[kLoopWaves];
+    __shared__ int met_lds;
+
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    const int w = blockIdx.x, b = blockIdx.y, Pg = gridDim.x, B = p.B;
+    const int K = EXACT ? KC : p.K, H = p.H, d = p.d, L = p.L;
+    const int nv = d >> 3;
+    const bool writer = w == 0;  // the workgroup of the group that writes the token's outputs
+    floatx4 *xa = reinterpret_cast<floatx4 *>(loop_lds_x);
+    floatx4 *xb = xa + nv;
+
+    // ---- once per token: ids, rows, RMSNorm weight, carried probabilities
+    int idv[KC];
+#pragma unroll
+    for (int k = 0; k < KC; ++k) idv[k] = p.ids[(size_t)b * K + min(k, K - 1)];
+    half8 gv[VPT];
+#pragma unroll
+    for (int u = 0; u < VPT; ++u) gv[u] = load_half8(p.gamma + min(tid + u * kLoopThreads, nv - 1) * 8);
+    float prev[KC];
+#pragma unroll
+    for (int k = 0; k < KC; ++k) prev[k] = 0.f;
+    if (p.prev0) {
+#pragma unroll
+        for (int k = 0; k < KC; ++k)
+            if (k < K) prev[k] = p.prev0[(size_t)b * K + k];
+    }
+    const half_t *rows[KC];
+    bool bad_id = false;
+#pragma unroll
+    for (int k = 0; k < KC; ++k) {
+        const bool ok = idv[k] >= 0 && idv[k] < p.V;
+        if (k < K && !ok) bad_id = true;
+        rows[k] = p.lm_head + (size_t)(ok ? idv[k] : 0) * d;
+    }
+    half8 wv[KC][VPT];
+    auto load_rows = [&]() {
+#pragma unroll
+        for (int k = 0; k < KC; ++k)
+#pragma unroll
+            for (int u = 0; u < VPT; ++u) {
+                const int v = tid + u * kLoopThreads;
+                const half8 x = load_half8(rows[k] + min(v, nv - 1) * 8);
+                wv[k][u] = (k < K && v < nv) ? x : zero_half8();
+            }
+    };
+    if (KEEP) load_rows();
+
+    const int row_begin = min(p.V, w * p.rows_per_wg);
+    const int row_end = min(p.V, row_begin + p.rows_per_wg);
+    int meetings = 0;       // verifications so far: the arrival counter stands at meetings * Pg afterwards
+    int exit_layer = -1, exit_token = -1;
+    int status = 0;
+    // first layer from l0 on whose predictor is active (L if none); uniform over the grid
+    auto next_active = [&](int l0) {
+        int q = l0;
+        while (q < L && p.active && p.active[q] == 0) ++q;
+        return q;
+    };
+    // A layer's inputs -- its hidden state, this thread's predictor row and the output bias -- are requested
+    // one active layer ahead (every layer's hidden state exists before the call), so that a layer that does
+    // not fire costs arithmetic and two barriers, not a trip to memory.
+    half8 hv_pf[VPT];
+    MlpRow<KC> row_pf;
+    half_t b2_pf;
+    auto prefetch = [&](int q) {
+        const half_t *hrow = p.hidden + ((size_t)q * B + b) * d;
+#pragma unroll
+        for (int u = 0; u < VPT; ++u) hv_pf[u] = load_half8(hrow + min(tid + u * kLoopThreads, nv - 1) * 8);
+        mlp_row_load<KC>(row_pf, p.W1 + (size_t)q * H * 3 * K, p.b1 ? p.b1 + (size_t)q * H : nullptr,
+                         p.w2 + (size_t)q * H, K, H, tid);
+        b2_pf = (p.b2 ? p.b2 : p.gamma)[p.b2 ? q : 0];  // always a valid address; masked at use
+    };
+    int l = next_active(0);
+    int evaluated_upto = -1;  // last layer whose outputs below are final
+    if (l < L) prefetch(l);
+    while (l < L) {
+        const size_t tok = (size_t)l * B + b;
+        const int lnext = next_active(l + 1);
+        const half_t *W1 = p.W1 + (size_t)l * H * 3 * K;
+        const half_t *w2 = p.w2 + (size_t)l * H;
+        const half_t *b1 = p.b1 ? p.b1 + (size_t)l * H : nullptr;
+        MlpRow<KC> rowm[1];
+        rowm[0] = row_pf;
+        const half_t b2raw = b2_pf;
+        half8 hv[VPT];
+#pragma unroll
+        for (int u = 0; u < VPT; ++u) hv[u] = tid + u * kLoopThreads < nv ? hv_pf[u] : zero_half8();
+        prefetch(min(lnext, L - 1));  // unconditional (a load under a branch would make the compiler drain the others)
+        if (!KEEP) load_rows();
+
+        float ssq = 0.f, acc[KC];
+#pragma unroll
+        for (int k = 0; k < KC; ++k) acc[k] = 0.f;
+#pragma unroll
+        for (int u = 0; u < VPT; ++u)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float hf = (float)hv[u][e];
+                const float x = hf * (float)gv[u][e];
+                ssq += hf * hf;
+#pragma unroll
+                for (int k = 0; k < KC; ++k) acc[k] += x * (float)wv[k][u][e];
+            }
+        ssq = wave_sum_to_last_row(ssq);
+#pragma unroll
+        for (int k = 0; k < KC; ++k) acc[k] = wave_sum_to_last_row(acc[k]);
+        if (lane == kWave - 1) {
+            red[wave][0] = ssq;
+#pragma unroll
+            for (int k = 0; k < KC; ++k) red[wave][1 + k] = acc[k];
+        }
+        __syncthreads();
+        ssq = 0.f;
+#pragma unroll
+        for (int k = 0; k < KC; ++k) acc[k] = 0.f;
+#pragma unroll
+        for (int q = 0; q < kLoopWaves; ++q) {
+            ssq += red[q][0];
+#pragma unroll
+            for (int k = 0; k < KC; ++k) acc[k] += red[q][1 + k];
+        }
+        const float r = 1.0f / sqrtf(ssq * (1.0f / (float)d) + p.eps);
+        float z[KC], pr[KC];
+#pragma unroll
+        for (int k = 0; k < KC; ++k) z[k] = bad_id ? quiet_nan() : acc[k] * r;
+        local_softmax<KC>(z, K, pr);
+        float part = mlp_partial<KC, kLoopThreads, 1>(rowm, W1, b1, w2, K, H, tid, z, pr, prev);
+        part = wave_sum_to_last_row(part);
+        if (lane == kWave - 1) red_u[wave] = part;
+        __syncthreads();
+        float uo = p.b2 ? (float)b2raw : 0.f;
+#pragma unroll
+        for (int q = 0; q < kLoopWaves; ++q) uo += red_u[q];
+        const float sc = sigmoidf(uo);
+        const bool fire = sc > p.threshold;  // the same bits in every thread of every workgroup of the group
+        if (writer && tid == 0) {
+            p.scores[tok] = sc;
+            p.exit_flags[tok] = fire ? 1 : 0;
+#pragma unroll
+            for (int k = 0; k < KC; ++k)
+                if (k < K) {
+                    p.logits[tok * K + k] = z[k];
+                    p.probs[tok * K + k] = pr[k];
+                }
+            if (!fire) {
+                p.ver_token[tok] = -1;
+                p.hit[tok] = 0;
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < KC; ++k) prev[k] = pr[k];
+        if (!fire) {
+            evaluated_upto = l;
+            l = lnext;
+            continue;
+        }
+
+        // ---- verification: this workgroup's block of LM-head rows against x = h * gamma
+#pragma unroll
+        for (int u = 0; u < VPT; ++u) {
+            const int v = tid + u * kLoopThreads;
+            if (v < nv) {
+                floatx4 a4, b4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    a4[e] = (float)hv[u][e] * (float)gv[u][e];
+                    b4[e] = (float)hv[u][4 + e] * (float)gv[u][4 + e];
+                }
+                xa[v] = a4;
+                xb[v] = b4;
+            }
+        }
+        __syncthreads();
+        float bv = -INFINITY;
+        int bi = 0x7fffffff;
+        head_argmax_rows<STREAM>(p.lm_head, d, row_begin, row_end, wave, kLoopWaves, lane, xa, xb, r, bv, bi);
+        if (lane == 0) {
+            cv[wave] = bv;
+            ci[wave] = bi;
+        }
+        __syncthreads();
+        // candidates of successive verifications alternate between two buffers: a workgroup that runs ahead
+        // into the next verification writes the other buffer while a slower one still reads this one, and
+        // it cannot get two verifications ahead, because the next meeting needs everybody
+        const size_t cbase = ((size_t)(meetings & 1) * B + b) * Pg;
+        if (tid == 0) {
+            for (int q = 1; q < kLoopWaves; ++q)
+                if (cv[q] > bv || (cv[q] == bv && ci[q] < bi)) {
+                    bv = cv[q];
+                    bi = ci[q];
+                }
+            __hip_atomic_store(p.cand_val + cbase + w, bv, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(p.cand_idx + cbase + w, bi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);  // the candidate has landed where every XCD reads it
+            __hip_atomic_fetch_add(p.arrive + b, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int target = (meetings + 1) * Pg;
+            int met = 0;
+            for (long long it = 0; it < p.spin_limit; ++it) {
+                if (__hip_atomic_load(p.arrive + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) {
+                    met = 1;
+                    break;
+                }
+                if (__hip_atomic_load(p.abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) break;
+                __builtin_amdgcn_s_sleep(8);
+            }
+            if (!met) __hip_atomic_store(p.abort, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            met_lds = met;
+        }
+        __syncthreads();
+        if (!met_lds) {  // uniform: the group could not meet within the spin limit
+            status = 1;
+            break;
+        }
+        ++meetings;
+        // every workgroup combines the group's candidates itself (lowest row on ties)
+        bv = -INFINITY;
+        bi = 0x7fffffff;
+        for (int i = tid; i < Pg; i += kLoopThreads) {
+            const float v = __hip_atomic_load(p.cand_val + cbase + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int ix = __hip_atomic_load(p.cand_idx + cbase + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (v > bv || (v == bv && ix < bi)) {
+                bv = v;
+                bi = ix;
+            }
+        }
+        wave_argmax(bv, bi);
+        __syncthreads();  // cv / ci were read by thread 0 before the meeting; met_lds by everybody
+        if (lane == 0) {
+            cv[wave] = bv;
+            ci[wave] = bi;
+        }
+        __syncthreads();
+        bv = cv[0];
+        bi = ci[0];
+#pragma unroll
+        for (int q = 1; q < kLoopWaves; ++q)
+            if (cv[q] > bv || (cv[q] == bv && ci[q] < bi)) {
+                bv = cv[q];
+                bi = ci[q];
+            }
+        bool hit = false;
+#pragma unroll
+        for (int k = 0; k < KC; ++k)
+            if (k < K && idv[k] == bi) hit = true;
+        if (writer && tid == 0) {
+            p.ver_token[tok] = bi;
+            p.hit[tok] = hit ? 1 : 0;
+        }
+        evaluated_upto = l;
+        if (hit) {  // the token leaves the model at this layer
+            exit_layer = l;
+            exit_token = bi;
+            break;
+        }
+        __syncthreads();  // cv / ci are rewritten by the next verification
+        l = lnext;
+    }
+
+    // ---- layers that were not evaluated (inactive, after the exit, or from a failed meeting on): defined outputs
+    if (writer) {
+        for (int ll = 0; ll < L; ++ll) {
+            if (ll <= evaluated_upto && !(p.active && p.active[ll] == 0)) continue;
+            const size_t tok = (size_t)ll * B + b;
+            if (tid < K) {
+                p.logits[tok * K + tid] = 0.f;
+                p.probs[tok * K + tid] = 0.f;
+            }
+            if (tid == 0) {
+                p.scores[tok] = 0.f;
+                p.exit_flags[tok] = 0;
+                p.ver_token[tok] = -1;
+                p.hit[tok] = 0;
+            }
+        }
+        if (tid == 0) {
+            p.exit_layer[b] = exit_layer;
+            p.token[b] = exit_token;
+            p.status[b] = status;
+        }
+    }
+}
+
+template <int KC, int VPT, bool EXACT>
+static hipError_t launch_loop_one(LoopParams p, int max_wgs, hipStream_t s) {
+    const bool stream = head_streams(p.d, p.V);
+    auto kern = stream ? layer_loop_kernel<KC, VPT, EXACT, true> : layer_loop_kernel<KC, VPT, EXACT, false>;
+    const size_t lds = (size_t)p.d * sizeof(float);
+    // every workgroup of a group must be resident while the group meets: size the grid from what the
+    // runtime says fits on the device
+    int dev = 0, cus = 0, per_cu = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e == hipSuccess)
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(kern), kLoopThreads, lds);
+    if (e != hipSuccess) return e;
+    long long fit = (long long)cus * (per_cu > 2 ? 2 : per_cu);
+    if (fit > max_wgs) fit = max_wgs;
+    const int Pg = (int)(fit / p.B);
+    if (Pg < 1) return hipErrorInvalidConfiguration;
+    const int quantum = kLoopWaves * kHeadRows;
+    p.rows_per_wg = (((p.V + Pg - 1) / Pg + quantum - 1) / quantum) * quantum;
+    hipLaunchKernelGGL(kern, dim3(Pg, p.B), dim3(kLoopThreads), lds, s, p);
+    return hipGetLastError();
+}
+
+template <int KC, bool EXACT>
+static hipError_t launch_loop_vpt(const LoopParams &p, int max_wgs, hipStream_t s) {
+    if ((p.d >> 3) <= kLoopThreads) return launch_loop_one<KC, 1, EXACT>(p, max_wgs, s);
+    return launch_loop_one<KC, 2, EXACT>(p, max_wgs, s);
+}
+
+// d <= 8192 (two 16-byte vectors per thread and row).  max_wgs bounds the grid (the workspace holds two
+// candidates per workgroup).
+hipError_t launch_layer_loop(const LoopParams &p, int max_wgs, hipStream_t s) {
+    if (p.K == 4) return launch_loop_vpt<4, true>(p, max_wgs, s);
+    if (p.K == 8) return launch_loop_vpt<8, true>(p, max_wgs, s);
+    if (p.K < 4) return launch_loop_vpt<4, false>(p, max_wgs, s);
+    if (p.K < 8) return launch_loop_vpt<8, false>(p, max_wgs, s);
+    return launch_loop_vpt<16, false>(p, max_wgs, s);
+}
+
+}  // namespace specee

@@ -10,26 +10,14 @@
 // loads per row in flight, and reduces with DPP.  The RMSNorm scale multiplies
 // the finished dot product.
 #include "device_utils.h"
+#include "head_stream.h"
 #include "kernels.h"
 
 namespace specee {
 
 constexpr int kGemvThreads = 512;
 constexpr int kGemvWaves = kGemvThreads / kWave;
-constexpr int kGemvUnroll = 4;   // 16-byte loads in flight per row per wavefront
-constexpr int kGemvRows = 2;     // rows in flight per wavefront
-
-__device__ __forceinline__ float dot8(half8 w, floatx4 xa, floatx4 xb, float acc) {
-    acc += (float)w[0] * xa[0];
-    acc += (float)w[1] * xa[1];
-    acc += (float)w[2] * xa[2];
-    acc += (float)w[3] * xa[3];
-    acc += (float)w[4] * xb[0];
-    acc += (float)w[5] * xb[1];
-    acc += (float)w[6] * xb[2];
-    acc += (float)w[7] * xb[3];
-    return acc;
-}
+constexpr int kGemvRows = kHeadRows;  // rows in flight per wavefront
 
 // ARGMAX: instead of storing the V logits, keep the best (value, row) of this
 // workgroup's rows (lowest row on ties) and store one candidate per workgroup:
@@ -82,44 +70,15 @@ __global__ __launch_bounds__(kGemvThreads) void lm_head_gemv_kernel(int d, int V
     float *o = out + (size_t)n * V;
     float bv = -INFINITY;
     int bi = 0x7fffffff;
-    for (int row = row_begin + wave * kGemvRows; row < row_end; row += kGemvWaves * kGemvRows) {
-        const bool two = row + 1 < row_end;
-        const half_t *w0 = lm_head + (size_t)row * d;
-        const half_t *w1 = lm_head + (size_t)(two ? row + 1 : row) * d;
-        float acc0 = 0.f, acc1 = 0.f;
-        // loads are unconditional (vector index clamped, contribution selected afterwards) so that the
-        // compiler keeps them all in flight instead of draining the memory pipeline at a branch join
-        for (int v0 = lane; v0 < nv; v0 += kWave * kGemvUnroll) {
-            half8 a[kGemvUnroll], b[kGemvUnroll];
-#pragma unroll
-            for (int u = 0; u < kGemvUnroll; ++u) {
-                const int v = min(v0 + u * kWave, nv - 1);
-                a[u] = STREAM ? load_half8_stream(w0 + v * 8) : load_half8(w0 + v * 8);
-                b[u] = STREAM ? load_half8_stream(w1 + v * 8) : load_half8(w1 + v * 8);
-            }
-#pragma unroll
-            for (int u = 0; u < kGemvUnroll; ++u) {
-                const bool in = v0 + u * kWave < nv;
-                const int v = min(v0 + u * kWave, nv - 1);
-                const floatx4 pa = xa[v], pb = xb[v];
-                const float t0 = dot8(a[u], pa, pb, 0.f), t1 = dot8(b[u], pa, pb, 0.f);
-                acc0 += in ? t0 : 0.f;
-                acc1 += in ? t1 : 0.f;
-            }
-        }
-        if (ARGMAX) {
-            acc0 = wave_sum(acc0);
-            acc1 = wave_sum(acc1);
-            float v0 = acc0 * r, v1 = acc1 * r;
-            if (v0 > bv) {
-                bv = v0;
-                bi = row;
-            }
-            if (two && v1 > bv) {
-                bv = v1;
-                bi = row + 1;
-            }
-        } else {
+    if (ARGMAX) {
+        head_argmax_rows<STREAM>(lm_head, d, row_begin, row_end, wave, kGemvWaves, lane, xa, xb, r, bv, bi);
+    } else {
+        for (int row = row_begin + wave * kGemvRows; row < row_end; row += kGemvWaves * kGemvRows) {
+            const bool two = row + 1 < row_end;
+            const half_t *w0 = lm_head + (size_t)row * d;
+            const half_t *w1 = lm_head + (size_t)(two ? row + 1 : row) * d;
+            float acc0 = 0.f, acc1 = 0.f;
+            head_two_rows<STREAM>(w0, w1, nv, lane, xa, xb, acc0, acc1);
             acc0 = wave_sum_to_last_row(acc0);  // DPP only; the total lands in the last 16 lanes
             acc1 = wave_sum_to_last_row(acc1);
             if (lane == kWave - 1) {
@@ -198,51 +157,53 @@ __global__ __launch_bounds__(256) void verify_finish_kernel(const float *best_va
     }
 }
 
-// A head beyond this size cannot stay in the 256 MB last-level cache between calls: stream it.
-static bool head_streams(int d, int V) {
-    return (size_t)V * d * sizeof(half_t) > ((size_t)288 << 20);
+// Rows per workgroup: two resident workgroups per CU on 256 CUs, each with a contiguous block of rows
+// that is a whole number of rounds of its wavefronts.
+static int gemv_rows_per_wg(int V) {
+    const int wgs = 512;
+    const int quantum = kGemvWaves * kGemvRows;
+    return (((V + wgs - 1) / wgs + quantum - 1) / quantum) * quantum;
+}
+
+int lm_head_gemv_workgroups(int V) {
+    const int rows_per_wg = gemv_rows_per_wg(V);
+    return (V + rows_per_wg - 1) / rows_per_wg;
+}
+
+// One launch of the head kernel.  x = h * gamma takes 4*d bytes of dynamic LDS; from d = 12288 on that is
+// more than a kernel may use without asking, so the limit is raised (per launch: the library keeps no
+// state; a refusal shows as the launch error).
+template <bool ARGMAX, bool STREAM>
+static void launch_gemv_one(int d, int V, float eps, int N, const half_t *hidden, const half_t *gamma,
+                            const half_t *lm_head, float *out, float *best_val, int32_t *best_idx,
+                            const int32_t *gate, const int32_t *done, hipStream_t s) {
+    const int rows_per_wg = gemv_rows_per_wg(V);
+    const int wgs = (V + rows_per_wg - 1) / rows_per_wg;
+    const size_t lds = (size_t)d * sizeof(float);
+    auto kern = lm_head_gemv_kernel<ARGMAX, STREAM>;
+    if (lds > 48 * 1024)
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)lds);
+    hipLaunchKernelGGL(kern, dim3(wgs, N), dim3(kGemvThreads), lds, s, d, V, eps, hidden, gamma, lm_head, out,
+                       rows_per_wg, best_val, best_idx, gate, done);
 }
 
 hipError_t launch_lm_head_gemv(int d, int V, float eps, int N, const half_t *hidden, const half_t *gamma,
                                const half_t *lm_head, float *out, hipStream_t s) {
-    // two resident workgroups per CU on 256 CUs; each takes a contiguous block of rows
-    int wgs = 512;
-    int rows_per_wg = (V + wgs - 1) / wgs;
-    const int quantum = kGemvWaves * kGemvRows;
-    rows_per_wg = ((rows_per_wg + quantum - 1) / quantum) * quantum;
-    wgs = (V + rows_per_wg - 1) / rows_per_wg;
-    size_t lds = (size_t)d * sizeof(float);
     if (head_streams(d, V))
-        hipLaunchKernelGGL((lm_head_gemv_kernel<false, true>), dim3(wgs, N), dim3(kGemvThreads), lds, s, d, V, eps,
-                           hidden, gamma, lm_head, out, rows_per_wg, nullptr, nullptr, nullptr, nullptr);
+        launch_gemv_one<false, true>(d, V, eps, N, hidden, gamma, lm_head, out, nullptr, nullptr, nullptr, nullptr, s);
     else
-        hipLaunchKernelGGL((lm_head_gemv_kernel<false, false>), dim3(wgs, N), dim3(kGemvThreads), lds, s, d, V, eps,
-                           hidden, gamma, lm_head, out, rows_per_wg, nullptr, nullptr, nullptr, nullptr);
+        launch_gemv_one<false, false>(d, V, eps, N, hidden, gamma, lm_head, out, nullptr, nullptr, nullptr, nullptr, s);
     return hipGetLastError();
-}
-
-int lm_head_gemv_workgroups(int V) {
-    int wgs = 512;
-    int rows_per_wg = (V + wgs - 1) / wgs;
-    const int quantum = kGemvWaves * kGemvRows;
-    rows_per_wg = ((rows_per_wg + quantum - 1) / quantum) * quantum;
-    return (V + rows_per_wg - 1) / rows_per_wg;
 }
 
 hipError_t launch_lm_head_argmax_gemv(int d, int V, float eps, int N, const half_t *hidden, const half_t *gamma,
                                       const half_t *lm_head, float *best_val, int32_t *best_idx, const int32_t *gate,
                                       const int32_t *done, hipStream_t s) {
-    int wgs = lm_head_gemv_workgroups(V);
-    int rows_per_wg = (V + wgs - 1) / wgs;
-    const int quantum = kGemvWaves * kGemvRows;
-    rows_per_wg = ((rows_per_wg + quantum - 1) / quantum) * quantum;
-    size_t lds = (size_t)d * sizeof(float);
     if (head_streams(d, V))
-        hipLaunchKernelGGL((lm_head_gemv_kernel<true, true>), dim3(wgs, N), dim3(kGemvThreads), lds, s, d, V, eps,
-                           hidden, gamma, lm_head, nullptr, rows_per_wg, best_val, best_idx, gate, done);
+        launch_gemv_one<true, true>(d, V, eps, N, hidden, gamma, lm_head, nullptr, best_val, best_idx, gate, done, s);
     else
-        hipLaunchKernelGGL((lm_head_gemv_kernel<true, false>), dim3(wgs, N), dim3(kGemvThreads), lds, s, d, V, eps,
-                           hidden, gamma, lm_head, nullptr, rows_per_wg, best_val, best_idx, gate, done);
+        launch_gemv_one<true, false>(d, V, eps, N, hidden, gamma, lm_head, nullptr, best_val, best_idx, gate, done, s);
     return hipGetLastError();
 }
 

@@ -82,6 +82,24 @@ TreeLayout tree_layout(int S, int n_total, int Mcap) {
     return L;
 }
 
+// Workspace of the persistent layer loop: arrival counters [B] and the abort flag (cleared at every call),
+// then two buffers of arg-max candidates, one (value, row) pair per workgroup.
+constexpr int kLoopMaxTokens = 64;
+constexpr int kLoopMaxWgs = 1024;
+struct LoopLayout {
+    size_t flags_off, val_off, idx_off, total;
+    int flag_ints;
+};
+LoopLayout loop_layout(int B) {
+    LoopLayout l;
+    l.flag_ints = B + 1;
+    l.flags_off = 0;
+    l.val_off = align256((size_t)l.flag_ints * sizeof(int32_t));
+    l.idx_off = l.val_off + align256((size_t)2 * kLoopMaxWgs * sizeof(float));
+    l.total = l.idx_off + align256((size_t)2 * kLoopMaxWgs * sizeof(int32_t));
+    return l;
+}
+
 // Workspace of the whole-tree kernel when S > 1 workgroups share a tree: accumulators
 // [G][S][256 threads x row tiles] quads, sums of squares [G][S][64], tickets [G].
 size_t whole_tree_part_bytes(int G, int S, int Mcap) {
@@ -155,6 +173,9 @@ size_t specee_workspace_bytes(int op, const specee_dims *dm, int n, int Mcap) {
             int P = n <= 2 ? lm_head_gemv_workgroups(dm->V) : lm_head_gemm_workgroups(dm->V);
             return 2 * align256((size_t)n * P * sizeof(float));
         }
+        case SPECEE_OP_LAYER_LOOP:
+            if (check_dims(dm, true) || n > kLoopMaxTokens) return (size_t)-1;
+            return loop_layout(n).total;
         case SPECEE_OP_PREDICT_TREE:
             if (check_dims(dm, true) || Mcap < 1 || Mcap > 4096) return (size_t)-1;
         {
@@ -395,6 +416,45 @@ int specee_predict_tree_static(const specee_dims *dm, int G, int N, int Mcap, co
                                       M_out, cols, logits, probs, scores, exit_flags, path_exit, base,
                                       SPECEE_STATIC_SCRATCH_BYTES, true, stream);
     return r == SPECEE_EWORKSPACE ? SPECEE_ESCRATCH : r;
+}
+
+int specee_layer_loop(const specee_dims *dm, int L, int B, const specee_half *hidden, const specee_half *gamma,
+                      const specee_half *lm_head, const int32_t *ids, const float *prev0, const specee_mlp *mlp,
+                      const int32_t *active, float *logits, float *probs, float *scores, int32_t *exit_flags,
+                      int32_t *ver_token, int32_t *hit, int32_t *exit_layer, int32_t *token, int32_t *status,
+                      long long spin_limit, void *workspace, size_t workspace_bytes, void *stream) {
+    int rc = check_dims(dm, true);
+    if (rc) return rc;
+    if (dm->d > 8192 || B < 0 || B > kLoopMaxTokens || L < 0 || L > 65535 || spin_limit < 0) return SPECEE_EINVAL;
+    if (B == 0) return SPECEE_OK;
+    if (L > 0 && (rc = check_mlp(mlp))) return rc;
+    if (!exit_layer || !token || !status) return SPECEE_EINVAL;
+    if (L > 0 && (!hidden || !gamma || !lm_head || !ids || !logits || !probs || !scores || !exit_flags || !ver_token ||
+                  !hit))
+        return SPECEE_EINVAL;
+    if (misaligned(hidden) || misaligned(gamma) || misaligned(lm_head) || misaligned(workspace)) return SPECEE_EALIGN;
+    const LoopLayout lay = loop_layout(B);
+    if (!workspace || workspace_bytes < lay.total) return SPECEE_EWORKSPACE;
+    char *ws = static_cast<char *>(workspace);
+    LoopParams p{};
+    p.d = dm->d; p.V = dm->V; p.K = dm->K; p.H = dm->H; p.L = L; p.B = B;
+    p.eps = dm->eps; p.threshold = dm->threshold;
+    p.hidden = H(hidden); p.gamma = H(gamma); p.lm_head = H(lm_head); p.ids = ids; p.prev0 = prev0;
+    if (mlp) {
+        p.W1 = H(mlp->W1); p.b1 = H(mlp->b1); p.w2 = H(mlp->w2); p.b2 = H(mlp->b2);
+    }
+    p.active = active;
+    p.logits = logits; p.probs = probs; p.scores = scores; p.exit_flags = exit_flags;
+    p.ver_token = ver_token; p.hit = hit; p.exit_layer = exit_layer; p.token = token; p.status = status;
+    p.arrive = reinterpret_cast<int32_t *>(ws + lay.flags_off);
+    p.abort = p.arrive + B;
+    p.cand_val = reinterpret_cast<float *>(ws + lay.val_off);
+    p.cand_idx = reinterpret_cast<int32_t *>(ws + lay.idx_off);
+    p.spin_limit = spin_limit > 0 ? spin_limit : (1ll << 20);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (launch_zero_i32(p.arrive, lay.flag_ints, st) != hipSuccess) return SPECEE_EHIP;
+    // the launcher caps the grid at kLoopMaxWgs workgroups; each candidate buffer holds one entry per workgroup
+    return launch_layer_loop(p, kLoopMaxWgs, st) == hipSuccess ? SPECEE_OK : SPECEE_EHIP;
 }
 
 int specee_verify(const specee_dims *dm, int N, const specee_half *hidden, const specee_half *gamma,

@@ -15,7 +15,7 @@ _PKG = Path(__file__).resolve().parent
 LIB_PATH = _PKG / "libspecee.so"
 _lib = None
 
-OP_PREDICT, OP_PREDICT_SWEEP, OP_PREDICT_TREE, OP_LM_HEAD, OP_VERIFY = range(5)
+OP_PREDICT, OP_PREDICT_SWEEP, OP_PREDICT_TREE, OP_LM_HEAD, OP_VERIFY, OP_LAYER_LOOP = range(6)
 
 
 class SpeceeError(RuntimeError):
@@ -171,6 +171,37 @@ def predict_sweep(hidden, gamma, lm_head, ids, W1, w2, b1=None, b2=None, prev0=N
                                     _ptr(out["first_exit"]), _stream(stream))
     if rc:
         raise SpeceeError("specee_predict_sweep", rc)
+    return out
+
+
+def layer_loop(hidden, gamma, lm_head, ids, W1, w2, b1=None, b2=None, prev0=None, active=None, eps=1e-5,
+               threshold=0.5, spin_limit=0, out=None, workspace=None, stream=None):
+    """specee_layer_loop: hidden [L][B][d], one predictor per layer; predict -> verify -> exit on the device."""
+    L, B, d = hidden.shape
+    V = lm_head.shape[0]
+    K = ids.shape[1]
+    H = w2.shape[1]
+    dev = hidden.device
+    if out is None:
+        i32, f32 = torch.int32, torch.float32
+        out = dict(logits=torch.empty((L, B, K), dtype=f32, device=dev), probs=torch.empty((L, B, K), dtype=f32, device=dev),
+                   scores=torch.empty((L, B), dtype=f32, device=dev), exit=torch.empty((L, B), dtype=i32, device=dev),
+                   ver_token=torch.empty((L, B), dtype=i32, device=dev), hit=torch.empty((L, B), dtype=i32, device=dev),
+                   exit_layer=torch.empty((B,), dtype=i32, device=dev), token=torch.empty((B,), dtype=i32, device=dev),
+                   status=torch.empty((B,), dtype=i32, device=dev))
+    dims = _dims(d, V, K, H, eps, threshold)
+    mlp = _mlp(W1, w2, b1, b2)
+    workspace, wbytes = _workspace(OP_LAYER_LOOP, dims, B, 0, workspace, dev)
+    f16 = torch.float16
+    rc = lib().specee_layer_loop(C.byref(dims), C.c_int(L), C.c_int(B), _ptr(hidden, f16), _ptr(gamma, f16),
+                                 _ptr(lm_head, f16), _ptr(ids, torch.int32), _ptr(prev0, torch.float32), C.byref(mlp),
+                                 _ptr(active, torch.int32), _ptr(out["logits"]), _ptr(out["probs"]),
+                                 _ptr(out["scores"]), _ptr(out["exit"]), _ptr(out["ver_token"]), _ptr(out["hit"]),
+                                 _ptr(out["exit_layer"]), _ptr(out["token"]), _ptr(out["status"]),
+                                 C.c_longlong(int(spin_limit)), _ptr(workspace), wbytes, _stream(stream))
+    if rc:
+        raise SpeceeError("specee_layer_loop", rc)
+    out["_workspace"] = workspace
     return out
 
 

@@ -132,3 +132,158 @@ def test_layer_loop_device_side_control(sp, oracle):
         g.replay()
         torch.cuda.synchronize()
         check(state, exp, done_ref, c, f"graph replay {rep}")
+
+
+# ------------------------------------------------------------------ the same loop as ONE launch (specee_layer_loop)
+def loop_inputs(seed, d, V, K, H, L, B, plant, bias=True):
+    """Random model and tokens; token b's first id is the full head's arg-max at layer plant[b] (None: never)."""
+    rng = np.random.default_rng(seed)
+    t = dict(
+        hidden=rng.standard_normal((L, B, d)).astype(np.float16),
+        gamma=(1 + 0.05 * rng.standard_normal(d)).astype(np.float16),
+        lm_head=(0.05 * rng.standard_normal((V, d))).astype(np.float16),
+        ids=np.stack([rng.choice(V, K, replace=False) for _ in range(B)]).astype(np.int32),
+        W1=(0.1 * rng.standard_normal((L, H, 3 * K))).astype(np.float16),
+        w2=(0.1 * rng.standard_normal((L, H))).astype(np.float16),
+        b1=(0.1 * rng.standard_normal((L, H))).astype(np.float16) if bias else None,
+        b2=(0.1 * rng.standard_normal(L)).astype(np.float16) if bias else None)
+    return t, plant
+
+
+def plant_hits(oracle, t, plant):
+    V = t["lm_head"].shape[0]
+    K = t["ids"].shape[1]
+    for b, l in enumerate(plant):
+        if l is None:
+            continue
+        full = oracle.lm_head_gemv(t["hidden"][l][b:b + 1], t["gamma"], t["lm_head"])[0]
+        tok = int(full.argmax())
+        rest = [int(i) for i in t["ids"][b] if i != tok][:K - 1]
+        t["ids"][b] = [tok] + rest
+    return t
+
+
+def check_loop(oracle, sp, t, threshold, active=None, what="", graph=False):
+    L, B, d = t["hidden"].shape
+    ref = oracle.layer_loop(t["hidden"], t["gamma"], t["lm_head"], t["ids"], t["W1"], t["w2"], t["b1"], t["b2"],
+                            active=active, threshold=threshold)
+    live = ref["scores"] != 0
+    assert np.all(np.abs(ref["scores"][live] - threshold) > 1e-3), "pick another seed: a score sits on the threshold"
+    # a verification's arg-max is only comparable when the runner-up is further away than the tolerance
+    for l, b in zip(*np.nonzero(ref["exit"])):
+        full = np.sort(oracle.lm_head_gemv(t["hidden"][l][b:b + 1], t["gamma"], t["lm_head"])[0])
+        assert full[-1] - full[-2] > 4e-3 * max(1.0, abs(full[-1])), "pick another seed: arg-max nearly tied"
+    args = [dev(t[k]) for k in ("hidden", "gamma", "lm_head", "ids", "W1", "w2", "b1", "b2")]
+    kw = dict(active=dev(active), threshold=threshold)
+    out = sp.layer_loop(*args, **kw)
+    torch.cuda.synchronize()
+
+    def compare(o, tag):
+        g = {k: host(v) for k, v in o.items() if k != "_workspace"}
+        assert np.all(g["status"] == 0), tag + " status"
+        for k in ("exit", "ver_token", "hit", "exit_layer", "token"):
+            assert np.array_equal(g[k], ref[k]), f"{what} {tag} {k}"
+        close(g["logits"], ref["logits"], 1.0, f"{what} {tag} logits")
+        close(g["probs"], ref["probs"], 1e-3, f"{what} {tag} probs")
+        close(g["scores"], ref["scores"], 1e-3, f"{what} {tag} scores")
+    compare(out, "eager")
+    if graph:
+        ws = out.pop("_workspace")
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            sp.layer_loop(*args, out=out, workspace=ws, **kw)
+        torch.cuda.current_stream().wait_stream(s)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            sp.layer_loop(*args, out=out, workspace=ws, **kw)
+        for rep in range(3):
+            for k, x in out.items():
+                if k != "_workspace":
+                    x.fill_(7)
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            compare(out, f"graph replay {rep}")
+    return ref
+
+
+@pytest.mark.parametrize("seed,d,V,K,H,L,B,plant,threshold,bias", [
+    (6, 1032, 301, 4, 512, 6, 7, [0, 3, None, 5, 1, 2, 4], 0.45, True),     # ragged d, planted exits at every depth
+    (1, 2056, 997, 8, 512, 5, 3, [4, None, 2], 0.45, False),                # K = 8
+    (1, 520, 777, 3, 100, 7, 5, [6, 1, None, 3, 3], 0.48, True),            # K odd: generic MLP path
+    (1, 8192, 2000, 4, 1024, 4, 2, [3, 1], 0.45, True),                     # two vectors per thread, H > 512
+    (4, 64, 40, 16, 8, 5, 4, [2, 2, None, 0], 0.5, True),                   # K = KMAX, tiny d
+    (14, 1024, 1000, 4, 512, 6, 64, [i % 6 if i % 5 else None for i in range(64)], 0.6, False),  # 64 tokens: groups of 4
+])
+def test_layer_loop_one_launch_matches_oracle(sp, oracle, seed, d, V, K, H, L, B, plant, threshold, bias):
+    t, plant = loop_inputs(seed, d, V, K, H, L, B, plant, bias)
+    t = plant_hits(oracle, t, plant)
+    oracle.set_threads(8)
+    ref = check_loop(oracle, sp, t, threshold, what=f"loop d={d} K={K} B={B}", graph=(d == 1032))
+    oracle.set_threads(1)
+    assert ref["hit"].sum() >= 1 and (ref["exit"].sum() > ref["hit"].sum() or B <= 3)
+    assert (ref["exit_layer"] >= 0).any() and (ref["exit_layer"] < L - 1).any()
+
+
+def test_layer_loop_one_launch_active_mask_and_never_or_always_firing(sp, oracle):
+    t, plant = loop_inputs(12, 1032, 301, 4, 512, 6, 7, [0, 3, None, 5, 1, 2, 4])
+    t = plant_hits(oracle, t, plant)
+    active = np.array([0, 1, 1, 0, 1, 1], np.int32)
+    ref = check_loop(oracle, sp, t, 0.45, active=active, what="active mask")
+    assert not ref["scores"][0].any() and not ref["scores"][3].any()
+    ref = check_loop(oracle, sp, t, 2.0, what="never fires")              # no verification at all
+    assert np.all(ref["exit_layer"] == -1) and not ref["exit"].any()
+    ref = check_loop(oracle, sp, t, -1.0, what="always fires")            # a verification at every layer until the hit
+    assert ref["exit"].sum() >= 20
+
+
+def test_layer_loop_one_launch_llama7b_shape(sp, oracle):
+    """The 32-layer sweep of one token at d=4096, V=32000, K=4 with an accepted verification on the way."""
+    c = synth.CONFIGS["C2"]
+    t = synth.make("C2", seed=4, bias=False)
+    t = dict(t, ids=t["ids"].copy(), b1=None, b2=None)
+    oracle.set_threads(8)
+    # the drifting hidden state keeps its arg-max token over many layers, so the planted token is accepted at the
+    # first layer from which it leads and whose predictor fires (layer 14 here, after four rejected verifications)
+    t = plant_hits(oracle, t, [21])
+    ref = check_loop(oracle, sp, t, 0.5, what="7B shape", graph=True)
+    oracle.set_threads(1)
+    assert ref["exit_layer"][0] == 14 and ref["exit"].sum() == 5
+    print("7B loop: fired at", np.flatnonzero(ref["exit"][:, 0]).tolist(), "exit", ref["exit_layer"].tolist())
+
+
+def test_layer_loop_bounded_wait_gives_up_instead_of_hanging(sp, oracle):
+    """With a spin limit of one poll a group almost never meets: the call must still return, with status 1 for
+    the tokens it gave up on (or 0 with correct results if the workgroups did arrive together)."""
+    t, plant = loop_inputs(12, 1032, 3001, 4, 512, 4, 2, [1, 2])
+    t = plant_hits(oracle, t, plant)
+    args = [dev(t[k]) for k in ("hidden", "gamma", "lm_head", "ids", "W1", "w2", "b1", "b2")]
+    out = sp.layer_loop(*args, threshold=-1.0, spin_limit=1)
+    torch.cuda.synchronize()
+    st = host(out["status"])
+    assert set(st.tolist()) <= {0, 1}
+    ref = oracle.layer_loop(t["hidden"], t["gamma"], t["lm_head"], t["ids"], t["W1"], t["w2"], t["b1"], t["b2"],
+                            threshold=-1.0)
+    ok = st == 0
+    assert np.array_equal(host(out["exit_layer"])[ok], ref["exit_layer"][ok])
+    assert np.all(host(out["exit_layer"])[~ok] == -1) and np.all(host(out["token"])[~ok] == -1)
+    # the next call on the same workspace starts clean
+    out2 = sp.layer_loop(*args, threshold=-1.0, workspace=out["_workspace"])
+    torch.cuda.synchronize()
+    assert np.all(host(out2["status"]) == 0) and np.array_equal(host(out2["exit_layer"]), ref["exit_layer"])
+
+
+def test_layer_loop_argument_errors(sp):
+    z = lambda shape, dt: torch.zeros(shape, dtype=dt, device="cuda")
+    f16, i32 = torch.float16, torch.int32
+    L, B, d, V, K, H = 2, 65, 64, 10, 4, 8
+    with pytest.raises(sp.SpeceeError) as ei:     # more tokens than groups
+        sp.layer_loop(z((L, B, d), f16), z((d,), f16), z((V, d), f16), z((B, K), i32), z((L, H, 3 * K), f16),
+                      z((L, H), f16), workspace=torch.empty(1 << 20, dtype=torch.uint8, device="cuda"))
+    assert ei.value.code == -1
+    with pytest.raises(sp.SpeceeError) as ei:     # workspace too small
+        sp.layer_loop(z((L, 2, d), f16), z((d,), f16), z((V, d), f16), z((2, K), i32), z((L, H, 3 * K), f16),
+                      z((L, H), f16), workspace=torch.empty(64, dtype=torch.uint8, device="cuda"))
+    assert ei.value.code == -3
