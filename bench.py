@@ -80,18 +80,32 @@ def main():
     def up(a):
         return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dev)
 
+    last_spread = {}
+
     def ev_time(fn, iters, warm):
-        """milliseconds per call of fn, HIP events on the stream the kernels run on"""
+        """Milliseconds per call of fn (median over up to ten consecutive samples of the timed calls), from HIP
+        events on the stream the kernels run on.  The spread of the samples is kept for spread()."""
         for _ in range(warm):
             fn()
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(iters):
-            fn()
-        e1.record()
+        nsamp = min(10, iters)
+        per = max(1, iters // nsamp)
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(nsamp + 1)]
+        evs[0].record()
+        for i in range(nsamp):
+            for _ in range(per):
+                fn()
+            evs[i + 1].record()
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / iters
+        ms = np.array([evs[i].elapsed_time(evs[i + 1]) / per for i in range(nsamp)])
+        last_spread.update(p10=float(np.percentile(ms, 10)), median=float(np.median(ms)),
+                           p90=float(np.percentile(ms, 90)), samples=nsamp, calls_per_sample=per)
+        return float(np.median(ms))
+
+    def spread(div=1.0):
+        """p10 / p90 of the last ev_time() in microseconds per unit (div units per call of fn)."""
+        return {"us_p10": last_spread["p10"] * 1e3 / div, "us_p90": last_spread["p90"] * 1e3 / div,
+                "timing_samples": last_spread["samples"]}
 
     def capture(fn):
         """Capture fn's launches into a HIP graph; returns the graph."""
@@ -145,15 +159,23 @@ def main():
             graphs[w % R].replay()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        # marks inside the timed region (an event record costs the stream nothing measurable): twenty slices of it
+        nsl = max(1, min(20, args.steps))
+        cuts = sorted(set(int(round(i * args.steps / nsl)) for i in range(1, nsl)))
+        marks = {c: torch.cuda.Event(enable_timing=True) for c in cuts}
         t0 = time.perf_counter()
         e0.record()
         for k in range(args.steps):
+            if k in marks:
+                marks[k].record()
             graphs[k % R].replay()
         e1.record()
         torch.cuda.synchronize()
         wall_ms = (time.perf_counter() - t0) * 1e3
         ms_per_step = e0.elapsed_time(e1) / args.steps
         us_per_call = ms_per_step * 1e3 / L
+        edges = [(0, e0)] + [(c, marks[c]) for c in cuts] + [(args.steps, e1)]
+        slice_us = np.array([a[1].elapsed_time(b[1]) * 1e3 / ((b[0] - a[0]) * L) for a, b in zip(edges, edges[1:])])
         alg = predict_bytes(d, K)
         achieved = alg / (us_per_call * 1e-6) / 1e9
         result = {
@@ -163,6 +185,8 @@ def main():
             "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
             "ms_per_step": ms_per_step,
             "us_per_call": us_per_call,
+            "us_per_call_p10_median_p90": [float(np.percentile(slice_us, 10)), float(np.median(slice_us)),
+                                           float(np.percentile(slice_us, 90))],
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
             "dtype": "f32", "dtype_note": "fp16 inputs widened exactly, fp32 products and sums", "data": "synthetic",
             "config": {"workload": "C2: 32-layer exit sweep for one token, d=4096 V=32000 K=4, MLP 12->512->1, "
@@ -189,7 +213,7 @@ def main():
                 gs[it[0] % len(gs)].replay()
                 it[0] += 1
             ms = ev_time(rot, 400, 40)
-            extra["c2_one_launch_sweep"] = {"us_per_sweep": ms * 1e3, "evals_per_s": L / (ms * 1e-3)}
+            extra["c2_one_launch_sweep"] = {"us_per_sweep": ms * 1e3, "evals_per_s": L / (ms * 1e-3), **spread()}
 
     # ------------------------------------------------------------------ C1: isolated single call, cold vs warm
     if want("single") and not args.no_extra:
@@ -210,6 +234,7 @@ def main():
                 sp.predict(hid[:1], gamma, lm, ids[:1], prev[:1], w1_1, w2_1, out=outs)
         gc, gw = capture(cold_calls), capture(warm_calls)
         us_cold = ev_time(gc.replay, 20, 3) * 1e3 / R1
+        sp_cold = spread(R1)
         us_warm = ev_time(gw.replay, 20, 3) * 1e3 / R1
         # the 256 rotating inputs above fit the 256 MB last-level cache; 7680 tokens whose rows cover the whole
         # head (and 63 MB of hidden states) do not, so these calls find their rows in HBM
@@ -226,7 +251,7 @@ def main():
         us_hbm = ev_time(gh.replay, 3, 1) * 1e3 / R2
         del gh
         extra["c1_single_call"] = {"us_per_call_rotated_ids": us_cold, "us_per_call_same_inputs": us_warm,
-                                   "us_per_call_rows_from_hbm": us_hbm,
+                                   "us_per_call_rows_from_hbm": us_hbm, "rotated_ids": sp_cold,
                                    "algorithmic_bytes": predict_bytes(d, K)}
 
     # ------------------------------------------------------------------ full-vocabulary head, N=1 (what the predictor replaces)
@@ -241,9 +266,10 @@ def main():
             it[0] += 1
         g = capture(lambda: [full() for _ in range(8)])
         lm_us = ev_time(g.replay, 30, 5) * 1e3 / 8
+        sp_lm = spread(8)
         byts = V * d * 2 + d * 4 + V * 4
         extra["lm_head_gemv_32000x4096"] = {
-            "us_per_call": lm_us, "achieved_GBps": byts / lm_us / 1e3, "frac_of_8TBps": byts / lm_us / 1e3 / HBM_PEAK_GBS,
+            "us_per_call": lm_us, **sp_lm, "achieved_GBps": byts / lm_us / 1e3, "frac_of_8TBps": byts / lm_us / 1e3 / HBM_PEAK_GBS,
             "algorithmic_bytes": byts, "traffic": MEASURED_TRAFFIC.get("lm_head_gemv_7b"),
             "note": "262 MB head is re-read every call; the 256 MB Infinity Cache can hold part of it"}
         vids = up(synth.ids_uniform_distinct(1, K, V, 5))
@@ -252,7 +278,7 @@ def main():
                           device=dev)
         gv = capture(lambda: [sp.verify(hid[i:i + 1], gamma, lm, vids, out=vout, workspace=vws) for i in range(8)])
         v_us = ev_time(gv.replay, 30, 5) * 1e3 / 8
-        extra["specee_verify_32000x4096"] = {"us_per_call": v_us, "achieved_GBps": V * d * 2 / v_us / 1e3}
+        extra["specee_verify_32000x4096"] = {"us_per_call": v_us, **spread(8), "achieved_GBps": V * d * 2 / v_us / 1e3}
         if result is not None:
             extra["speedup_vs_full_vocab_head"] = {
                 "predictor_us": result["us_per_call"], "lm_head_gemv_us": lm_us,
@@ -279,7 +305,7 @@ def main():
             g = capture(lambda: [sp.predict(hid, gamma, lm, ids, prev, w1_1, w2_1, out=o) for _ in range(reps)])
             us = ev_time(g.replay, 20, 3) * 1e3 / reps
             byts = predict_bytes(d, K, B, distinct_rows=len(np.unique(ids_h)))
-            tp[f"B={B}"] = {"us_per_launch": us, "evals_per_s": B / us * 1e6, "algorithmic_bytes": byts,
+            tp[f"B={B}"] = {"us_per_launch": us, **spread(reps), "evals_per_s": B / us * 1e6, "algorithmic_bytes": byts,
                             "achieved_GBps": byts / us / 1e3, "frac_of_8TBps": byts / us / 1e3 / HBM_PEAK_GBS}
         # B=8000 touches every row of the 262 MB head, most of which the 256 MB last-level cache can keep from
         # one launch to the next; alternating between two different heads takes that help away
@@ -294,7 +320,7 @@ def main():
                              for r in range(8)])
         us = ev_time(g.replay, 20, 3) * 1e3 / 8
         byts = predict_bytes(d, K, B, distinct_rows=B * K)
-        tp["B=8000_two_heads_alternating"] = {"us_per_launch": us, "evals_per_s": B / us * 1e6,
+        tp["B=8000_two_heads_alternating"] = {"us_per_launch": us, **spread(8), "evals_per_s": B / us * 1e6,
                                               "algorithmic_bytes": byts, "achieved_GBps": byts / us / 1e3,
                                               "frac_of_8TBps": byts / us / 1e3 / HBM_PEAK_GBS}
         del lm_b
@@ -323,7 +349,7 @@ def main():
         g = capture(tree_calls_prealloc)
         us = ev_time(g.replay, 20, 3) * 1e3 / len(dev_trees)
         byts = int(np.mean([c3.N * d * 2 + m * d * 2 for m in Ms])) + d * 2 + (3 * K * H + H) * 2
-        extra["c3_tree_N60"] = {"us_per_call": us, "mean_M": float(np.mean(Ms)), "algorithmic_bytes": byts,
+        extra["c3_tree_N60"] = {"us_per_call": us, **spread(len(dev_trees)), "mean_M": float(np.mean(Ms)), "algorithmic_bytes": byts,
                                 "achieved_GBps": byts / us / 1e3, "node_evals_per_s": c3.N / us * 1e6}
         # throughput: G different trees per launch (own hidden states, own id pools)
         for G in (64, 256):
@@ -351,7 +377,7 @@ def main():
             # what the launch really requests: every tree reads its own merged rows (rows shared between
             # trees are served by the caches the second time, but they do cross the memory path)
             bytsT = G * c3.N * d * 2 + sum(len(np.unique(x)) for x in ii_h) * d * 2 + d * 2 + (3 * K * H + H) * 2
-            extra[f"c3_tree_batch_G{G}"] = {"us_per_launch": us, "node_evals_per_s": G * c3.N / us * 1e6,
+            extra[f"c3_tree_batch_G{G}"] = {"us_per_launch": us, **spread(reps), "node_evals_per_s": G * c3.N / us * 1e6,
                                             "distinct_rows_in_batch": int(len(np.unique(ii_h))),
                                             "algorithmic_bytes": bytsG, "achieved_GBps": bytsG / us / 1e3,
                                             "frac_of_8TBps": bytsG / us / 1e3 / HBM_PEAK_GBS,
@@ -393,7 +419,7 @@ def main():
                                  for _ in range(reps)])
             us = ev_time(g.replay, 20, 3) * 1e3 / reps
             byts = q4_bytes(B, len(np.unique(ids_h)))
-            res[f"B={B}"] = {"us_per_launch": us, "evals_per_s": B / us * 1e6, "algorithmic_bytes": byts,
+            res[f"B={B}"] = {"us_per_launch": us, **spread(reps), "evals_per_s": B / us * 1e6, "algorithmic_bytes": byts,
                              "achieved_GBps": byts / us / 1e3, "frac_of_8TBps": byts / us / 1e3 / HBM_PEAK_GBS}
         extra["q4_predict_7b"] = res
         del qd, sd, zd
@@ -424,6 +450,7 @@ def main():
         # never fires: every layer pays the predictor and two empty verification launches
         g = capture(lambda: loop(2.0))
         res["never_fires_us_per_token"] = ev_time(g.replay, 50, 5) * 1e3
+        res["never_fires_spread"] = spread()
         # always fires, never hits: every layer pays a full-vocabulary verification
         g = capture(lambda: loop(-1.0))
         res["always_fires_never_hits_us_per_token"] = ev_time(g.replay, 20, 3) * 1e3
@@ -449,6 +476,7 @@ def main():
         g = one_launch(2.0, ids_rand)
         us = ev_time(g.replay, 200, 20) * 1e3
         r1["never_fires_us_per_token"] = us
+        r1["never_fires_spread"] = spread()
         r1["never_fires_us_per_layer"] = us / L
         g = one_launch(-1.0, ids_rand)
         us = ev_time(g.replay, 20, 3) * 1e3
@@ -489,13 +517,13 @@ def main():
         nrows = len(np.unique(t4["ids"]))
         byts_layer = predict_bytes(c4.d, c4.K, c4.B, distinct_rows=nrows)
         extra["c4_13b_16seq_per_layer_calls"] = {
-            "us_per_layer_call": ms * 1e3 / c4.L, "ms_all_40_layers": ms, "evals_per_s": c4.L * c4.B / (ms * 1e-3),
+            "us_per_layer_call": ms * 1e3 / c4.L, **spread(c4.L), "ms_all_40_layers": ms, "evals_per_s": c4.L * c4.B / (ms * 1e-3),
             "algorithmic_bytes_per_layer": byts_layer, "achieved_GBps": byts_layer / (ms * 1e3 / c4.L) / 1e3}
         so = sp.predict_sweep(T4["hidden"], T4["gamma"], lm4, T4["ids"], T4["W1"], T4["w2"])
         g = capture(lambda: sp.predict_sweep(T4["hidden"], T4["gamma"], lm4, T4["ids"], T4["W1"], T4["w2"], out=so))
         us = ev_time(g.replay, 100, 10) * 1e3
         byts = c4.L * c4.B * c4.d * 2 + nrows * c4.d * 2 + c4.d * 2 + c4.L * (3 * c4.K * H + H) * 2
-        extra["c4_13b_one_launch_sweep"] = {"us_per_launch": us, "evals_per_s": c4.L * c4.B / us * 1e6,
+        extra["c4_13b_one_launch_sweep"] = {"us_per_launch": us, **spread(), "evals_per_s": c4.L * c4.B / us * 1e6,
                                             "algorithmic_bytes": byts, "achieved_GBps": byts / us / 1e3,
                                             "frac_of_8TBps": byts / us / 1e3 / HBM_PEAK_GBS}
         del lm4, T4
@@ -525,13 +553,13 @@ def main():
         g = capture(c5_calls)
         us_tree = ev_time(g.replay, 20, 3) * 1e3 / len(dts)
         byts = int(np.mean([c5.N * c5.d * 2 + m * c5.d * 2 for m in Ms])) + c5.d * 2 + (3 * c5.K * H + H) * 2
-        extra["c5_tree_N64_V128256"] = {"us_per_call": us_tree, "mean_M": float(np.mean(Ms)),
+        extra["c5_tree_N64_V128256"] = {"us_per_call": us_tree, **spread(len(dts)), "mean_M": float(np.mean(Ms)),
                                         "algorithmic_bytes": byts, "achieved_GBps": byts / us_tree / 1e3}
         full = torch.empty((c5.N, c5.V), device=dev)
         g = capture(lambda: sp.lm_head_gemv(dts[0][0], g5, lm5, out=full))
         us64 = ev_time(g.replay, 30, 5) * 1e3
         b64 = c5.V * c5.d * 2 + c5.N * c5.d * 2 + c5.N * c5.V * 4
-        extra["lm_head_gemv_128256x8192_N64"] = {"us_per_call": us64, "algorithmic_bytes": b64,
+        extra["lm_head_gemv_128256x8192_N64"] = {"us_per_call": us64, **spread(), "algorithmic_bytes": b64,
                                                  "achieved_GBps": b64 / us64 / 1e3,
                                                  "frac_of_8TBps": b64 / us64 / 1e3 / HBM_PEAK_GBS,
                                                  "mfma_TFLOPs": 2 * 2.0 * c5.N * c5.V * c5.d / us64 / 1e6,
@@ -540,7 +568,7 @@ def main():
         g = capture(lambda: sp.lm_head_gemv(dts[0][0][:1], g5, lm5, out=one))
         us1 = ev_time(g.replay, 30, 5) * 1e3
         b1 = c5.V * c5.d * 2 + c5.d * 4 + c5.V * 4
-        extra["lm_head_gemv_128256x8192_N1"] = {"us_per_call": us1, "algorithmic_bytes": b1,
+        extra["lm_head_gemv_128256x8192_N1"] = {"us_per_call": us1, **spread(), "algorithmic_bytes": b1,
                                                 "achieved_GBps": b1 / us1 / 1e3,
                                                 "frac_of_8TBps": b1 / us1 / 1e3 / HBM_PEAK_GBS}
         extra["c5_tree_N64_V128256"]["speedup_vs_full_head_N64"] = us64 / us_tree
@@ -570,7 +598,7 @@ def main():
                                         workspace=wsb)
             g = capture(c5_batch)
             us = ev_time(g.replay, 10, 2) * 1e3 / 4
-            extra[f"c5_tree_batch_G{G}"] = {"us_per_launch": us, "node_evals_per_s": G * c5.N / us * 1e6,
+            extra[f"c5_tree_batch_G{G}"] = {"us_per_launch": us, **spread(4), "node_evals_per_s": G * c5.N / us * 1e6,
                                             "bytes_with_rows_counted_per_tree": bytes_tree,
                                             "frac_of_8TBps_rows_per_tree": bytes_tree / us / 1e3 / HBM_PEAK_GBS}
             del batches

@@ -245,6 +245,77 @@ def verify(hidden, gamma, lm_head, ids, eps=1e-5):
     return dict(token=token, max_logit=mx, hit=hit)
 
 
+def _q4(qweight, scales, zeros, group, d):
+    qweight = np.ascontiguousarray(qweight, dtype=np.uint32)
+    scales, zeros = _h(scales), _h(zeros)
+    V = qweight.shape[0]
+    assert qweight.shape == (V, d // 8) and scales.shape == (V, d // group) and zeros.shape == scales.shape
+    return qweight, scales, zeros, V
+
+
+def lm_head_gemv_q4(hidden, gamma, qweight, scales, zeros, group, eps=1e-5):
+    """Every vocabulary logit against the 4-bit group-quantised head: out [N][V]."""
+    hidden, gamma = _h(hidden), _h(gamma)
+    N, d = hidden.shape
+    qweight, scales, zeros, V = _q4(qweight, scales, zeros, group, d)
+    out = np.zeros((N, V))
+    u16 = C.c_uint16
+    rc = lib().lm_head_gemv_q4_ref(C.c_int(d), C.c_int(V), C.c_double(eps), C.c_int(N), _p(hidden, u16),
+                                   _p(gamma, u16), _p(qweight, C.c_uint32), _p(scales, u16), _p(zeros, u16),
+                                   C.c_int(group), _p(out, C.c_double))
+    _check(rc, "lm_head_gemv_q4_ref")
+    return out
+
+
+def verify_q4(hidden, gamma, qweight, scales, zeros, group, ids, eps=1e-5):
+    hidden, gamma, ids = _h(hidden), _h(gamma), _i(ids)
+    N, d = hidden.shape
+    qweight, scales, zeros, V = _q4(qweight, scales, zeros, group, d)
+    K = ids.shape[1]
+    token = np.zeros(N, dtype=np.int32); mx = np.zeros(N); hit = np.zeros(N, dtype=np.int32)
+    u16 = C.c_uint16
+    rc = lib().specee_verify_q4_ref(C.c_int(d), C.c_int(V), C.c_int(K), C.c_double(eps), C.c_int(N),
+                                    _p(hidden, u16), _p(gamma, u16), _p(qweight, C.c_uint32), _p(scales, u16),
+                                    _p(zeros, u16), C.c_int(group), _p(ids, C.c_int32), _p(token, C.c_int32),
+                                    _p(mx, C.c_double), _p(hit, C.c_int32))
+    _check(rc, "specee_verify_q4_ref")
+    return dict(token=token, max_logit=mx, hit=hit)
+
+
+def predict_tree_q4(hidden, gamma, qweight, scales, zeros, group, ids, prev_probs, W1, w2, b1=None, b2=None,
+                    parent=None, Mcap=64, eps=1e-5, threshold=0.5):
+    """G trees of N nodes against the quantised head.  hidden [G][N][d] (or [N][d]); ids [G][N][K]."""
+    single = hidden.ndim == 2
+    if single:
+        hidden, ids, prev_probs = hidden[None], np.asarray(ids)[None], np.asarray(prev_probs)[None]
+        parent = None if parent is None else np.asarray(parent)[None]
+    hidden, gamma = _h(hidden), _h(gamma)
+    ids, prev, parent = _i(ids), _f(prev_probs), _i(parent)
+    W1, w2, b1, b2 = _h(W1), _h(w2), _h(b1), _h(b2)
+    G, N, d = hidden.shape
+    qweight, scales, zeros, V = _q4(qweight, scales, zeros, group, d)
+    K = ids.shape[2]
+    H = w2.shape[0]
+    assert ids.shape == (G, N, K) and prev.shape == (G, N, K) and W1.shape == (H, 3 * K)
+    merged = np.zeros((G, Mcap), dtype=np.int32); M = np.zeros(G, dtype=np.int32)
+    cols = np.zeros((G, N, K), dtype=np.int32)
+    logits = np.zeros((G, N, K)); probs = np.zeros((G, N, K)); scores = np.zeros((G, N))
+    ex = np.zeros((G, N), dtype=np.int32)
+    path = np.zeros((G, N), dtype=np.int32) if parent is not None else None
+    u16, u32, i32, f32, f64 = C.c_uint16, C.c_uint32, C.c_int32, C.c_float, C.c_double
+    rc = lib().specee_predict_tree_q4_ref(
+        C.c_int(d), C.c_int(V), C.c_int(K), C.c_int(H), C.c_double(eps), C.c_float(threshold),
+        C.c_int(G), C.c_int(N), C.c_int(Mcap), _p(hidden, u16), _p(gamma, u16), _p(qweight, u32), _p(scales, u16),
+        _p(zeros, u16), C.c_int(group), _p(ids, i32), _p(parent, i32), _p(prev, f32), _p(W1, u16), _p(b1, u16),
+        _p(w2, u16), _p(b2, u16), _p(merged, i32), _p(M, i32), _p(cols, i32), _p(logits, f64), _p(probs, f64),
+        _p(scores, f64), _p(ex, i32), _p(path, i32))
+    _check(rc, "specee_predict_tree_q4_ref")
+    out = dict(merged=merged, M=M, cols=cols, logits=logits, probs=probs, scores=scores, exit=ex, path_exit=path)
+    if single:
+        out = {k: (v[0] if v is not None else None) for k, v in out.items()}
+    return out
+
+
 def layer_loop(hidden, gamma, lm_head, ids, W1, w2, b1=None, b2=None, prev0=None, active=None, eps=1e-5,
                threshold=0.5):
     """The early-exit loop of B tokens down L layers: predictor at every active layer, verification after a

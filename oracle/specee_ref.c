@@ -205,6 +205,22 @@ int specee_predict_ref(int d, int V, int K, int H, double eps, float threshold, 
  * Everything else is specee_predict_ref: the logits are taken against these
  * weights, nothing is rounded in between.
  */
+/* One logit against row v of the quantised head: <RMSNorm(h), w_v> with
+ * w_v[i] = scale[v][i/group] * (code[v][i] - zero[v][i/group]). */
+static double normed_dot_q4(const uint16_t *h, const uint16_t *gamma, const uint32_t *qweight, const uint16_t *scales,
+                            const uint16_t *zeros, int group, size_t v, int d, double r) {
+    const int ng = d / group;
+    double acc = 0.0;
+    for (int i = 0; i < d; ++i) {
+        const uint32_t word = qweight[v * (size_t)(d / 8) + (size_t)(i / 8)];
+        const double code = (double)((word >> (4 * (i % 8))) & 15u);
+        const double w = H2D(scales[v * ng + i / group]) * (code - H2D(zeros[v * ng + i / group]));
+        const double x = H2D(h[i]) * r * H2D(gamma[i]);
+        acc += x * w;
+    }
+    return acc;
+}
+
 int specee_predict_q4_ref(int d, int V, int K, int H, double eps, float threshold, int B, const uint16_t *hidden,
                           const uint16_t *gamma, const uint32_t *qweight, const uint16_t *scales,
                           const uint16_t *zeros, int group, const int32_t *ids, const float *prev_probs,
@@ -214,22 +230,12 @@ int specee_predict_q4_ref(int d, int V, int K, int H, double eps, float threshol
     if (group < 8 || group % 8 != 0 || d % group != 0) return REF_EINVAL;
     for (int i = 0; i < B * K; ++i)
         if (ids[i] < 0 || ids[i] >= V) return REF_EINVAL;
-    const int ng = d / group;
 #pragma omp parallel for num_threads(g_threads) schedule(static)
     for (int n = 0; n < B; ++n) {
         const uint16_t *h = hidden + (size_t)n * d;
         double r = specee_ref_rms_scale(h, d, eps);
         for (int k = 0; k < K; ++k) {
-            const size_t v = (size_t)ids[n * K + k];
-            double acc = 0.0;
-            for (int i = 0; i < d; ++i) {
-                const uint32_t word = qweight[v * (size_t)(d / 8) + (size_t)(i / 8)];
-                const double code = (double)((word >> (4 * (i % 8))) & 15u);
-                const double w = H2D(scales[v * ng + i / group]) * (code - H2D(zeros[v * ng + i / group]));
-                const double x = H2D(h[i]) * r * H2D(gamma[i]);
-                acc += x * w;
-            }
-            logits[n * K + k] = acc;
+            logits[n * K + k] = normed_dot_q4(h, gamma, qweight, scales, zeros, group, (size_t)ids[n * K + k], d, r);
         }
         score_token(logits + n * K, prev_probs + n * K, K, H, W1, b1, w2, b2, threshold, probs + n * K,
                     features ? features + (size_t)n * 3 * K : NULL, scores + n, exit_flags + n);
@@ -431,6 +437,103 @@ int specee_verify_ref(int d, int V, int K, double eps, int N, const uint16_t *hi
             if (ids[n * K + k] == best) hit[n] = 1;
     }
     free(y);
+    return REF_OK;
+}
+
+/*
+ * The full-vocabulary head, the verification and the token tree on the 4-bit
+ * group-quantised LM head (the quantised setting of Sec. 7.1 / 7.3 runs the whole
+ * predict -> verify loop, and the tree mapping, on the quantised model): the
+ * definitions above with every LM-head row replaced by its dequantised weights
+ * scale * (code - zero); nothing else changes and nothing is rounded.
+ */
+int lm_head_gemv_q4_ref(int d, int V, double eps, int N, const uint16_t *hidden, const uint16_t *gamma,
+                        const uint32_t *qweight, const uint16_t *scales, const uint16_t *zeros, int group,
+                        double *out) {
+    if (d < 1 || V < 1 || N < 0) return REF_EINVAL;
+    if (group < 8 || group % 8 != 0 || d % group != 0) return REF_EINVAL;
+    for (int n = 0; n < N; ++n) {
+        const uint16_t *h = hidden + (size_t)n * d;
+        double r = specee_ref_rms_scale(h, d, eps);
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+        for (int v = 0; v < V; ++v)
+            out[(size_t)n * V + v] = normed_dot_q4(h, gamma, qweight, scales, zeros, group, (size_t)v, d, r);
+    }
+    return REF_OK;
+}
+
+int specee_verify_q4_ref(int d, int V, int K, double eps, int N, const uint16_t *hidden, const uint16_t *gamma,
+                         const uint32_t *qweight, const uint16_t *scales, const uint16_t *zeros, int group,
+                         const int32_t *ids, int32_t *token, double *max_logit, int32_t *hit) {
+    if (d < 1 || V < 1 || N < 0 || K < 1) return REF_EINVAL;
+    double *y = (double *)malloc(sizeof(double) * (size_t)V);
+    if (!y) return REF_EINVAL;
+    for (int n = 0; n < N; ++n) {
+        int rc = lm_head_gemv_q4_ref(d, V, eps, 1, hidden + (size_t)n * d, gamma, qweight, scales, zeros, group, y);
+        if (rc != REF_OK) {
+            free(y);
+            return rc;
+        }
+        int best = 0;
+        for (int v = 1; v < V; ++v)
+            if (y[v] > y[best]) best = v; /* strict: the lowest id wins a tie */
+        token[n] = best;
+        max_logit[n] = y[best];
+        hit[n] = 0;
+        for (int k = 0; k < K; ++k)
+            if (ids[n * K + k] == best) hit[n] = 1;
+    }
+    free(y);
+    return REF_OK;
+}
+
+int specee_predict_tree_q4_ref(int d, int V, int K, int H, double eps, float threshold, int G, int N, int Mcap,
+                               const uint16_t *hidden, const uint16_t *gamma, const uint32_t *qweight,
+                               const uint16_t *scales, const uint16_t *zeros, int group, const int32_t *ids,
+                               const int32_t *parent, const float *prev_probs, const uint16_t *W1,
+                               const uint16_t *b1, const uint16_t *w2, const uint16_t *b2, int32_t *merged,
+                               int32_t *M_out, int32_t *cols, double *logits, double *probs, double *scores,
+                               int32_t *exit_flags, int32_t *path_exit) {
+    if (check_dims(d, V, K, H, N) || G < 0 || Mcap < 1) return REF_EINVAL;
+    if (group < 8 || group % 8 != 0 || d % group != 0) return REF_EINVAL;
+    if (path_exit && !parent) return REF_EINVAL;
+    for (size_t i = 0; i < (size_t)G * N * K; ++i)
+        if (ids[i] < 0 || ids[i] >= V) return REF_EINVAL;
+    if (parent)
+        for (int g = 0; g < G; ++g)
+            for (int n = 0; n < N; ++n) {
+                int32_t p = parent[(size_t)g * N + n];
+                if (p < -1 || p >= n) return REF_EINVAL;
+            }
+    for (int g = 0; g < G; ++g) {
+        int32_t *gmerged = merged + (size_t)g * Mcap;
+        int32_t *gcols = cols + (size_t)g * N * K;
+        int rc = specee_merge_ref(ids + (size_t)g * N * K, N * K, gmerged, Mcap, M_out + g, gcols);
+        if (rc != REF_OK) return rc;
+        const int M = M_out[g];
+        double *Z = (double *)malloc(sizeof(double) * (size_t)N * (size_t)(M > 0 ? M : 1));
+        if (!Z) return REF_EINVAL;
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+        for (int n = 0; n < N; ++n) { /* every node against every merged token of its tree */
+            const uint16_t *h = hidden + ((size_t)g * N + n) * d;
+            double r = specee_ref_rms_scale(h, d, eps);
+            for (int m = 0; m < M; ++m)
+                Z[(size_t)n * M + m] = normed_dot_q4(h, gamma, qweight, scales, zeros, group, (size_t)gmerged[m], d, r);
+        }
+        for (int n = 0; n < N; ++n) { /* each node reads back its own K columns */
+            size_t gn = (size_t)g * N + n;
+            for (int k = 0; k < K; ++k) logits[gn * K + k] = Z[(size_t)n * M + gcols[n * K + k]];
+            score_token(logits + gn * K, prev_probs + gn * K, K, H, W1, b1, w2, b2, threshold, probs + gn * K,
+                        NULL, scores + gn, exit_flags + gn);
+        }
+        free(Z);
+        if (path_exit)
+            for (int n = 0; n < N; ++n) {
+                size_t gn = (size_t)g * N + n;
+                int32_t p = parent[gn];
+                path_exit[gn] = exit_flags[gn] && (p < 0 ? 1 : path_exit[(size_t)g * N + p]);
+            }
+    }
     return REF_OK;
 }
 

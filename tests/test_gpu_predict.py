@@ -337,7 +337,8 @@ def test_sweep_c4_llama13b_16_sequences_40_layers(sp, oracle):
 
 
 # ---------------------------------------------------------------- full-vocabulary head
-@pytest.mark.parametrize("d,V,N", [(8, 1, 1), (64, 37, 3), (1032, 1000, 2), (4096, 4099, 1), (8200, 515, 2)])
+@pytest.mark.parametrize("d,V,N", [(8, 1, 1), (64, 37, 3), (1032, 1000, 2), (4096, 4099, 1), (8200, 515, 2),
+                                   (16384, 130, 2)])      # the largest accepted hidden size (64 KB of LDS for x)
 def test_lm_head_small(sp, oracle, d, V, N):
     t = custom(d + V, d, V, 1, 1, N, False)
     ref = oracle.lm_head_gemv(t["hidden"], t["gamma"], t["lm_head"])

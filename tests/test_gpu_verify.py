@@ -39,7 +39,7 @@ def check_verify(got, full, ids, what):
 
 
 @pytest.mark.parametrize("d,V,N,K", [(64, 37, 1, 3), (1032, 1001, 2, 4), (4096, 515, 5, 4), (520, 4100, 64, 8),
-                                     (2048, 300, 70, 2), (8, 1, 1, 1)])
+                                     (2048, 300, 70, 2), (8, 1, 1, 1), (16384, 100, 2, 4)])
 def test_verify_small(sp, oracle, d, V, N, K):
     rng = np.random.default_rng(d + V + N)
     h = rng.standard_normal((N, d)).astype(np.float16)

@@ -680,3 +680,84 @@ def test_q4_rejects_bad_arguments(oracle):
     s12 = np.ones((q2.shape[0], 4), np.float16)
     with pytest.raises(ValueError):                     # group must be a multiple of 8
         run_q4(oracle, t2, q2, s12, s12, 12)
+
+
+# ---------------------------------------------------------------- full head, verification and tree on the quantised head
+def np_dequant(codes, scales, zeros, group):
+    return f64(scales).repeat(group, axis=1) * (codes.astype(np.float64) - f64(zeros).repeat(group, axis=1))
+
+
+def test_q4_full_head_matches_numpy_matmul_on_dequantised_weights_and_the_predictor_rows(oracle):
+    t, codes, q, scales, zeros, group = q4_case(51, d=96, V=29, K=3, B=5, group=32)
+    full = oracle.lm_head_gemv_q4(t["hidden"], t["gamma"], q, scales, zeros, group)
+    want = np_normed(t["hidden"], t["gamma"], 1e-5) @ np_dequant(codes, scales, zeros, group).T
+    np.testing.assert_allclose(full, want, rtol=1e-11, atol=1e-11)
+    # the reduced logits of the quantised predictor are these logits at the ids (same routine: bit-equal)
+    pred = run_q4(oracle, t, q, scales, zeros, group)
+    assert np.array_equal(pred["logits"], np.take_along_axis(full, t["ids"], axis=1))
+    # weights that fp16 holds exactly: the pinned fp16 head on them
+    rng = np.random.default_rng(2)
+    s2 = (2.0 ** rng.integers(-6, -1, size=scales.shape)).astype(np.float16)
+    w16 = np_dequant(codes, s2, zeros, group).astype(np.float16)
+    assert np.array_equal(f64(w16), np_dequant(codes, s2, zeros, group))
+    np.testing.assert_allclose(oracle.lm_head_gemv_q4(t["hidden"], t["gamma"], q, s2, zeros, group),
+                               oracle.lm_head_gemv(t["hidden"], t["gamma"], w16), rtol=1e-12, atol=1e-12)
+
+
+def test_q4_verification_is_argmax_membership_on_the_dequantised_head(oracle):
+    t, codes, q, scales, zeros, group = q4_case(52, d=64, V=31, K=3, B=12, group=16)
+    want = np_normed(t["hidden"], t["gamma"], 1e-5) @ np_dequant(codes, scales, zeros, group).T
+    am = want.argmax(axis=1)
+    t["ids"][::2, 1] = am[::2]
+    for n in range(1, 12, 2):
+        while am[n] in t["ids"][n]:
+            t["ids"][n] = (t["ids"][n] + 1) % 31
+    v = oracle.verify_q4(t["hidden"], t["gamma"], q, scales, zeros, group, t["ids"])
+    assert np.array_equal(v["token"], am)
+    np.testing.assert_allclose(v["max_logit"], want.max(axis=1), rtol=1e-11, atol=1e-11)
+    assert v["hit"].tolist() == [1, 0] * 6
+    # two identical quantised rows: the lower id wins
+    codes[20] = codes[int(am[0])]
+    scales[20], zeros[20] = scales[int(am[0])], zeros[int(am[0])]
+    q2 = (codes.reshape(31, -1, 8) << (4 * np.arange(8, dtype=np.uint32))).sum(axis=2, dtype=np.uint32)
+    v2 = oracle.verify_q4(t["hidden"][:1], t["gamma"], q2, scales, zeros, group, t["ids"][:1])
+    assert v2["token"][0] == min(20, int(am[0]))
+
+
+def test_q4_tree_equals_independent_quantised_predictors_and_the_fp16_tree_on_representable_weights(oracle):
+    rng = np.random.default_rng(53)
+    d, V, K, H, N, G, group = 64, 23, 3, 16, 9, 2, 16
+    t, codes, q, scales, zeros, _ = q4_case(53, d=d, V=V, K=K, H=H, B=N, group=group)
+    hidden = rng.standard_normal((G, N, d)).astype(np.float16)
+    ids = rng.integers(0, V, size=(G, N, K)).astype(np.int32)
+    prev = rng.dirichlet(np.ones(K), size=(G, N)).astype(np.float32)
+    parent = np.tile(np.array([-1, 0, 0, 1, 1, 2, 3, 3, 5], np.int32), (G, 1))
+    tree = oracle.predict_tree_q4(hidden, t["gamma"], q, scales, zeros, group, ids, prev, t["W1"], t["w2"], t["b1"],
+                                  t["b2"], parent=parent, Mcap=27)
+    for g in range(G):
+        u, inv = np.unique(ids[g], return_inverse=True)
+        assert tree["M"][g] == len(u) and np.array_equal(tree["merged"][g][:len(u)], u)
+        assert np.all(tree["merged"][g][len(u):] == -1) and np.array_equal(tree["cols"][g].ravel(), inv.ravel())
+        one = oracle.predict_q4(hidden[g], t["gamma"], q, scales, zeros, group, ids[g], prev[g], t["W1"], t["w2"],
+                                t["b1"], t["b2"])
+        for k in ("logits", "probs", "scores", "exit"):
+            assert np.array_equal(tree[k][g], one[k]), k
+        for n in range(N):                       # the path rule by walking to the root
+            ok, cur = 1, n
+            while cur >= 0:
+                ok &= int(one["exit"][cur])
+                cur = int(parent[g, cur])
+            assert tree["path_exit"][g, n] == ok
+    assert 0 < tree["exit"].sum() < tree["exit"].size
+    s2 = (2.0 ** rng.integers(-6, -1, size=scales.shape)).astype(np.float16)
+    w16 = np_dequant(codes, s2, zeros, group).astype(np.float16)
+    a = oracle.predict_tree_q4(hidden, t["gamma"], q, s2, zeros, group, ids, prev, t["W1"], t["w2"], t["b1"], t["b2"],
+                               parent=parent, Mcap=27)
+    b = oracle.predict_tree(hidden, t["gamma"], w16, ids, prev, t["W1"], t["w2"], t["b1"], t["b2"], parent=parent,
+                            Mcap=27)
+    np.testing.assert_allclose(a["logits"], b["logits"], rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(a["scores"], b["scores"], rtol=1e-12, atol=1e-12)
+    assert np.array_equal(a["path_exit"], b["path_exit"]) and np.array_equal(a["cols"], b["cols"])
+    with pytest.raises(ValueError):              # merged set larger than the capacity
+        oracle.predict_tree_q4(hidden, t["gamma"], q, scales, zeros, group, ids, prev, t["W1"], t["w2"], parent=parent,
+                               Mcap=3)
