@@ -33,8 +33,24 @@ __host__ __device__ constexpr int merge_lds_ints(int n) {
 // independent LDS reads).
 // own_ids[e] returns the thread's own ids (INT_MAX for slots beyond n) to callers that go on to
 // validate them, which saves reading them a second time.
+// This thread's ids of a tree, element i = tid + e * T: the merges below take them in registers, so that a
+// caller can request them before anything else it loads.  Clamped address, no branch, nothing consumed:
+// slots beyond n hold a copy of the last id and are masked (INT_MAX) by the merges.
 template <int T>
-__device__ inline int merge_block(const int32_t *ids, int n, int32_t *lds, int32_t *&uniq,
+__device__ __forceinline__ void merge_load_ids(const int32_t *ids, int n, int (&kreg)[kMergePerThread]) {
+    const int E = (((n + 3) & ~3) + T - 1) / T;
+#pragma unroll
+    for (int e = 0; e < kMergePerThread; ++e) {
+        kreg[e] = 0x7fffffff;
+        if (e < E) {  // uniform over the workgroup
+            const int i = threadIdx.x + e * T;
+            kreg[e] = ids[min(i, n - 1)];  // raw: masking it here would make the caller wait for it
+        }
+    }
+}
+
+template <int T>
+__device__ inline int merge_block(const int (&kin)[kMergePerThread], int n, int32_t *lds, int32_t *&uniq,
                                   int (&col_of)[kMergePerThread], int (&own_ids)[kMergePerThread]) {
     const int tid = threadIdx.x;
     constexpr int nwaves = T >> 6;
@@ -54,12 +70,9 @@ __device__ inline int merge_block(const int32_t *ids, int n, int32_t *lds, int32
     int kreg[kMergePerThread], rep[kMergePerThread];
 #pragma unroll
     for (int e = 0; e < kMergePerThread; ++e) {
-        kreg[e] = 0x7fffffff;
-        if (e < E) {
-            const int i = tid + e * T;
-            kreg[e] = i < n ? ids[i] : 0x7fffffff;
-            if (i < n4) key[i] = kreg[e];
-        }
+        const int i = tid + e * T;
+        kreg[e] = (e < E && i < n) ? kin[e] : 0x7fffffff;
+        if (e < E && i < n4) key[i] = kreg[e];
     }
     for (unsigned t = tid; t < TS; t += T) table[t] = -1;
     __syncthreads();
@@ -188,8 +201,104 @@ __device__ inline int merge_block(const int32_t *ids, int n, int32_t *lds, int32
 template <int T>
 __device__ inline int merge_block(const int32_t *ids, int n, int32_t *lds, int32_t *&uniq,
                                   int (&col_of)[kMergePerThread]) {
-    int own_ids[kMergePerThread];
-    return merge_block<T>(ids, n, lds, uniq, col_of, own_ids);
+    int kin[kMergePerThread], own_ids[kMergePerThread];
+    merge_load_ids<T>(ids, n, kin);
+    return merge_block<T>(kin, n, lds, uniq, col_of, own_ids);
+}
+
+// The same merge through a bitmap of the vocabulary, for trees whose ids all lie in [0, V) with a
+// vocabulary that fits (V bits and one running count per 32-bit word in LDS): every id sets its bit
+// (one LDS atomic, no probing), a prefix sum over the words' population counts ranks the words, and the
+// column of an id is its word's prefix plus the set bits below it in the word.  Sorted order comes for
+// free, there is no comparison loop, and four barriers do instead of eight -- this merge sits in the
+// prologue of the one-launch tree kernel, where nothing else can run until the rows are known.
+// A tree with an id outside [0, V) takes merge_block (any int32 is a legal key there); the choice is
+// uniform over the workgroup.  Contract as merge_block: all threads call, kin from merge_load_ids, uniq /
+// col_of / own_ids as there; lds needs merge_bitmap_ints(V, n) ints (and merge_lds_ints(n) for the fallback).
+__host__ __device__ constexpr int merge_bitmap_words(int V) {
+    return (V + 31) >> 5;
+}
+__host__ __device__ constexpr int merge_bitmap_ints(int V, int n) {
+    return 2 * merge_bitmap_words(V) + ((n + 3) & ~3) + 16;
+}
+template <int T>
+__device__ inline int merge_bitmap(const int (&kin)[kMergePerThread], int n, int V, int32_t *lds, int32_t *&uniq,
+                                   int (&col_of)[kMergePerThread], int (&own_ids)[kMergePerThread]) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int nwaves = T >> 6;
+    const int W = merge_bitmap_words(V);
+    const int n4 = (n + 3) & ~3;
+    uint32_t *bits = reinterpret_cast<uint32_t *>(lds);   // [W]
+    int32_t *pre = lds + W;                                // [W] set bits in all lower words
+    int32_t *out = lds + 2 * W;                            // [n4] sorted distinct ids
+    int32_t *wtot = lds + 2 * W + n4;                      // [nwaves <= 16]
+    const int E = (n4 + T - 1) / T;
+    int kreg[kMergePerThread];
+    bool bad = false;
+    for (int w = tid; w < W; w += T) bits[w] = 0u;  // before the ids are looked at: they may still be on their way
+#pragma unroll
+    for (int e = 0; e < kMergePerThread; ++e) {
+        const bool live = e < E && tid + e * T < n;
+        kreg[e] = live ? kin[e] : 0x7fffffff;
+        if (live) bad |= kreg[e] < 0 || kreg[e] >= V;
+    }
+    if (__syncthreads_or(bad)) return merge_block<T>(kin, n, lds, uniq, col_of, own_ids);  // uniform
+
+    // 1. every id sets its bit
+#pragma unroll
+    for (int e = 0; e < kMergePerThread; ++e)
+        if (e < E && tid + e * T < n) atomicOr(&bits[kreg[e] >> 5], 1u << (kreg[e] & 31));
+    __syncthreads();
+
+    // 2. thread t owns the words [t * wpt, (t + 1) * wpt): exclusive prefix of their population counts
+    const int wpt = (W + T - 1) / T;
+    const int w0 = tid * wpt;
+    int cnt = 0;
+    for (int j = 0; j < wpt; ++j)
+        if (w0 + j < W) cnt += __popc(bits[w0 + j]);
+    int incl = cnt;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int up = __shfl_up(incl, off, kWave);
+        if (lane >= off) incl += up;
+    }
+    if (lane == 63) wtot[wave] = incl;
+    __syncthreads();
+    int before = incl - cnt, M = 0;
+#pragma unroll
+    for (int q = 0; q < nwaves; ++q) {
+        const int t = wtot[q];
+        if (q < wave) before += t;
+        M += t;
+    }
+
+    // 3. running count per word, and the sorted distinct ids: the set bits in order
+    for (int j = 0; j < wpt; ++j) {
+        const int w = w0 + j;
+        if (w < W) {
+            uint32_t x = bits[w];
+            pre[w] = before;
+            while (x) {
+                const int b = __ffs((int)x) - 1;
+                out[before++] = (w << 5) + b;
+                x &= x - 1;
+            }
+        }
+    }
+    __syncthreads();
+
+    // 4. column of an id: set bits in lower words plus set bits below it in its own word
+#pragma unroll
+    for (int e = 0; e < kMergePerThread; ++e) {
+        col_of[e] = 0;
+        if (e < E && tid + e * T < n) {
+            const int k = kreg[e];
+            col_of[e] = pre[k >> 5] + __popc(bits[k >> 5] & ((1u << (k & 31)) - 1u));
+        }
+        own_ids[e] = kreg[e];
+    }
+    uniq = out;
+    return M;
 }
 
 }  // namespace specee

@@ -34,6 +34,7 @@ namespace specee {
 
 constexpr int kTcFusedMax = kMergePerThread * 256;  // ids per tree when the merge is fused
 constexpr int kWholeWideMaxWgs = 256;               // one 512-thread workgroup per CU
+constexpr int kMergeBitmapMaxV = 65536;               // vocabularies up to here are merged through a bitmap
 constexpr int kGammaLds = 4096;                     // elements of the RMSNorm weight a workgroup may stage in LDS
 // shape of the sixteen-row-tile whole-tree variant: stages in flight, threads, k elements per stage
 constexpr int kWide16Pd = 2, kWide16Threads = 512, kWide16Kch = 128;
@@ -103,7 +104,12 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     const int k_end = min(d, k_begin + p.dslice);
     const int nchunks = (k_end - k_begin + kTcKC - 1) / kTcKC;
 
-    // ---- B side: this lane's node and k-slots; requested before anything else
+    // ---- the tree's ids go out first of all: the rows, the longest chain of the kernel, hang on them, and
+    // behind the hidden-state requests below they would arrive a microsecond or two later
+    int ids_r[kMergePerThread];
+    if (FUSED) merge_load_ids<kTcThreads>(p.ids + (size_t)g * p.N * p.K, p.N * p.K, ids_r);
+
+    // ---- B side: this lane's node and k-slots
     const int node = n0 + nt_w * 16 + c;
     const bool node_ok = node < p.N;
     const half_t *hrow = p.hidden + ((size_t)g * p.N + (node_ok ? node : 0)) * d;
@@ -122,8 +128,13 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     auto b_valid = [&](int kc, int j) {
         return node_ok && k_begin + kc * kTcKC + koff(j) < k_end;
     };
+    // With the merge fused in, the first stages of hidden states are NOT requested here: every workgroup
+    // of the launch would do so at once, and behind that burst the ids -- and with them the merge and the
+    // rows, the chain that decides when the stage loop can start -- come back microseconds later.  They
+    // follow the row requests below.
+    constexpr int PD0 = FUSED ? 0 : PD;
 #pragma unroll
-    for (int u = 0; u < PD; ++u) issue_b(u, u);
+    for (int u = 0; u < PD0; ++u) issue_b(u, u);
     // GL: this thread's share of the slice's RMSNorm weight, parked in LDS after the merge
     constexpr int kGamPt = GL ? kGammaLds / 8 / kTcThreads : 1;
     half8 gam_r[kGamPt];
@@ -149,13 +160,72 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     }
 
     // ---- merged rows
-    int M;
+    int M, Mtrue = 0;
     int32_t *uniq = nullptr;
+    int col_of[kMergePerThread], own_id[kMergePerThread];
     if (FUSED) {
         const int n_ids = p.N * p.K;
-        int col_of[kMergePerThread], own_id[kMergePerThread];
-        const int Mtrue = merge_block<kTcThreads>(p.ids + (size_t)g * n_ids, n_ids, reinterpret_cast<int32_t *>(smem),
-                                                  uniq, col_of, own_id);
+        // through a bitmap of the vocabulary when it fits in the row tile buffers, else by hashing
+        // (a bitmap of a larger vocabulary costs more to clear and to count than the hash table does: measured
+        // equal at 32000 tokens, 3 % behind at 128256)
+        const bool bitmap = p.V <= kMergeBitmapMaxV &&
+                            (size_t)merge_bitmap_ints(p.V, n_ids) * sizeof(int32_t) <=
+                                (kDynLds ? (size_t)2 * ROWS * kTcRow * sizeof(half_t) : sizeof(static_smem));
+        Mtrue = bitmap ? merge_bitmap<kTcThreads>(ids_r, n_ids, p.V, reinterpret_cast<int32_t *>(smem), uniq, col_of,
+                                                  own_id)
+                       : merge_block<kTcThreads>(ids_r, n_ids, reinterpret_cast<int32_t *>(smem), uniq, col_of, own_id);
+        M = Mtrue;
+    } else {
+        M = p.Mptr ? p.Mptr[g] : p.Mcap;
+    }
+    const bool overflow = M > p.Mcap;
+    if (overflow) M = p.Mcap;
+    const int m0 = blockIdx.y * ROWS;
+    if (MODE != 3 && m0 >= M) return;  // uniform over the workgroup
+
+    // ---- A side: this thread copies vectors (row, v) of the row tile: index = tid + 256*i.  The rows are
+    // requested the moment they are known; everything else the merge produced is put away afterwards.
+    const half_t *arow[APT];
+    bool arow_ok[APT];
+    int a_r[APT], a_v[APT];
+#pragma unroll
+    for (int i = 0; i < APT; ++i) {
+        const int vi = tid + kTcThreads * i;
+        a_r[i] = vi / VPR;
+        a_v[i] = vi % VPR;
+        const int m = m0 + a_r[i];
+        arow_ok[i] = m < M;
+        int row = 0;
+        if (arow_ok[i]) {
+            row = FUSED ? uniq[m] : (p.rowlist ? p.rowlist[(size_t)g * p.Mcap + m] : m);
+            if (row < 0 || row >= p.V) row = 0;  // invalid id: the node is reported NaN, nothing is read out of bounds
+        }
+        arow[i] = p.lm_head + (size_t)row * d;
+    }
+    half8 a_buf[PD][APT];
+    // LA (a compile-time constant wrapped in a type): slices of the row tile -- kTcThreads / VPR rows each --
+    // that are loaded and written to LDS.  All of them, except in the sixteen-tile variant, whose stage loop
+    // exists in a few versions for trees that fill less of the capacity (see below); within a version every
+    // load is unconditional, so the compiler's count of outstanding loads stays exact.
+    typedef std::integral_constant<int, APT> all_slices;
+    auto issue_a = [&](int kc, int slot, auto la) {
+#pragma unroll
+        for (int i = 0; i < decltype(la)::value; ++i) {
+            const int ko = min(k_begin + kc * kTcKC + a_v[i] * 8, k_end - 8);
+            a_buf[slot][i] = load_half8(arow[i] + ko);
+        }
+    };
+    auto a_valid = [&](int kc, int i) {
+        return arow_ok[i] && k_begin + kc * kTcKC + a_v[i] * 8 < k_end;
+    };
+#pragma unroll
+    for (int u = 0; u < PD; ++u) {  // in the order the stages need them
+        if (u >= PD0) issue_b(u, u);
+        issue_a(u, u, all_slices{});
+    }
+
+    if (FUSED) {
+        const int n_ids = p.N * p.K;
         if (blockIdx.x == 0 && blockIdx.y == 0 && nb == 0) {
             if (tid == 0) p.M_out[g] = Mtrue;
             for (int m = tid; m < p.Mcap; m += kTcThreads)
@@ -180,32 +250,6 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
                 if (tid + e * kTcThreads < n_ids) prev_lds[tid + e * kTcThreads] = prev_r[e];
             if (f.path_exit && tid < p.N) par_lds[tid] = par_r;
         }
-        M = Mtrue;
-    } else {
-        M = p.Mptr ? p.Mptr[g] : p.Mcap;
-    }
-    const bool overflow = M > p.Mcap;
-    if (overflow) M = p.Mcap;
-    const int m0 = blockIdx.y * ROWS;
-    if (MODE != 3 && m0 >= M) return;  // uniform over the workgroup
-
-    // ---- A side: this thread copies vectors (row, v) of the row tile: index = tid + 256*i
-    const half_t *arow[APT];
-    bool arow_ok[APT];
-    int a_r[APT], a_v[APT];
-#pragma unroll
-    for (int i = 0; i < APT; ++i) {
-        const int vi = tid + kTcThreads * i;
-        a_r[i] = vi / VPR;
-        a_v[i] = vi % VPR;
-        const int m = m0 + a_r[i];
-        arow_ok[i] = m < M;
-        int row = 0;
-        if (arow_ok[i]) {
-            row = FUSED ? uniq[m] : (p.rowlist ? p.rowlist[(size_t)g * p.Mcap + m] : m);
-            if (row < 0 || row >= p.V) row = 0;  // invalid id: the node is reported NaN, nothing is read out of bounds
-        }
-        arow[i] = p.lm_head + (size_t)row * d;
     }
     if (GL) {
         static_assert(!GL || FUSED, "the barrier below publishes the staged weight");
@@ -216,24 +260,6 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
         }
     }
     if (FUSED) __syncthreads();  // the merge scratch becomes the row tile buffers
-    half8 a_buf[PD][APT];
-    // LA (a compile-time constant wrapped in a type): slices of the row tile -- kTcThreads / VPR rows each --
-    // that are loaded and written to LDS.  All of them, except in the sixteen-tile variant, whose stage loop
-    // exists in a few versions for trees that fill less of the capacity (see below); within a version every
-    // load is unconditional, so the compiler's count of outstanding loads stays exact.
-    typedef std::integral_constant<int, APT> all_slices;
-    auto issue_a = [&](int kc, int slot, auto la) {
-#pragma unroll
-        for (int i = 0; i < decltype(la)::value; ++i) {
-            const int ko = min(k_begin + kc * kTcKC + a_v[i] * 8, k_end - 8);
-            a_buf[slot][i] = load_half8(arow[i] + ko);
-        }
-    };
-    auto a_valid = [&](int kc, int i) {
-        return arow_ok[i] && k_begin + kc * kTcKC + a_v[i] * 8 < k_end;
-    };
-#pragma unroll
-    for (int u = 0; u < PD; ++u) issue_a(u, u, all_slices{});
 
     // MODE 3: for the matrix-core MLP the predictor goes to LDS after the contraction, as a padded
     // image in the part of the row-tile buffers that the logits leave free (when it fits).  Up to
