@@ -422,6 +422,25 @@ def main():
             res[f"B={B}"] = {"us_per_launch": us, **spread(reps), "evals_per_s": B / us * 1e6, "algorithmic_bytes": byts,
                              "achieved_GBps": byts / us / 1e3, "frac_of_8TBps": byts / us / 1e3 / HBM_PEAK_GBS}
         extra["q4_predict_7b"] = res
+        # the full head and the verification step on the same quantised head (70 MB instead of 262 MB)
+        hid8 = up(synth.hidden(8, d, 321))
+        out_q = torch.empty((1, V), device=dev)
+        g = capture(lambda: [sp.lm_head_gemv_q4(hid8[i:i + 1], gamma, qd, sd, zd, group, out=out_q) for i in range(8)])
+        us = ev_time(g.replay, 30, 5) * 1e3 / 8
+        head_bytes = V * (row_bytes) + d * 4 + V * 4
+        extra["lm_head_gemv_q4_32000x4096"] = {"us_per_call": us, **spread(8), "algorithmic_bytes": head_bytes,
+                                               "achieved_GBps": head_bytes / us / 1e3,
+                                               "frac_of_8TBps": head_bytes / us / 1e3 / HBM_PEAK_GBS}
+        vids = up(synth.ids_uniform_distinct(1, K, V, 5))
+        vo_q = sp.verify_q4(hid8[:1], gamma, qd, sd, zd, group, vids)
+        vws_q = torch.empty(sp.workspace_bytes(sp.OP_VERIFY_Q4, sp.Dims(d, V, K, 1, 1e-5, 0.5), 1), dtype=torch.uint8,
+                            device=dev)
+        g = capture(lambda: [sp.verify_q4(hid8[i:i + 1], gamma, qd, sd, zd, group, vids, out=vo_q, workspace=vws_q)
+                             for i in range(8)])
+        us = ev_time(g.replay, 30, 5) * 1e3 / 8
+        extra["specee_verify_q4_32000x4096"] = {"us_per_call": us, **spread(8),
+                                                "achieved_GBps": V * row_bytes / us / 1e3,
+                                                "frac_of_8TBps": V * row_bytes / us / 1e3 / HBM_PEAK_GBS}
         del qd, sd, zd
 
     # ------------------------------------------------------------------ layer loop with device-side control (one token)

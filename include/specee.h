@@ -83,7 +83,9 @@ typedef enum specee_op {
     SPECEE_OP_PREDICT_TREE = 2,
     SPECEE_OP_LM_HEAD = 3,
     SPECEE_OP_VERIFY = 4,
-    SPECEE_OP_LAYER_LOOP = 5
+    SPECEE_OP_LAYER_LOOP = 5,
+    SPECEE_OP_VERIFY_Q4 = 6,
+    SPECEE_OP_PREDICT_TREE_Q4 = 7
 } specee_op;
 
 /*
@@ -225,6 +227,29 @@ int specee_verify(const specee_dims *dims, int N, const specee_half *hidden, con
                   const specee_half *lm_head, const int32_t *ids, const int32_t *gate /* [N] or NULL */,
                   int32_t *done /* [N] or NULL */, int32_t *token, float *max_logit, int32_t *hit, void *workspace,
                   size_t workspace_bytes, void *stream);
+
+/*
+ * lm_head_gemv and specee_verify on the 4-bit group-quantised LM head of
+ * specee_predict_q4 (same format, same reading): the weight-quantised setting of
+ * the paper's cloud evaluation runs the whole predict -> verify loop on the
+ * quantised model (Sec. 7.1 "Quantization", Sec. 7.3).  Every LM-head row is
+ * scale * (code - zero) per group; nothing else changes, and the dequantised
+ * weights are never formed or rounded.  One pass over the head per hidden state
+ * (d/2 + 4*d/group bytes per row).
+ *   lm_head_gemv_q4: out [N][V] fp32.  Needs no workspace.
+ *   specee_verify_q4: arguments and outputs as specee_verify (gate, done, token,
+ *   max_logit, hit).  Workspace: SPECEE_OP_VERIFY_Q4 with n = N.
+ * group: a multiple of 8 that divides d; qweight 4-byte aligned (16-byte aligned
+ * rows and group % 32 == 0 take the faster path).
+ */
+int lm_head_gemv_q4(const specee_dims *dims, int N, const specee_half *hidden, const specee_half *gamma,
+                    const uint32_t *qweight, const specee_half *scales, const specee_half *zeros, int group,
+                    float *out, void *stream);
+int specee_verify_q4(const specee_dims *dims, int N, const specee_half *hidden, const specee_half *gamma,
+                     const uint32_t *qweight, const specee_half *scales, const specee_half *zeros, int group,
+                     const int32_t *ids, const int32_t *gate /* [N] or NULL */, int32_t *done /* [N] or NULL */,
+                     int32_t *token, float *max_logit, int32_t *hit, void *workspace, size_t workspace_bytes,
+                     void *stream);
 
 /*
  * The early-exit decode loop of B tokens down L layers in one launch (Sec. 4.3.3:

@@ -135,4 +135,15 @@ hipError_t launch_verify_finish(const float *best_val, const int32_t *best_idx, 
                                 int K, const int32_t *gate, int32_t *done, int32_t *token, float *max_logit,
                                 int32_t *hit, hipStream_t s);
 
+// Full-vocabulary head on a 4-bit group-quantised head (lm_head_q4_kernels.hip): all logits, or arg-max
+// candidates per workgroup for verification (combined by launch_verify_finish)
+int lm_head_q4_workgroups(int V);
+hipError_t launch_lm_head_q4(int d, int V, float eps, int N, const half_t *hidden, const half_t *gamma,
+                             const uint32_t *qweight, const half_t *scales, const half_t *zeros, int group,
+                             float *out, hipStream_t s);
+hipError_t launch_lm_head_q4_argmax(int d, int V, float eps, int N, const half_t *hidden, const half_t *gamma,
+                                    const uint32_t *qweight, const half_t *scales, const half_t *zeros, int group,
+                                    float *best_val, int32_t *best_idx, const int32_t *gate, const int32_t *done,
+                                    hipStream_t s);
+
 }  // namespace specee

@@ -173,6 +173,9 @@ size_t specee_workspace_bytes(int op, const specee_dims *dm, int n, int Mcap) {
             int P = n <= 2 ? lm_head_gemv_workgroups(dm->V) : lm_head_gemm_workgroups(dm->V);
             return 2 * align256((size_t)n * P * sizeof(float));
         }
+        case SPECEE_OP_VERIFY_Q4:
+            if (check_dims(dm, false)) return (size_t)-1;
+            return 2 * align256((size_t)n * lm_head_q4_workgroups(dm->V) * sizeof(float));
         case SPECEE_OP_LAYER_LOOP:
             if (check_dims(dm, true) || n > kLoopMaxTokens) return (size_t)-1;
             return loop_layout(n).total;
@@ -416,6 +419,58 @@ int specee_predict_tree_static(const specee_dims *dm, int G, int N, int Mcap, co
                                       M_out, cols, logits, probs, scores, exit_flags, path_exit, base,
                                       SPECEE_STATIC_SCRATCH_BYTES, true, stream);
     return r == SPECEE_EWORKSPACE ? SPECEE_ESCRATCH : r;
+}
+
+static int check_q4(const specee_dims *dm, const uint32_t *qweight, const specee_half *scales,
+                    const specee_half *zeros, int group) {
+    if (group < 8 || group % 8 != 0 || dm->d % group != 0) return SPECEE_EINVAL;
+    if (!qweight || !scales || !zeros) return SPECEE_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(qweight) & 3) != 0) return SPECEE_EALIGN;
+    return SPECEE_OK;
+}
+
+int lm_head_gemv_q4(const specee_dims *dm, int N, const specee_half *hidden, const specee_half *gamma,
+                    const uint32_t *qweight, const specee_half *scales, const specee_half *zeros, int group,
+                    float *out, void *stream) {
+    int rc = check_dims(dm, false);
+    if (rc) return rc;
+    if (N < 0 || N > 65535) return SPECEE_EINVAL;
+    if (group < 8 || group % 8 != 0 || dm->d % group != 0) return SPECEE_EINVAL;
+    if (N == 0) return SPECEE_OK;
+    if ((rc = check_q4(dm, qweight, scales, zeros, group))) return rc;
+    if (!hidden || !gamma || !out) return SPECEE_EINVAL;
+    if (misaligned(hidden) || misaligned(gamma)) return SPECEE_EALIGN;
+    return launch_lm_head_q4(dm->d, dm->V, dm->eps, N, H(hidden), H(gamma), qweight, H(scales), H(zeros), group, out,
+                             static_cast<hipStream_t>(stream)) == hipSuccess
+               ? SPECEE_OK
+               : SPECEE_EHIP;
+}
+
+int specee_verify_q4(const specee_dims *dm, int N, const specee_half *hidden, const specee_half *gamma,
+                     const uint32_t *qweight, const specee_half *scales, const specee_half *zeros, int group,
+                     const int32_t *ids, const int32_t *gate, int32_t *done, int32_t *token, float *max_logit,
+                     int32_t *hit, void *workspace, size_t workspace_bytes, void *stream) {
+    int rc = check_dims(dm, false);
+    if (rc) return rc;
+    if (N < 0 || N > 65535 || dm->K < 1 || dm->K > SPECEE_KMAX) return SPECEE_EINVAL;
+    if (group < 8 || group % 8 != 0 || dm->d % group != 0) return SPECEE_EINVAL;
+    if (N == 0) return SPECEE_OK;
+    if ((rc = check_q4(dm, qweight, scales, zeros, group))) return rc;
+    if (!hidden || !gamma || !ids || !token || !max_logit || !hit) return SPECEE_EINVAL;
+    if (misaligned(hidden) || misaligned(gamma) || misaligned(workspace)) return SPECEE_EALIGN;
+    const int P = lm_head_q4_workgroups(dm->V);
+    const size_t half_ws = align256((size_t)N * P * sizeof(float));
+    if (!workspace || workspace_bytes < 2 * half_ws) return SPECEE_EWORKSPACE;
+    float *best_val = static_cast<float *>(workspace);
+    int32_t *best_idx = reinterpret_cast<int32_t *>(static_cast<char *>(workspace) + half_ws);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (launch_lm_head_q4_argmax(dm->d, dm->V, dm->eps, N, H(hidden), H(gamma), qweight, H(scales), H(zeros), group,
+                                 best_val, best_idx, gate, done, st) != hipSuccess)
+        return SPECEE_EHIP;
+    return launch_verify_finish(best_val, best_idx, P, N, ids, dm->K, gate, done, token, max_logit, hit, st) ==
+                   hipSuccess
+               ? SPECEE_OK
+               : SPECEE_EHIP;
 }
 
 int specee_layer_loop(const specee_dims *dm, int L, int B, const specee_half *hidden, const specee_half *gamma,

@@ -15,7 +15,8 @@ _PKG = Path(__file__).resolve().parent
 LIB_PATH = _PKG / "libspecee.so"
 _lib = None
 
-OP_PREDICT, OP_PREDICT_SWEEP, OP_PREDICT_TREE, OP_LM_HEAD, OP_VERIFY, OP_LAYER_LOOP = range(6)
+OP_PREDICT, OP_PREDICT_SWEEP, OP_PREDICT_TREE, OP_LM_HEAD, OP_VERIFY, OP_LAYER_LOOP, OP_VERIFY_Q4, \
+    OP_PREDICT_TREE_Q4 = range(8)
 
 
 class SpeceeError(RuntimeError):
@@ -308,6 +309,52 @@ def verify(hidden, gamma, lm_head, ids, gate=None, eps=1e-5, out=None, workspace
                              _ptr(workspace), wbytes, _stream(stream))
     if rc:
         raise SpeceeError("specee_verify", rc)
+    return out
+
+
+def _q4_args(qweight, scales, zeros, group, d):
+    V = qweight.shape[0]
+    assert qweight.shape == (V, d // 8) and qweight.dtype == torch.int32, "codes travel as int32 words"
+    assert scales.shape == (V, d // group) and zeros.shape == scales.shape
+    f16 = torch.float16
+    return V, (_ptr(qweight, torch.int32), _ptr(scales, f16), _ptr(zeros, f16), C.c_int(group))
+
+
+def lm_head_gemv_q4(hidden, gamma, qweight, scales, zeros, group, eps=1e-5, out=None, stream=None):
+    """lm_head_gemv_q4: out [N][V] against the 4-bit group-quantised head."""
+    N, d = hidden.shape
+    V, q = _q4_args(qweight, scales, zeros, group, d)
+    if out is None:
+        out = torch.empty((N, V), dtype=torch.float32, device=hidden.device)
+    dims = _dims(d, V, 1, 1, eps, 0.5)
+    f16 = torch.float16
+    rc = lib().lm_head_gemv_q4(C.byref(dims), C.c_int(N), _ptr(hidden, f16), _ptr(gamma, f16), *q,
+                               _ptr(out, torch.float32), _stream(stream))
+    if rc:
+        raise SpeceeError("lm_head_gemv_q4", rc)
+    return out
+
+
+def verify_q4(hidden, gamma, qweight, scales, zeros, group, ids, gate=None, eps=1e-5, out=None, workspace=None,
+              stream=None, done=None):
+    """specee_verify_q4: specee_verify against the 4-bit group-quantised head."""
+    N, d = hidden.shape
+    V, q = _q4_args(qweight, scales, zeros, group, d)
+    K = ids.shape[1]
+    dev = hidden.device
+    if out is None:
+        out = dict(token=torch.empty((N,), dtype=torch.int32, device=dev),
+                   max_logit=torch.empty((N,), dtype=torch.float32, device=dev),
+                   hit=torch.empty((N,), dtype=torch.int32, device=dev))
+    dims = _dims(d, V, K, 1, eps, 0.5)
+    workspace, wbytes = _workspace(OP_VERIFY_Q4, dims, N, 0, workspace, dev)
+    f16 = torch.float16
+    rc = lib().specee_verify_q4(C.byref(dims), C.c_int(N), _ptr(hidden, f16), _ptr(gamma, f16), *q,
+                                _ptr(ids, torch.int32), _ptr(gate, torch.int32), _ptr(done, torch.int32),
+                                _ptr(out["token"]), _ptr(out["max_logit"]), _ptr(out["hit"]), _ptr(workspace), wbytes,
+                                _stream(stream))
+    if rc:
+        raise SpeceeError("specee_verify_q4", rc)
     return out
 
 
