@@ -441,6 +441,24 @@ def main():
         extra["specee_verify_q4_32000x4096"] = {"us_per_call": us, **spread(8),
                                                 "achieved_GBps": V * row_bytes / us / 1e3,
                                                 "frac_of_8TBps": V * row_bytes / us / 1e3 / HBM_PEAK_GBS}
+        # token trees on the quantised head: 256 trees of the 60-node shape per launch, one workgroup per tree
+        c3 = synth.CONFIGS["C3"]
+        Gq = 256
+        tq = [synth.make("C3", seed=3000 + i, lm=np.zeros((1, 1), np.float16)) for i in range(Gq)]
+        ids_hq = np.stack([t["ids"] for t in tq])
+        tw1q, tw2q = up(tq[0]["W1"]), up(tq[0]["w2"])
+        prevq, parq = up(np.stack([t["prev_probs"] for t in tq])), up(np.stack([t["parent"] for t in tq]))
+        hq = [torch.randn((Gq, c3.N, d), device=dev, dtype=torch.float16) for _ in range(4)]
+        iq = [((up(ids_hq) + 7919 * r) % V).to(torch.int32) for r in range(4)]
+        oq = sp.predict_tree_q4(hq[0], gamma, qd, sd, zd, group, iq[0], prevq, tw1q, tw2q, parent=parq, Mcap=c3.Mcap)
+        g = capture(lambda: [sp.predict_tree_q4(hq[r], gamma, qd, sd, zd, group, iq[r], prevq, tw1q, tw2q, parent=parq,
+                                                Mcap=c3.Mcap, out=oq) for r in range(4)])
+        us = ev_time(g.replay, 20, 3) * 1e3 / 4
+        bq = Gq * c3.N * d * 2 + sum(len(np.unique(x)) for x in ids_hq) * row_bytes + d * 2 + (3 * K * H + H) * 2
+        extra["q4_tree_batch_G256"] = {"us_per_launch": us, **spread(4), "node_evals_per_s": Gq * c3.N / us * 1e6,
+                                       "bytes_with_rows_counted_per_tree": bq,
+                                       "frac_of_8TBps_rows_per_tree": bq / us / 1e3 / HBM_PEAK_GBS}
+        del hq, iq
         del qd, sd, zd
 
     # ------------------------------------------------------------------ layer loop with device-side control (one token)

@@ -252,6 +252,26 @@ int specee_verify_q4(const specee_dims *dims, int N, const specee_half *hidden, 
                      void *stream);
 
 /*
+ * specee_predict_tree on the 4-bit group-quantised LM head (Sec. 6.2 in the
+ * quantised setting of Sec. 7.1 / 7.3): arguments, outputs and conventions as
+ * specee_predict_tree, the head given as for specee_predict_q4.  The merged
+ * contraction runs on the codes themselves (exact), each quantisation group's
+ * sums being scaled and shifted by that group's scale and zero-point.
+ * One workgroup per tree, so the call is meant for batches of trees; a single
+ * tree is correct but takes one CU's time.  Needs no workspace.
+ * Limits: N <= 64, N*K <= 1024, Mcap <= 128, group a multiple of 32 that divides
+ * d, qweight 8-byte aligned; d and group such that the staged scales and
+ * zero-points fit in LDS (d / group <= 128 at Mcap <= 64).  Other shapes return
+ * SPECEE_EINVAL.
+ */
+int specee_predict_tree_q4(const specee_dims *dims, int G, int N, int Mcap, const specee_half *hidden,
+                           const specee_half *gamma, const uint32_t *qweight, const specee_half *scales,
+                           const specee_half *zeros, int group, const int32_t *ids, const int32_t *parent,
+                           const float *prev_probs, const specee_mlp *mlp /* HOST */, int32_t *merged_ids,
+                           int32_t *M_out, int32_t *cols, float *logits, float *probs, float *scores,
+                           int32_t *exit_flags, int32_t *path_exit, void *stream);
+
+/*
  * The early-exit decode loop of B tokens down L layers in one launch (Sec. 4.3.3:
  * a positive prediction is followed by verification, and the token leaves the
  * model at the first layer whose verification accepts a speculative token;

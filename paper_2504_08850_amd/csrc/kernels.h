@@ -135,6 +135,22 @@ hipError_t launch_verify_finish(const float *best_val, const int32_t *best_idx, 
                                 int K, const int32_t *gate, int32_t *done, int32_t *token, float *max_logit,
                                 int32_t *hit, hipStream_t s);
 
+// Token trees on a 4-bit group-quantised head, one workgroup per tree (tree_q4.hip)
+struct TreeQ4Params {
+    int d, V, N, K, Mcap, group;
+    float eps;
+    const half_t *hidden;     // [G][N][d]
+    const half_t *gamma;      // [d]
+    const uint32_t *qweight;  // [V][d/8]
+    const half_t *qscales;    // [V][d/group]
+    const half_t *qzeros;     // [V][d/group]
+    const int32_t *ids;       // [G][N][K]
+    int32_t *merged_out, *M_out, *cols_out;
+};
+bool tree_q4_supported(int d, int N, int K, int Mcap, int group);
+size_t tree_q4_lds_bytes(int d, int Mcap, int group);
+hipError_t launch_tree_q4(const TreeQ4Params &p, const TreeFinishParams &f, int G, hipStream_t st);
+
 // Full-vocabulary head on a 4-bit group-quantised head (lm_head_q4_kernels.hip): all logits, or arg-max
 // candidates per workgroup for verification (combined by launch_verify_finish)
 int lm_head_q4_workgroups(int V);

@@ -173,6 +173,8 @@ size_t specee_workspace_bytes(int op, const specee_dims *dm, int n, int Mcap) {
             int P = n <= 2 ? lm_head_gemv_workgroups(dm->V) : lm_head_gemm_workgroups(dm->V);
             return 2 * align256((size_t)n * P * sizeof(float));
         }
+        case SPECEE_OP_PREDICT_TREE_Q4:
+            return check_dims(dm, true) ? (size_t)-1 : 0;
         case SPECEE_OP_VERIFY_Q4:
             if (check_dims(dm, false)) return (size_t)-1;
             return 2 * align256((size_t)n * lm_head_q4_workgroups(dm->V) * sizeof(float));
@@ -471,6 +473,35 @@ int specee_verify_q4(const specee_dims *dm, int N, const specee_half *hidden, co
                    hipSuccess
                ? SPECEE_OK
                : SPECEE_EHIP;
+}
+
+int specee_predict_tree_q4(const specee_dims *dm, int G, int N, int Mcap, const specee_half *hidden,
+                           const specee_half *gamma, const uint32_t *qweight, const specee_half *scales,
+                           const specee_half *zeros, int group, const int32_t *ids, const int32_t *parent,
+                           const float *prev_probs, const specee_mlp *mlp, int32_t *merged_ids, int32_t *M_out,
+                           int32_t *cols, float *logits, float *probs, float *scores, int32_t *exit_flags,
+                           int32_t *path_exit, void *stream) {
+    // the head pointer of the fp16 entry point is not used here: any aligned non-null value passes its check
+    int rc = check_tree_args(dm, G, N, Mcap, hidden, gamma, reinterpret_cast<const specee_half *>(gamma), ids, parent,
+                             prev_probs, mlp, merged_ids, M_out, cols, logits, probs, scores, exit_flags, path_exit);
+    if (rc) return rc;
+    if (group < 8 || group % 8 != 0 || dm->d % group != 0) return SPECEE_EINVAL;
+    if (G == 0) return SPECEE_OK;
+    if ((rc = check_q4(dm, qweight, scales, zeros, group))) return rc;
+    if ((reinterpret_cast<uintptr_t>(qweight) & 7) != 0) return SPECEE_EALIGN;
+    if (!tree_q4_supported(dm->d, N, dm->K, Mcap, group)) return SPECEE_EINVAL;
+    TreeQ4Params tp{};
+    tp.d = dm->d; tp.V = dm->V; tp.N = N; tp.K = dm->K; tp.Mcap = Mcap; tp.group = group; tp.eps = dm->eps;
+    tp.hidden = H(hidden); tp.gamma = H(gamma); tp.qweight = qweight; tp.qscales = H(scales); tp.qzeros = H(zeros);
+    tp.ids = ids; tp.merged_out = merged_ids; tp.M_out = M_out; tp.cols_out = cols;
+    TreeFinishParams fp{};
+    fp.d = dm->d; fp.V = dm->V; fp.K = dm->K; fp.H = dm->H; fp.N = N; fp.Mcap = Mcap;
+    fp.eps = dm->eps; fp.threshold = dm->threshold;
+    fp.prev = prev_probs;
+    fp.W1 = H(mlp->W1); fp.b1 = H(mlp->b1); fp.w2 = H(mlp->w2); fp.b2 = H(mlp->b2);
+    fp.logits = logits; fp.probs = probs; fp.scores = scores; fp.exit_flags = exit_flags;
+    fp.parent = parent; fp.path_exit = path_exit;
+    return launch_tree_q4(tp, fp, G, static_cast<hipStream_t>(stream)) == hipSuccess ? SPECEE_OK : SPECEE_EHIP;
 }
 
 int specee_layer_loop(const specee_dims *dm, int L, int B, const specee_half *hidden, const specee_half *gamma,

@@ -1,0 +1,322 @@
+// Token trees under the merged mapping (paper Sec. 6.2) on a 4-bit group-quantised LM head (the
+// weight-quantised setting of Sec. 7.1 / 7.3; format as for the quantised-rows predictor): one workgroup
+// per tree does the merge, the N x M x d contraction on the matrix cores, the per-node features, MLP and
+// judgment, and the path rule.
+//
+// The contraction never forms a dequantised weight.  With x = h * gamma split exactly into hi + lo (fp16),
+//     Z[n][m] = sum_g scale[m][g] * ( sum_{i in g} x[n][i] * code[m][i]  -  zero[m][g] * sum_{i in g} x[n][i] ):
+// the inner sum runs on v_mfma_f32_16x16x32_f16 with the CODES as the A operand -- integers 0..15, exact
+// in fp16 -- into a per-group accumulator; at the end of a group every lane folds its four rows' sums into
+// the running logits with that group's scale and zero-point (two FMAs per row) and starts over.  The
+// group sums of x come from the same registers the B operand is built from.  A merged row is d/2 bytes of
+// codes, so a tree reads its hidden states (N * 2d bytes) and an eighth as many row bytes as on the fp16
+// head; the rows' scales and zero-points (4 * d / group bytes each) are staged in LDS once.
+//
+// Layout per 128-element stage: the row tile [16 * MT rows][128] is expanded from codes to fp16 in
+// registers (0x6400 | c is the half 1024 + c) and written to double-buffered LDS; k-step j of a stage
+// covers elements 32j .. 32j+31 (lane group q takes 8 consecutive ones), so a quantisation group --
+// a multiple of 32 elements -- ends on a k-step boundary.  Within a k-step the eight elements of a lane
+// sit in the order (0,4,1,5,2,6,3,7) on both operands (any order is valid if A and B agree), which is
+// the order the nibble pairs come out of a 32-bit word.
+#include "device_utils.h"
+#include "kernels.h"
+#include "merge_block.h"
+#include "tree_finish.h"
+
+namespace specee {
+
+constexpr int kTq4Threads = 256;
+constexpr int kTq4Waves = kTq4Threads / kWave;
+constexpr int kTq4Kch = 128;                        // elements per stage
+constexpr int kTq4Row = kTq4Kch + 8;                // halves per LDS row
+constexpr int kTq4MaxIds = kMergePerThread * kTq4Threads;
+
+// eight codes of a word as halves, in the order (0,4,1,5,2,6,3,7)
+__device__ __forceinline__ half8 codes_to_half8(uint32_t w) {
+    half8 out;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const uint32_t bits = ((w >> (4 * p)) & 0x000f000fu) | 0x64006400u;  // nibbles p and p + 4
+        const half2_t v = __builtin_bit_cast(half2_t, bits) - half2_t{(half_t)1024.f, (half_t)1024.f};
+        out[2 * p] = v[0];
+        out[2 * p + 1] = v[1];
+    }
+    return out;
+}
+
+// MT: row tiles of 16 merged rows (Mcap <= 16 * MT).  KC: as in the other predictor kernels.
+template <int MT, int KC>
+__global__ __launch_bounds__(kTq4Threads) void tree_q4_kernel(TreeQ4Params p, TreeFinishParams f) {
+    constexpr int ROWS = 16 * MT;
+    constexpr int JN = kTq4Kch / 32;                      // k-steps per stage
+    constexpr int CPT = ROWS * (kTq4Kch / 16) / kTq4Threads;  // 8-byte code chunks (16 elements) per thread per stage
+    extern __shared__ __attribute__((aligned(16))) half_t q4_smem[];
+    // dynamic LDS: row tiles [2][ROWS][kTq4Row] halves | scales [ng][ROWS] halves | zero-points [ng][ROWS] halves
+    typedef half_t (*tile_t)[ROWS][kTq4Row];
+    tile_t a_lds = reinterpret_cast<tile_t>(q4_smem);
+    const int ng = p.d / p.group;
+    half_t *sc_lds = q4_smem + 2 * ROWS * kTq4Row;
+    half_t *zp_lds = sc_lds + (size_t)ng * ROWS;
+    __shared__ int32_t cols_lds[kTq4MaxIds];
+    __shared__ float prev_lds[kTq4MaxIds];
+    __shared__ float ssq_lds[64];
+    __shared__ int32_t bad_lds[64];
+    __shared__ int32_t exit_lds[64];
+    __shared__ int32_t par_lds[64];
+    static_assert(sizeof(half_t) * 2 * ROWS * kTq4Row >= sizeof(int32_t) * merge_lds_ints(kTq4MaxIds),
+                  "merge scratch must fit in the row tile buffers");
+    static_assert(sizeof(half_t) * 2 * ROWS * kTq4Row >= sizeof(float) * 64 * ROWS, "the logits must fit");
+    static_assert(CPT >= 1, "at least one chunk per thread");
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, q = lane >> 4;
+    const int g = blockIdx.x;
+    const int d = p.d, N = p.N, K = p.K, n_ids = N * K;
+    const int nchunks = (d + kTq4Kch - 1) / kTq4Kch;
+
+    // ---- the ids first; then what does not depend on them
+    int ids_r[kMergePerThread];
+    merge_load_ids<kTq4Threads>(p.ids + (size_t)g * n_ids, n_ids, ids_r);
+    const int node = wave * 16 + c;
+    const bool node_ok = node < N;
+    const half_t *hrow = p.hidden + ((size_t)g * N + (node_ok ? node : 0)) * d;
+    float prev_r[kMergePerThread];
+#pragma unroll
+    for (int e = 0; e < kMergePerThread; ++e)
+        prev_r[e] = f.prev[(size_t)g * n_ids + min(tid + e * kTq4Threads, n_ids - 1)];
+    const int32_t *pp = f.path_exit ? f.parent + (size_t)g * N + min(tid, N - 1) : p.ids;
+    const int par_r = *pp;
+    if (tid < 64) bad_lds[tid] = 0;
+
+    // ---- merge
+    int32_t *uniq = nullptr;
+    int col_of[kMergePerThread], own_id[kMergePerThread];
+    const bool bitmap = p.V <= 65536 && (size_t)merge_bitmap_ints(p.V, n_ids) * sizeof(int32_t) <=
+                                            sizeof(half_t) * 2 * ROWS * kTq4Row;
+    const int Mtrue = bitmap ? merge_bitmap<kTq4Threads>(ids_r, n_ids, p.V, reinterpret_cast<int32_t *>(q4_smem), uniq,
+                                                         col_of, own_id)
+                             : merge_block<kTq4Threads>(ids_r, n_ids, reinterpret_cast<int32_t *>(q4_smem), uniq,
+                                                        col_of, own_id);
+    const bool overflow = Mtrue > p.Mcap;
+    const int M = overflow ? p.Mcap : Mtrue;
+
+    // ---- the rows' codes are requested the moment the rows are known: chunk (row, v) = tid + 256 * i
+    const uint32_t *crow[CPT];
+    bool crow_ok[CPT];
+    int c_r[CPT], c_v[CPT];
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+        const int ci = tid + kTq4Threads * i;
+        c_r[i] = ci / (kTq4Kch / 16);
+        c_v[i] = ci % (kTq4Kch / 16);
+        crow_ok[i] = c_r[i] < M;
+        int row = crow_ok[i] ? uniq[c_r[i]] : 0;
+        if (row < 0 || row >= p.V) row = 0;  // invalid id: the node is reported NaN, nothing is read out of bounds
+        crow[i] = p.qweight + (size_t)row * (d >> 3);
+    }
+    constexpr int PD = 2;
+    uint2 a_buf[PD][CPT];
+    half8 h_buf[PD][JN], g_buf[PD][JN];
+    auto issue = [&](int kc, int slot) {  // unconditional, clamped into the row; masked when consumed
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) {
+            const int ko = min(kc * kTq4Kch + c_v[i] * 16, d - 16);
+            a_buf[slot][i] = *reinterpret_cast<const uint2 *>(crow[i] + (ko >> 3));
+        }
+#pragma unroll
+        for (int j = 0; j < JN; ++j) {
+            const int ko = min(kc * kTq4Kch + 32 * j + 8 * q, d - 8);
+            g_buf[slot][j] = load_half8(p.gamma + ko);
+            h_buf[slot][j] = load_half8(hrow + ko);
+        }
+    };
+#pragma unroll
+    for (int u = 0; u < PD; ++u) issue(u, u);
+
+    // ---- publish the merge, park what the scoring phase needs, stage the rows' scales and zero-points
+    if (tid == 0) p.M_out[g] = Mtrue;
+    for (int m = tid; m < p.Mcap; m += kTq4Threads) p.merged_out[(size_t)g * p.Mcap + m] = m < Mtrue ? uniq[m] : -1;
+#pragma unroll
+    for (int e = 0; e < kMergePerThread; ++e) {
+        const int i = tid + e * kTq4Threads;
+        if (i < n_ids) {
+            p.cols_out[(size_t)g * n_ids + i] = col_of[e];
+            cols_lds[i] = col_of[e];
+            prev_lds[i] = prev_r[e];
+            if (own_id[e] < 0 || own_id[e] >= p.V) bad_lds[i / K] = 1;  // benign race: all writers store 1
+        }
+    }
+    if (f.path_exit && tid < N) par_lds[tid] = par_r;
+    for (int i = tid; i < ROWS * ng; i += kTq4Threads) {
+        const int m = i / ng, gi = i - m * ng;
+        int row = m < M ? uniq[m] : 0;
+        if (row < 0 || row >= p.V) row = 0;
+        sc_lds[(size_t)gi * ROWS + m] = m < M ? p.qscales[(size_t)row * ng + gi] : (half_t)0.f;
+        zp_lds[(size_t)gi * ROWS + m] = m < M ? p.qzeros[(size_t)row * ng + gi] : (half_t)0.f;
+    }
+    __syncthreads();  // the merge scratch becomes the row tile buffers; scales and zero-points are in place
+
+    floatx4 acc[MT], tmp[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = tmp[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    float ssq = 0.f, xs = 0.f;
+
+    // the row tile of stage kc from the prefetched codes: 16 elements per chunk, two 16-byte LDS writes
+    auto tile_to_lds = [&](int kc, int slot, int b) {
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) {
+            const bool in = crow_ok[i] && kc * kTq4Kch + c_v[i] * 16 < d;
+            const half8 lo = codes_to_half8(a_buf[slot][i].x), hi = codes_to_half8(a_buf[slot][i].y);
+            *reinterpret_cast<half8 *>(&a_lds[b][c_r[i]][c_v[i] * 16]) = in ? lo : zero_half8();
+            *reinterpret_cast<half8 *>(&a_lds[b][c_r[i]][c_v[i] * 16 + 8]) = in ? hi : zero_half8();
+        }
+    };
+    // x = h * gamma of this lane's node, k-step j of stage kc, split exactly into hi + lo, elements in the
+    // order (0,4,1,5,2,6,3,7); also the lane's share of the sum of squares, and of the sum of x over this
+    // k-step (xsum; it joins the group sum when the k-step is multiplied)
+    auto build_b = [&](int kc, int slot, int j, half8 &hi, half8 &lo, float &xsum) {
+        const bool in = node_ok && kc * kTq4Kch + 32 * j + 8 * q < d;
+        const half8 hsel = in ? h_buf[slot][j] : zero_half8();
+        const half8 gvec = g_buf[slot][j];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const half2_t hh = {hsel[e], hsel[e + 4]};
+            const half2_t gg = {gvec[e], gvec[e + 4]};
+            const half2_t x = hh * gg;
+            const half2_t rres = __builtin_elementwise_fma(hh, gg, -x);
+            ssq = __builtin_amdgcn_fdot2(hh, hh, ssq, false);
+            xsum += ((float)x[0] + (float)rres[0]) + ((float)x[1] + (float)rres[1]);
+            hi[2 * e] = x[0];
+            hi[2 * e + 1] = x[1];
+            lo[2 * e] = rres[0];
+            lo[2 * e + 1] = rres[1];
+        }
+    };
+    // end of a quantisation group: acc += scale * (tmp - zero * sum of x over the group), row by row
+    auto fold = [&](int gi) {
+        float t = xs;
+        t += __shfl_xor(t, 16, kWave);
+        t += __shfl_xor(t, 32, kWave);  // the four lane groups of node c hold disjoint elements
+        const half_t *scp = sc_lds + (size_t)gi * ROWS + 4 * q;
+        const half_t *zpp = zp_lds + (size_t)gi * ROWS + 4 * q;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const half4 s4 = *reinterpret_cast<const half4 *>(scp + 16 * mt);
+            const half4 z4 = *reinterpret_cast<const half4 *>(zpp + 16 * mt);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[mt][r] += (float)s4[r] * (tmp[mt][r] - (float)z4[r] * t);
+            tmp[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+        }
+        xs = 0.f;
+    };
+
+    const int ksteps_per_group = p.group >> 5;
+    int steps_in_group = 0, gi = 0;
+    const int nstages = ((nchunks + PD - 1) / PD) * PD;
+    int buf = 0;
+    for (int kc0 = 0; kc0 < nstages; kc0 += PD) {
+#pragma unroll
+        for (int u = 0; u < PD; ++u) {
+            const int kc = kc0 + u;
+            half8 bhi[JN], blo[JN];
+            float xstep[JN];
+            tile_to_lds(kc, u, buf);
+#pragma unroll
+            for (int j = 0; j < JN; ++j) {
+                xstep[j] = 0.f;
+                build_b(kc, u, j, bhi[j], blo[j], xstep[j]);
+            }
+            __syncthreads();
+            issue(kc + PD, u);
+#pragma unroll
+            for (int j = 0; j < JN; ++j) {
+                if (kc * kTq4Kch + 32 * j < d) {  // uniform: k-steps past the end belong to no group
+                    half8 a[MT];
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+                        a[mt] = *reinterpret_cast<const half8 *>(&a_lds[buf][mt * 16 + c][32 * j + 8 * q]);
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+                        tmp[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], bhi[j], tmp[mt], 0, 0, 0);
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+                        tmp[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], blo[j], tmp[mt], 0, 0, 0);
+                    xs += xstep[j];
+                    if (++steps_in_group == ksteps_per_group) {
+                        fold(gi);
+                        ++gi;
+                        steps_in_group = 0;
+                    }
+                }
+            }
+            buf ^= 1;
+        }
+    }
+    ssq += __shfl_xor(ssq, 16, kWave);
+    ssq += __shfl_xor(ssq, 32, kWave);
+
+    // ---- score the tree: logits to LDS, then one node per wavefront and round
+    __syncthreads();
+    float *Zl = reinterpret_cast<float *>(q4_smem);  // [64 nodes][ROWS]
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+        *reinterpret_cast<floatx4 *>(&Zl[(wave * 16 + c) * ROWS + mt * 16 + q * 4]) = acc[mt];
+    if (q == 0) ssq_lds[wave * 16 + c] = ssq;
+    __syncthreads();
+    FinishRows<KC> fr;
+    finish_load_rows<KC>(fr, f, lane);
+    for (int n = wave; n < N; n += kTq4Waves) {
+        const size_t gn = (size_t)g * N + n;
+        float a = 0.f;
+        if (lane < K) {
+            int col = cols_lds[n * K + lane];
+            col = (col >= 0 && col < ROWS) ? col : 0;
+            a = Zl[n * ROWS + col];
+        }
+        const bool bad = overflow || bad_lds[n] != 0;
+        const float r = 1.0f / sqrtf(ssq_lds[n] / (float)d + p.eps);
+        float z[KC], prev[KC];
+#pragma unroll
+        for (int k = 0; k < KC; ++k) {
+            const float v = __shfl(a, k < K ? k : 0, kWave);
+            z[k] = (k < K) ? (bad ? quiet_nan() : v * r) : 0.f;
+            prev[k] = (k < K) ? prev_lds[n * K + k] : 0.f;
+        }
+        const int ex = finish_score_node<KC>(fr, f, gn, z, prev, lane);
+        if (lane == kWave - 1) exit_lds[n] = ex;
+    }
+    if (f.path_exit) {
+        __syncthreads();
+        finish_paths(exit_lds, par_lds, N, tid, kTq4Threads, f.path_exit + (size_t)g * N);
+    }
+}
+
+bool tree_q4_supported(int d, int N, int K, int Mcap, int group) {
+    if (N > 64 || N * K > kTq4MaxIds || Mcap > 128 || group % 32 != 0 || d % group != 0) return false;
+    return tree_q4_lds_bytes(d, Mcap, group) <= 150 * 1024;
+}
+
+size_t tree_q4_lds_bytes(int d, int Mcap, int group) {
+    const int rows = Mcap <= 64 ? 64 : 128;
+    return sizeof(half_t) * ((size_t)2 * rows * kTq4Row + (size_t)2 * (d / group) * rows);
+}
+
+template <int MT, int KC>
+static hipError_t launch_tq4(const TreeQ4Params &p, const TreeFinishParams &f, int G, hipStream_t st) {
+    const size_t lds = tree_q4_lds_bytes(p.d, p.Mcap, p.group);
+    auto kern = tree_q4_kernel<MT, KC>;
+    if (lds > 48 * 1024)  // per launch: the library keeps no state; a refusal shows as the launch error
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)lds);
+    hipLaunchKernelGGL(kern, dim3(G), dim3(kTq4Threads), lds, st, p, f);
+    return hipGetLastError();
+}
+
+hipError_t launch_tree_q4(const TreeQ4Params &p, const TreeFinishParams &f, int G, hipStream_t st) {
+    const bool wide = p.Mcap > 64;
+    if (f.K <= 4) return wide ? launch_tq4<8, 4>(p, f, G, st) : launch_tq4<4, 4>(p, f, G, st);
+    if (f.K <= 8) return wide ? launch_tq4<8, 8>(p, f, G, st) : launch_tq4<4, 8>(p, f, G, st);
+    return wide ? launch_tq4<8, 16>(p, f, G, st) : launch_tq4<4, 16>(p, f, G, st);
+}
+
+}  // namespace specee

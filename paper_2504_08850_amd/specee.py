@@ -358,6 +358,43 @@ def verify_q4(hidden, gamma, qweight, scales, zeros, group, ids, gate=None, eps=
     return out
 
 
+def predict_tree_q4(hidden, gamma, qweight, scales, zeros, group, ids, prev_probs, W1, w2, b1=None, b2=None,
+                    parent=None, Mcap=64, eps=1e-5, threshold=0.5, out=None, stream=None):
+    """specee_predict_tree_q4: hidden [G][N][d] (or [N][d] for a single tree) against the quantised head."""
+    single = hidden.dim() == 2
+    if single:
+        hidden, ids, prev_probs = hidden[None], ids[None], prev_probs[None]
+        parent = None if parent is None else parent[None]
+    G, N, d = hidden.shape
+    V, q = _q4_args(qweight, scales, zeros, group, d)
+    K = ids.shape[2]
+    H = w2.shape[0]
+    dev = hidden.device
+    if out is None:
+        i32, f32 = torch.int32, torch.float32
+        out = dict(merged=torch.empty((G, Mcap), dtype=i32, device=dev), M=torch.empty((G,), dtype=i32, device=dev),
+                   cols=torch.empty((G, N, K), dtype=i32, device=dev),
+                   logits=torch.empty((G, N, K), dtype=f32, device=dev),
+                   probs=torch.empty((G, N, K), dtype=f32, device=dev),
+                   scores=torch.empty((G, N), dtype=f32, device=dev),
+                   exit=torch.empty((G, N), dtype=i32, device=dev),
+                   path_exit=torch.empty((G, N), dtype=i32, device=dev) if parent is not None else None)
+    dims = _dims(d, V, K, H, eps, threshold)
+    mlp = _mlp(W1, w2, b1, b2)
+    f16 = torch.float16
+    rc = lib().specee_predict_tree_q4(C.byref(dims), C.c_int(G), C.c_int(N), C.c_int(Mcap), _ptr(hidden, f16),
+                                      _ptr(gamma, f16), *q, _ptr(ids, torch.int32), _ptr(parent, torch.int32),
+                                      _ptr(prev_probs, torch.float32), C.byref(mlp), _ptr(out["merged"]),
+                                      _ptr(out["M"]), _ptr(out["cols"]), _ptr(out["logits"]), _ptr(out["probs"]),
+                                      _ptr(out["scores"]), _ptr(out["exit"]), _ptr(out.get("path_exit")),
+                                      _stream(stream))
+    if rc:
+        raise SpeceeError("specee_predict_tree_q4", rc)
+    if single:
+        return {k: (v[0] if v is not None else None) for k, v in out.items()}
+    return out
+
+
 def calib_copy(dst, src, stream=None):
     """specee_calib_copy: plain device copy of known size (counter calibration)."""
     nbytes = src.numel() * src.element_size()
