@@ -594,7 +594,9 @@ def main():
                                         "algorithmic_bytes": byts, "achieved_GBps": byts / us_tree / 1e3}
         full = torch.empty((c5.N, c5.V), device=dev)
         g = capture(lambda: sp.lm_head_gemv(dts[0][0], g5, lm5, out=full))
-        us64 = ev_time(g.replay, 30, 5) * 1e3
+        # (the first few dozen passes over a 2 GB head run 10-20 % slower than the sustained rate -- successive
+        # repetitions in one process on the same buffers read 501, 447, 438, 420 us -- so this one warms up longer)
+        us64 = ev_time(g.replay, 30, 40) * 1e3
         b64 = c5.V * c5.d * 2 + c5.N * c5.d * 2 + c5.N * c5.V * 4
         extra["lm_head_gemv_128256x8192_N64"] = {"us_per_call": us64, **spread(), "algorithmic_bytes": b64,
                                                  "achieved_GBps": b64 / us64 / 1e3,
