@@ -26,7 +26,7 @@
  *    [0, V) makes that token's logits, probs and score NaN and its exit flag 0;
  *    a tree whose merged set exceeds Mcap reports the true size in M_out and
  *    NaN / 0 in that tree's other outputs.  No kernel reads out of bounds in
- *    either case.
+ *    either case.  specee_status_word() folds these reports into one word.
  *  - Arithmetic: fp16 inputs are widened exactly; products and sums are fp32;
  *    outputs are fp32 / int32.  Reductions have a fixed order, so results are
  *    bit-identical from run to run.
@@ -330,6 +330,22 @@ int specee_sched_init(specee_sched *s, int L, int Q, int radius);
 int specee_sched_push(specee_sched *s, int exit_layer);
 /* active [L] (0/1) for the next token; offline_mask [L] or NULL. Returns the number of active layers. */
 int specee_sched_active(const specee_sched *s, const int32_t *offline_mask, int32_t *active);
+
+/*
+ * Device status word.  What only the device can see is reported in the outputs
+ * (see the conventions at the top): this call folds those reports into one
+ * int32 on the device, enqueued on `stream` like everything else, so that a
+ * caller reads one word after synchronising instead of scanning outputs:
+ *   bit SPECEE_STATUS_INVALID_ID      some score is NaN: a speculative id of that
+ *                                     token / node lies outside [0, V);
+ *   bit SPECEE_STATUS_MERGE_OVERFLOW  some M_out[g] > Mcap (trees only).
+ * scores [n_scores] fp32 as written by any predictor entry point; M_out [G] or
+ * NULL (then G and Mcap are ignored); status [1] int32 is overwritten.
+ */
+#define SPECEE_STATUS_INVALID_ID 1
+#define SPECEE_STATUS_MERGE_OVERFLOW 2
+int specee_status_word(const float *scores, size_t n_scores, const int32_t *M_out, int G, int Mcap,
+                       int32_t *status, void *stream);
 
 /*
  * Measurement aid, not part of the method: copies `bytes` (multiple of 16,

@@ -395,6 +395,18 @@ def predict_tree_q4(hidden, gamma, qweight, scales, zeros, group, ids, prev_prob
     return out
 
 
+def status_word(scores, M=None, Mcap=0, out=None, stream=None):
+    """specee_status_word: one int32 on the device (bit 1: an invalid id somewhere, bit 2: a merged set overflowed)."""
+    if out is None:
+        out = torch.empty((1,), dtype=torch.int32, device=scores.device)
+    G = 0 if M is None else M.numel()
+    rc = lib().specee_status_word(_ptr(scores, torch.float32), C.c_size_t(scores.numel()), _ptr(M, torch.int32),
+                                  C.c_int(G), C.c_int(Mcap), _ptr(out, torch.int32), _stream(stream))
+    if rc:
+        raise SpeceeError("specee_status_word", rc)
+    return out
+
+
 def calib_copy(dst, src, stream=None):
     """specee_calib_copy: plain device copy of known size (counter calibration)."""
     nbytes = src.numel() * src.element_size()

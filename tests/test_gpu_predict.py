@@ -357,3 +357,31 @@ def test_lm_head_llama7b_full_vocab(sp, oracle):
     w = close(got, ref, 1.0, "lm_head 32000x4096")
     print("lm_head 32000x4096 worst", w)
     assert int(got.argmax()) == int(ref.argmax())
+
+
+# ---------------------------------------------------------------- device status word
+def test_status_word_reports_invalid_ids_and_merge_overflow(sp):
+    t = synth.make("T3")
+    c = t["cfg"]
+    a = dict(hidden=dev(t["hidden"]), gamma=dev(t["gamma"]), lm=dev(t["lm_head"]), prev=dev(t["prev_probs"]),
+             W1=dev(t["W1"]), w2=dev(t["w2"]), parent=dev(t["parent"]))
+
+    def tree(ids, Mcap):
+        o = sp.predict_tree(a["hidden"], a["gamma"], a["lm"], dev(ids), a["prev"], a["W1"], a["w2"], parent=a["parent"],
+                            Mcap=Mcap)
+        w = sp.status_word(o["scores"], o["M"].reshape(1), Mcap)
+        torch.cuda.synchronize()
+        return int(host(w)[0])
+    assert tree(t["ids"], c.Mcap) == 0
+    bad = t["ids"].copy()
+    bad[5, 1] = c.V
+    assert tree(bad, c.Mcap) == 1                       # an id outside the vocabulary
+    assert tree(t["ids"], len(np.unique(t["ids"])) - 1) == 3   # overflow (its scores are NaN as well)
+    p = custom(9, 256, 100, 4, 64, 300, False)
+    ids = p["ids"].copy()
+    ids[250, 3] = -7
+    o = sp.predict(dev(p["hidden"]), dev(p["gamma"]), dev(p["lm_head"]), dev(ids), dev(p["prev_probs"]), dev(p["W1"]),
+                   dev(p["w2"]))
+    w = sp.status_word(o["scores"])
+    torch.cuda.synchronize()
+    assert int(host(w)[0]) == 1

@@ -97,3 +97,16 @@ def test_quantize_q4_round_trip_error_is_half_a_step():
     back = s * (codes - z)
     # min/max rounding: every element within about half a step of its group (fp16 scale and zero-point)
     assert np.all(np.abs(back - w.astype(np.float64)) <= 0.75 * s + 1e-6)
+
+
+def test_host_code_is_clean_under_address_and_undefined_behaviour_sanitizers():
+    """The C oracle and the library's host-side scheduler, built with -fsanitize=address,undefined and driven
+    over every entry point (tests/sanitize/sanitize_main.c): no report, exit status 0."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("sanitize_host", ROOT / "tests" / "sanitize" / "build_and_run.py")
+    sanitize = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(sanitize)
+    r = sanitize.run()
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "ERROR" not in r.stderr and "runtime error" not in r.stderr, r.stderr
+    assert "ok" in r.stdout
