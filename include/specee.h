@@ -30,6 +30,10 @@
  *  - Arithmetic: fp16 inputs are widened exactly; products and sums are fp32;
  *    outputs are fp32 / int32.  Reductions have a fixed order, so results are
  *    bit-identical from run to run.
+ *  - Range: the matrix-core paths (token trees, the full head for more than
+ *    two hidden states) form hidden * gamma in fp16 before splitting it exactly
+ *    into two halves, so |hidden[i] * gamma[i]| must stay below 65504 there
+ *    (beyond that the logits are inf / NaN); the other paths form it in fp32.
  *  - Calls that share a workspace must not overlap in time.
  */
 #ifndef SPECEE_H

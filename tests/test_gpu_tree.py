@@ -100,6 +100,31 @@ def test_tree_equals_independent_predict_calls_on_gpu(sp):
     close(tree["scores"], host(ind["scores"]), 1e-3, "tree vs independent scores")
 
 
+def test_tree_and_predict_agree_on_hidden_states_with_large_outliers(sp, oracle):
+    """A few hidden elements in the thousands (the outlier channels of real models): the matrix-core paths form
+    h * gamma in fp16 before splitting it exactly, which holds up to 65504; merged tree, independent predictors
+    and oracle must still agree."""
+    t = make_tree(21, 1024, 500, 4, 512, 40)
+    rng = np.random.default_rng(5)
+    h = t["hidden"].astype(np.float32)
+    for n in range(40):
+        h[n, rng.integers(0, 1024, 3)] = rng.choice([-1.0, 1.0], 3) * rng.uniform(500, 3000, 3)
+    t["hidden"] = h.astype(np.float16)
+    t["gamma"] = (1.5 + 0.05 * rng.standard_normal(1024)).astype(np.float16)
+    pool = rng.permutation(500)[:60]
+    t["ids"] = pool[rng.integers(0, 60, size=(40, 4))].astype(np.int32)
+    ref = ref_tree(oracle, t, 64)
+    lm_d = dev(t["lm_head"])
+    got = run_tree(sp, t, lm_d, 64)
+    check_tree(got, ref, 0.5, "outlier hidden states", min_compared=0.3)
+    ind = sp.predict(dev(t["hidden"]), dev(t["gamma"]), lm_d, dev(t["ids"]), dev(t["prev_probs"]), dev(t["W1"]),
+                     dev(t["w2"]))
+    torch.cuda.synchronize()
+    close(host(ind["logits"]), ref["logits"], 1.0, "independent predictors, outlier hidden states")
+    full = host(sp.lm_head_gemv(dev(t["hidden"][:8]), dev(t["gamma"]), lm_d))      # matrix-core head, same split
+    close(full, oracle.lm_head_gemv(t["hidden"][:8], t["gamma"], t["lm_head"]), 1.0, "full head, outlier hidden states")
+
+
 def make_tree(seed, d, V, K, H, N, ids=None, bias=False):
     rng = np.random.default_rng(seed)
     t = dict(
