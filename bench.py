@@ -307,6 +307,43 @@ def main():
             byts = predict_bytes(d, K, B, distinct_rows=len(np.unique(ids_h)))
             tp[f"B={B}"] = {"us_per_launch": us, **spread(reps), "evals_per_s": B / us * 1e6, "algorithmic_bytes": byts,
                             "achieved_GBps": byts / us / 1e3, "frac_of_8TBps": byts / us / 1e3 / HBM_PEAK_GBS}
+        # ids as a draft model would give them: Zipf(1.1) ranks over the vocabulary (the 16-sequence workload's
+        # recipe).  Hot rows repeat across tokens and stay in L2, so the launch moves little more than the
+        # hidden states; no de-duplication pass is needed for that.
+        B = 16384
+        rng = np.random.default_rng(3)
+        hid = up(rng.standard_normal((B, d), dtype=np.float32).astype(np.float16))
+        ids_h = synth.ids_zipf_vocab(B, K, V, 4242)
+        ids, prev = up(ids_h), up(synth.prob_rows(B, K, 9))
+        o = sp.predict(hid, gamma, lm, ids, prev, w1_1, w2_1)
+        g = capture(lambda: [sp.predict(hid, gamma, lm, ids, prev, w1_1, w2_1, out=o) for _ in range(8)])
+        us = ev_time(g.replay, 20, 3) * 1e3 / 8
+        byts = predict_bytes(d, K, B, distinct_rows=len(np.unique(ids_h)))
+        tp["B=16384_zipf_ids"] = {"us_per_launch": us, **spread(8), "evals_per_s": B / us * 1e6,
+                                  "distinct_rows": int(len(np.unique(ids_h))), "algorithmic_bytes": byts,
+                                  "achieved_GBps": byts / us / 1e3, "frac_of_8TBps": byts / us / 1e3 / HBM_PEAK_GBS,
+                                  "path": "specee_predict, one workgroup per token; repeated rows served by L2"}
+        # the same batch through the merged mapping: groups of Ng tokens scored as one "tree" each against the
+        # union of their ids (specee_predict_tree without parents), so that a row shared inside a group is read once
+        merged_alt = {}
+        for Ng, cap in ((32, 128), (64, 256)):
+            Gg = B // Ng
+            Mg = [len(np.unique(ids_h[i * Ng:(i + 1) * Ng])) for i in range(Gg)]
+            if max(Mg) > cap:
+                merged_alt[f"groups_of_{Ng}"] = {"skipped": f"a group's union ({max(Mg)}) exceeds {cap} rows"}
+                continue
+            ot = sp.predict_tree(hid.view(Gg, Ng, d), gamma, lm, ids.view(Gg, Ng, K), prev.view(Gg, Ng, K), w1_1, w2_1,
+                                 Mcap=cap)
+            wst = ot.pop("_workspace")
+            g = capture(lambda: [sp.predict_tree(hid.view(Gg, Ng, d), gamma, lm, ids.view(Gg, Ng, K),
+                                                 prev.view(Gg, Ng, K), w1_1, w2_1, Mcap=cap, out=ot, workspace=wst)
+                                 for _ in range(4)])
+            usm = ev_time(g.replay, 10, 2) * 1e3 / 4
+            torch.cuda.synchronize()
+            same = bool(torch.allclose(ot["scores"].flatten(), o["scores"], rtol=2e-3, atol=2e-6))
+            merged_alt[f"groups_of_{Ng}"] = {"us_per_launch": usm, **spread(4), "mean_union": float(np.mean(Mg)),
+                                             "rows_read": int(np.sum(Mg)), "scores_agree_with_direct_path": same}
+        tp["B=16384_zipf_ids"]["merged_mapping_alternative"] = merged_alt
         # B=8000 touches every row of the 262 MB head, most of which the 256 MB last-level cache can keep from
         # one launch to the next; alternating between two different heads takes that help away
         lm_b = up(synth.lm_head(V, d, synth.lm_seed(c2) + 1))

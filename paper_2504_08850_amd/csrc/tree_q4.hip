@@ -18,6 +18,8 @@
 // a multiple of 32 elements -- ends on a k-step boundary.  Within a k-step the eight elements of a lane
 // sit in the order (0,4,1,5,2,6,3,7) on both operands (any order is valid if A and B agree), which is
 // the order the nibble pairs come out of a 32-bit word.
+#include <type_traits>
+
 #include "device_utils.h"
 #include "kernels.h"
 #include "merge_block.h"
@@ -25,11 +27,16 @@
 
 namespace specee {
 
-constexpr int kTq4Threads = 256;
+// 512 threads: wavefronts w and w + 4 share node tile w and take half of the k-steps of every stage each (the
+// fold is linear, so each folds its own share of a group); their logits are added through LDS at the end.
+// One wavefront per node tile doing all of a stage was twice as slow: the per-stage instruction stream of a
+// wavefront, not memory, bounds a workgroup that streams a whole tree.
+constexpr int kTq4Threads = 512;
 constexpr int kTq4Waves = kTq4Threads / kWave;
+constexpr int kTq4Kh = kTq4Threads / 256;           // wavefronts per node tile
 constexpr int kTq4Kch = 128;                        // elements per stage
 constexpr int kTq4Row = kTq4Kch + 8;                // halves per LDS row
-constexpr int kTq4MaxIds = kMergePerThread * kTq4Threads;
+constexpr int kTq4MaxIds = 1024;                    // ids per tree (N * K)
 
 // eight codes of a word as halves, in the order (0,4,1,5,2,6,3,7)
 __device__ __forceinline__ half8 codes_to_half8(uint32_t w) {
@@ -48,15 +55,16 @@ __device__ __forceinline__ half8 codes_to_half8(uint32_t w) {
 template <int MT, int KC>
 __global__ __launch_bounds__(kTq4Threads) void tree_q4_kernel(TreeQ4Params p, TreeFinishParams f) {
     constexpr int ROWS = 16 * MT;
-    constexpr int JN = kTq4Kch / 32;                      // k-steps per stage
+    constexpr int JN = kTq4Kch / 32 / kTq4Kh;             // k-steps per stage and wavefront
     constexpr int CPT = ROWS * (kTq4Kch / 16) / kTq4Threads;  // 8-byte code chunks (16 elements) per thread per stage
     extern __shared__ __attribute__((aligned(16))) half_t q4_smem[];
-    // dynamic LDS: row tiles [2][ROWS][kTq4Row] halves | scales [ng][ROWS] halves | zero-points [ng][ROWS] halves
+    // dynamic LDS: row tiles [2][ROWS][kTq4Row] halves | scales [ng][ROWS] | zero-points [ng][ROWS] | gamma [d]
     typedef half_t (*tile_t)[ROWS][kTq4Row];
     tile_t a_lds = reinterpret_cast<tile_t>(q4_smem);
     const int ng = p.d / p.group;
     half_t *sc_lds = q4_smem + 2 * ROWS * kTq4Row;
     half_t *zp_lds = sc_lds + (size_t)ng * ROWS;
+    half_t *gam_lds = zp_lds + (size_t)ng * ROWS;  // the RMSNorm weight, staged once ([d]; 16-byte aligned: ROWS % 8 == 0)
     __shared__ int32_t cols_lds[kTq4MaxIds];
     __shared__ float prev_lds[kTq4MaxIds];
     __shared__ float ssq_lds[64];
@@ -68,7 +76,10 @@ __global__ __launch_bounds__(kTq4Threads) void tree_q4_kernel(TreeQ4Params p, Tr
     static_assert(sizeof(half_t) * 2 * ROWS * kTq4Row >= sizeof(float) * 64 * ROWS, "the logits must fit");
     static_assert(CPT >= 1, "at least one chunk per thread");
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    // in a scalar register: the group bookkeeping below branches on values derived from it, and the compiler
+    // would otherwise run those branches as divergent vector code
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, q = lane >> 4;
     const int g = blockIdx.x;
     const int d = p.d, N = p.N, K = p.K, n_ids = N * K;
@@ -77,7 +88,8 @@ __global__ __launch_bounds__(kTq4Threads) void tree_q4_kernel(TreeQ4Params p, Tr
     // ---- the ids first; then what does not depend on them
     int ids_r[kMergePerThread];
     merge_load_ids<kTq4Threads>(p.ids + (size_t)g * n_ids, n_ids, ids_r);
-    const int node = wave * 16 + c;
+    const int kh = wave >> 2, nt_w = wave & 3;  // k-share and node tile of this wavefront
+    const int node = nt_w * 16 + c;
     const bool node_ok = node < N;
     const half_t *hrow = p.hidden + ((size_t)g * N + (node_ok ? node : 0)) * d;
     float prev_r[kMergePerThread];
@@ -87,6 +99,19 @@ __global__ __launch_bounds__(kTq4Threads) void tree_q4_kernel(TreeQ4Params p, Tr
     const int32_t *pp = f.path_exit ? f.parent + (size_t)g * N + min(tid, N - 1) : p.ids;
     const int par_r = *pp;
     if (tid < 64) bad_lds[tid] = 0;
+    // the RMSNorm weight goes to LDS once (read again by every lane at every stage otherwise: cache hits, but
+    // they take slots of the vector memory path that the streaming needs)
+    // every eight of it in the order (0,4,1,5,2,6,3,7), the one the B operand is built in
+    for (int v = tid; v < (d >> 3); v += kTq4Threads) {
+        const half8 gv = load_half8(p.gamma + v * 8);
+        half8 gp;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            gp[2 * e] = gv[e];
+            gp[2 * e + 1] = gv[e + 4];
+        }
+        *reinterpret_cast<half8 *>(&gam_lds[v * 8]) = gp;
+    }
 
     // ---- merge
     int32_t *uniq = nullptr;
@@ -100,38 +125,46 @@ __global__ __launch_bounds__(kTq4Threads) void tree_q4_kernel(TreeQ4Params p, Tr
     const bool overflow = Mtrue > p.Mcap;
     const int M = overflow ? p.Mcap : Mtrue;
 
-    // ---- the rows' codes are requested the moment the rows are known: chunk (row, v) = tid + 256 * i
+    // ---- the rows' codes are requested the moment the rows are known: chunk (row, v) = tid + 512 * i.
+    // Rows beyond the merged set and nodes beyond the tree read row 0 / node 0: their logits are never looked at.
     const uint32_t *crow[CPT];
-    bool crow_ok[CPT];
     int c_r[CPT], c_v[CPT];
 #pragma unroll
     for (int i = 0; i < CPT; ++i) {
         const int ci = tid + kTq4Threads * i;
         c_r[i] = ci / (kTq4Kch / 16);
         c_v[i] = ci % (kTq4Kch / 16);
-        crow_ok[i] = c_r[i] < M;
-        int row = crow_ok[i] ? uniq[c_r[i]] : 0;
+        int row = c_r[i] < M ? uniq[c_r[i]] : 0;
         if (row < 0 || row >= p.V) row = 0;  // invalid id: the node is reported NaN, nothing is read out of bounds
         crow[i] = p.qweight + (size_t)row * (d >> 3);
     }
+    const int kq = 32 * kh * JN + 8 * q;  // this lane's first element within a stage
+    // stages in flight
     constexpr int PD = 2;
+    static_assert(PD % 2 == 0, "the LDS buffer of a stage is its slot's parity");
     uint2 a_buf[PD][CPT];
-    half8 h_buf[PD][JN], g_buf[PD][JN];
-    auto issue = [&](int kc, int slot) {  // unconditional, clamped into the row; masked when consumed
+    half8 h_buf[PD][JN];
+    // TAIL: the stage may reach past the end of the rows: loads are clamped into the row (and masked when
+    // consumed); a full stage needs neither
+    auto issue = [&](auto tail_c, int kc, int slot) {
+        constexpr bool TAIL = decltype(tail_c)::value;
 #pragma unroll
         for (int i = 0; i < CPT; ++i) {
-            const int ko = min(kc * kTq4Kch + c_v[i] * 16, d - 16);
+            const int ko = TAIL ? min(kc * kTq4Kch + c_v[i] * 16, d - 16) : kc * kTq4Kch + c_v[i] * 16;
             a_buf[slot][i] = *reinterpret_cast<const uint2 *>(crow[i] + (ko >> 3));
         }
 #pragma unroll
         for (int j = 0; j < JN; ++j) {
-            const int ko = min(kc * kTq4Kch + 32 * j + 8 * q, d - 8);
-            g_buf[slot][j] = load_half8(p.gamma + ko);
+            const int ko = TAIL ? min(kc * kTq4Kch + kq + 32 * j, d - 8) : kc * kTq4Kch + kq + 32 * j;
             h_buf[slot][j] = load_half8(hrow + ko);
         }
     };
+    const int nfull = d / kTq4Kch;  // stages that lie wholly inside the rows
 #pragma unroll
-    for (int u = 0; u < PD; ++u) issue(u, u);
+    for (int u = 0; u < PD; ++u) {
+        if (u < nfull) issue(std::false_type{}, u, u);
+        else issue(std::true_type{}, u, u);
+    }
 
     // ---- publish the merge, park what the scoring phase needs, stage the rows' scales and zero-points
     if (tid == 0) p.M_out[g] = Mtrue;
@@ -147,56 +180,91 @@ __global__ __launch_bounds__(kTq4Threads) void tree_q4_kernel(TreeQ4Params p, Tr
         }
     }
     if (f.path_exit && tid < N) par_lds[tid] = par_r;
-    for (int i = tid; i < ROWS * ng; i += kTq4Threads) {
-        const int m = i / ng, gi = i - m * ng;
-        int row = m < M ? uniq[m] : 0;
-        if (row < 0 || row >= p.V) row = 0;
-        sc_lds[(size_t)gi * ROWS + m] = m < M ? p.qscales[(size_t)row * ng + gi] : (half_t)0.f;
-        zp_lds[(size_t)gi * ROWS + m] = m < M ? p.qzeros[(size_t)row * ng + gi] : (half_t)0.f;
+    if ((ng & 7) == 0 && (((uintptr_t)p.qscales | (uintptr_t)p.qzeros) & 15) == 0) {
+        // eight groups of a row per 16-byte load; all of a thread's loads go out before the first is used
+        // (a loop of load -> store would make one trip to memory per round)
+        const int nvec = ROWS * (ng >> 3);
+        constexpr int kRounds = 4;
+        for (int i0 = tid; i0 < nvec; i0 += kTq4Threads * kRounds) {
+            half8 sv[kRounds], zv[kRounds];
+            int mm[kRounds], g0[kRounds];
+#pragma unroll
+            for (int r = 0; r < kRounds; ++r) {
+                const int i = min(i0 + r * kTq4Threads, nvec - 1);
+                mm[r] = i / (ng >> 3);
+                g0[r] = (i - mm[r] * (ng >> 3)) * 8;
+                int row = mm[r] < M ? uniq[mm[r]] : 0;
+                if (row < 0 || row >= p.V) row = 0;
+                sv[r] = load_half8(p.qscales + (size_t)row * ng + g0[r]);
+                zv[r] = load_half8(p.qzeros + (size_t)row * ng + g0[r]);
+            }
+#pragma unroll
+            for (int r = 0; r < kRounds; ++r)
+                if (i0 + r * kTq4Threads < nvec) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        sc_lds[(size_t)(g0[r] + e) * ROWS + mm[r]] = mm[r] < M ? sv[r][e] : (half_t)0.f;
+                        zp_lds[(size_t)(g0[r] + e) * ROWS + mm[r]] = mm[r] < M ? zv[r][e] : (half_t)0.f;
+                    }
+                }
+        }
+    } else {
+        for (int i = tid; i < ROWS * ng; i += kTq4Threads) {
+            const int m = i / ng, gi = i - m * ng;
+            int row = m < M ? uniq[m] : 0;
+            if (row < 0 || row >= p.V) row = 0;
+            sc_lds[(size_t)gi * ROWS + m] = m < M ? p.qscales[(size_t)row * ng + gi] : (half_t)0.f;
+            zp_lds[(size_t)gi * ROWS + m] = m < M ? p.qzeros[(size_t)row * ng + gi] : (half_t)0.f;
+        }
     }
     __syncthreads();  // the merge scratch becomes the row tile buffers; scales and zero-points are in place
 
-    floatx4 acc[MT], tmp[MT];
+    floatx4 acc[MT], tmp[MT], tsum = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[mt] = tmp[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
-    float ssq = 0.f, xs = 0.f;
+    float ssq = 0.f;
+    half8 ones8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ones8[e] = (half_t)1.f;
 
     // the row tile of stage kc from the prefetched codes: 16 elements per chunk, two 16-byte LDS writes
-    auto tile_to_lds = [&](int kc, int slot, int b) {
+    auto tile_to_lds = [&](auto tail_c, int kc, int slot, int b) {
+        constexpr bool TAIL = decltype(tail_c)::value;
 #pragma unroll
         for (int i = 0; i < CPT; ++i) {
-            const bool in = crow_ok[i] && kc * kTq4Kch + c_v[i] * 16 < d;
+            const bool in = !TAIL || kc * kTq4Kch + c_v[i] * 16 < d;
             const half8 lo = codes_to_half8(a_buf[slot][i].x), hi = codes_to_half8(a_buf[slot][i].y);
             *reinterpret_cast<half8 *>(&a_lds[b][c_r[i]][c_v[i] * 16]) = in ? lo : zero_half8();
             *reinterpret_cast<half8 *>(&a_lds[b][c_r[i]][c_v[i] * 16 + 8]) = in ? hi : zero_half8();
         }
     };
     // x = h * gamma of this lane's node, k-step j of stage kc, split exactly into hi + lo, elements in the
-    // order (0,4,1,5,2,6,3,7); also the lane's share of the sum of squares, and of the sum of x over this
-    // k-step (xsum; it joins the group sum when the k-step is multiplied)
-    auto build_b = [&](int kc, int slot, int j, half8 &hi, half8 &lo, float &xsum) {
-        const bool in = node_ok && kc * kTq4Kch + 32 * j + 8 * q < d;
-        const half8 hsel = in ? h_buf[slot][j] : zero_half8();
-        const half8 gvec = g_buf[slot][j];
+    // order (0,4,1,5,2,6,3,7) (the weight sits in LDS in that order already); also the lane's share of the
+    // sum of squares
+    auto build_b = [&](auto tail_c, int kc, int slot, int j, half8 &hi, half8 &lo) {
+        constexpr bool TAIL = decltype(tail_c)::value;
+        const int ko = kc * kTq4Kch + kq + 32 * j;
+        const half8 hsel = (!TAIL || ko < d) ? h_buf[slot][j] : zero_half8();
+        // (k-steps past the end read the tail of the weight: in bounds, and hsel is zero there)
+        const half8 gvec = *reinterpret_cast<const half8 *>(&gam_lds[TAIL ? min(ko, d - 8) : ko]);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const half2_t hh = {hsel[e], hsel[e + 4]};
-            const half2_t gg = {gvec[e], gvec[e + 4]};
+            const half2_t gg = {gvec[2 * e], gvec[2 * e + 1]};
             const half2_t x = hh * gg;
             const half2_t rres = __builtin_elementwise_fma(hh, gg, -x);
             ssq = __builtin_amdgcn_fdot2(hh, hh, ssq, false);
-            xsum += ((float)x[0] + (float)rres[0]) + ((float)x[1] + (float)rres[1]);
             hi[2 * e] = x[0];
             hi[2 * e + 1] = x[1];
             lo[2 * e] = rres[0];
             lo[2 * e + 1] = rres[1];
         }
     };
-    // end of a quantisation group: acc += scale * (tmp - zero * sum of x over the group), row by row
+    // end of a quantisation group: acc += scale * (tmp - zero * sum of x over the group), row by row.  The sum
+    // of x comes off the matrix cores too: a row tile of ones beside the codes leaves it, for the lane's node,
+    // in every register of tsum.
     auto fold = [&](int gi) {
-        float t = xs;
-        t += __shfl_xor(t, 16, kWave);
-        t += __shfl_xor(t, 32, kWave);  // the four lane groups of node c hold disjoint elements
+        const float t = tsum[0];
         const half_t *scp = sc_lds + (size_t)gi * ROWS + 4 * q;
         const half_t *zpp = zp_lds + (size_t)gi * ROWS + 4 * q;
 #pragma unroll
@@ -207,61 +275,84 @@ __global__ __launch_bounds__(kTq4Threads) void tree_q4_kernel(TreeQ4Params p, Tr
             for (int r = 0; r < 4; ++r) acc[mt][r] += (float)s4[r] * (tmp[mt][r] - (float)z4[r] * t);
             tmp[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
         }
-        xs = 0.f;
+        tsum = floatx4{0.f, 0.f, 0.f, 0.f};
     };
 
-    const int ksteps_per_group = p.group >> 5;
-    int steps_in_group = 0, gi = 0;
-    const int nstages = ((nchunks + PD - 1) / PD) * PD;
-    int buf = 0;
-    for (int kc0 = 0; kc0 < nstages; kc0 += PD) {
+    // A wavefront's k-steps ascend, and a k-step lies inside one group (groups are multiples of 32 elements):
+    // it folds whenever the next k-step it multiplies starts at or past the end of the group it has open.
+    int gi = 0, gend = p.group;
+    bool dirty = false;
+    auto round = [&](auto tail_c, int kc0) {
+        constexpr bool TAIL = decltype(tail_c)::value;
 #pragma unroll
         for (int u = 0; u < PD; ++u) {
             const int kc = kc0 + u;
+            constexpr int kBufOf[2] = {0, 1};
+            const int buf = kBufOf[u & 1];
             half8 bhi[JN], blo[JN];
-            float xstep[JN];
-            tile_to_lds(kc, u, buf);
+            tile_to_lds(tail_c, kc, u, buf);
 #pragma unroll
-            for (int j = 0; j < JN; ++j) {
-                xstep[j] = 0.f;
-                build_b(kc, u, j, bhi[j], blo[j], xstep[j]);
-            }
+            for (int j = 0; j < JN; ++j) build_b(tail_c, kc, u, j, bhi[j], blo[j]);
             __syncthreads();
-            issue(kc + PD, u);
+            issue(tail_c, kc + PD, u);
 #pragma unroll
             for (int j = 0; j < JN; ++j) {
-                if (kc * kTq4Kch + 32 * j < d) {  // uniform: k-steps past the end belong to no group
+                const int k0 = kc * kTq4Kch + 32 * (kh * JN + j);  // first element of this k-step
+                if (!TAIL || k0 < d) {  // uniform over the wavefront: k-steps past the end belong to no group
+                    if (k0 >= gend) {
+                        if (dirty) fold(gi);
+                        dirty = false;
+                        do {
+                            ++gi;
+                            gend += p.group;
+                        } while (k0 >= gend);
+                    }
                     half8 a[MT];
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt)
-                        a[mt] = *reinterpret_cast<const half8 *>(&a_lds[buf][mt * 16 + c][32 * j + 8 * q]);
+                        a[mt] = *reinterpret_cast<const half8 *>(&a_lds[buf][mt * 16 + c][32 * (kh * JN + j) + 8 * q]);
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt)
                         tmp[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], bhi[j], tmp[mt], 0, 0, 0);
+                    tsum = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones8, bhi[j], tsum, 0, 0, 0);
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt)
                         tmp[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], blo[j], tmp[mt], 0, 0, 0);
-                    xs += xstep[j];
-                    if (++steps_in_group == ksteps_per_group) {
-                        fold(gi);
-                        ++gi;
-                        steps_in_group = 0;
-                    }
+                    tsum = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones8, blo[j], tsum, 0, 0, 0);
+                    dirty = true;
                 }
             }
-            buf ^= 1;
         }
+    };
+    const int nstages = ((nchunks + PD - 1) / PD) * PD;
+    for (int kc0 = 0; kc0 < nstages; kc0 += PD) {
+        // a round is plain when its stages and the ones it prefetches all lie wholly inside the rows
+        if (kc0 + 2 * PD <= nfull) round(std::false_type{}, kc0);
+        else round(std::true_type{}, kc0);
     }
+    if (dirty) fold(gi);
     ssq += __shfl_xor(ssq, 16, kWave);
     ssq += __shfl_xor(ssq, 32, kWave);
 
-    // ---- score the tree: logits to LDS, then one node per wavefront and round
+    // ---- score the tree: the two k-shares of a node tile are added in a fixed order through the logit array
+    // itself, then one node per wavefront and round
     __syncthreads();
     float *Zl = reinterpret_cast<float *>(q4_smem);  // [64 nodes][ROWS]
+    if (kh == kTq4Kh - 1) {
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-        *reinterpret_cast<floatx4 *>(&Zl[(wave * 16 + c) * ROWS + mt * 16 + q * 4]) = acc[mt];
-    if (q == 0) ssq_lds[wave * 16 + c] = ssq;
+        for (int mt = 0; mt < MT; ++mt)
+            *reinterpret_cast<floatx4 *>(&Zl[(nt_w * 16 + c) * ROWS + mt * 16 + q * 4]) = acc[mt];
+        if (q == 0) ssq_lds[nt_w * 16 + c] = ssq;
+    }
+    __syncthreads();
+    if (kTq4Kh == 2 && kh == 0) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            floatx4 *cell = reinterpret_cast<floatx4 *>(&Zl[(nt_w * 16 + c) * ROWS + mt * 16 + q * 4]);
+            *cell = acc[mt] + *cell;
+        }
+        if (q == 0) ssq_lds[nt_w * 16 + c] += ssq;
+    }
     __syncthreads();
     FinishRows<KC> fr;
     finish_load_rows<KC>(fr, f, lane);
@@ -298,7 +389,7 @@ bool tree_q4_supported(int d, int N, int K, int Mcap, int group) {
 
 size_t tree_q4_lds_bytes(int d, int Mcap, int group) {
     const int rows = Mcap <= 64 ? 64 : 128;
-    return sizeof(half_t) * ((size_t)2 * rows * kTq4Row + (size_t)2 * (d / group) * rows);
+    return sizeof(half_t) * ((size_t)2 * rows * kTq4Row + (size_t)2 * (d / group) * rows + (size_t)d);
 }
 
 template <int MT, int KC>
