@@ -98,6 +98,7 @@ __global__ __launch_bounds__(kTq4Threads) void tree_q4_kernel(TreeQ4Params p, Tr
         prev_r[e] = f.prev[(size_t)g * n_ids + min(tid + e * kTq4Threads, n_ids - 1)];
     const int32_t *pp = f.path_exit ? f.parent + (size_t)g * N + min(tid, N - 1) : p.ids;
     const int par_r = *pp;
+    const half_t b2_r = *(f.b2 ? f.b2 : p.gamma);  // output bias (widened where it is used; masked when absent)
     if (tid < 64) bad_lds[tid] = 0;
     // the RMSNorm weight goes to LDS once (read again by every lane at every stage otherwise: cache hits, but
     // they take slots of the vector memory path that the streaming needs)
@@ -335,7 +336,7 @@ __global__ __launch_bounds__(kTq4Threads) void tree_q4_kernel(TreeQ4Params p, Tr
     ssq += __shfl_xor(ssq, 32, kWave);
 
     // ---- score the tree: the two k-shares of a node tile are added in a fixed order through the logit array
-    // itself, then one node per wavefront and round
+    // itself
     __syncthreads();
     float *Zl = reinterpret_cast<float *>(q4_smem);  // [64 nodes][ROWS]
     if (kh == kTq4Kh - 1) {
@@ -354,27 +355,89 @@ __global__ __launch_bounds__(kTq4Threads) void tree_q4_kernel(TreeQ4Params p, Tr
         if (q == 0) ssq_lds[nt_w * 16 + c] += ssq;
     }
     __syncthreads();
-    FinishRows<KC> fr;
-    finish_load_rows<KC>(fr, f, lane);
-    for (int n = wave; n < N; n += kTq4Waves) {
+    if (KC <= 8 && mlp_mfma_ok(K, f.H)) {
+        // The predictor MLP of the 16 nodes of a node tile on the matrix cores.  Lanes q == 0 of the first
+        // wavefront of the tile build the features of node c; the tile's wavefronts then share the hidden units.
+        static_assert(sizeof(half_t) * 2 * ROWS * kTq4Row >= sizeof(float) * (64 * ROWS + 4 * 16 * kMlpFeat),
+                      "the features must fit behind the logits");
+        float *F = Zl + 64 * ROWS + nt_w * 16 * kMlpFeat;
+        const int n = nt_w * 16 + c;  // node within the tree
         const size_t gn = (size_t)g * N + n;
-        float a = 0.f;
-        if (lane < K) {
-            int col = cols_lds[n * K + lane];
-            col = (col >= 0 && col < ROWS) ? col : 0;
-            a = Zl[n * ROWS + col];
-        }
-        const bool bad = overflow || bad_lds[n] != 0;
-        const float r = 1.0f / sqrtf(ssq_lds[n] / (float)d + p.eps);
-        float z[KC], prev[KC];
+        bool poisoned = false;
+        float z[KC], pr[KC];
+        if (q == 0 && kh == 0) {
+            const float r = 1.0f / sqrtf(ssq_lds[n] / (float)d + p.eps);
+            const bool bad = overflow || (n < N && bad_lds[n] != 0);
 #pragma unroll
-        for (int k = 0; k < KC; ++k) {
-            const float v = __shfl(a, k < K ? k : 0, kWave);
-            z[k] = (k < K) ? (bad ? quiet_nan() : v * r) : 0.f;
-            prev[k] = (k < K) ? prev_lds[n * K + k] : 0.f;
+            for (int k = 0; k < KC; ++k) {
+                float v = 0.f;
+                if (k < K && n < N) {
+                    int col = cols_lds[n * K + k];
+                    col = (col >= 0 && col < ROWS) ? col : 0;
+                    v = bad ? quiet_nan() : Zl[n * ROWS + col] * r;
+                }
+                z[k] = v;
+            }
+            local_softmax<KC>(z, K, pr);
+            poisoned = bad;
+#pragma unroll
+            for (int k = 0; k < KC; ++k)
+                if (k < K) {
+                    const float pv = n < N ? prev_lds[n * K + k] : 0.f;
+                    F[c * kMlpFeat + k] = z[k];
+                    F[c * kMlpFeat + K + k] = pr[k];
+                    F[c * kMlpFeat + 2 * K + k] = pr[k] - pv;
+                }
+            for (int t = 3 * K; t < kMlpFeat; ++t) F[c * kMlpFeat + t] = 0.f;
         }
-        const int ex = finish_score_node<KC>(fr, f, gn, z, prev, lane);
-        if (lane == kWave - 1) exit_lds[n] = ex;
+        __syncthreads();
+        const int htiles = f.H >> 4;
+        const bool split = kTq4Kh == 2 && (htiles & 7) == 0;  // uniform over the workgroup
+        const int per = split ? htiles >> 1 : htiles;
+        float u = 0.f;
+        if (kh == 0 || split) u = mlp_mfma_16<false>(F, f, lane, split ? kh * per : 0, per);
+        if (split) {
+            if (kh == 1 && q == 0) ssq_lds[n] = u;  // (the sums of squares were consumed before the barrier above)
+            __syncthreads();
+            if (kh == 0) u += ssq_lds[n];
+        }
+        if (q == 0 && kh == 0 && n < N) {
+            float sc = sigmoidf((f.b2 ? (float)b2_r : 0.f) + u);
+            if (poisoned) sc = quiet_nan();
+            const int ex = (sc > f.threshold) ? 1 : 0;
+            f.scores[gn] = sc;
+            f.exit_flags[gn] = ex;
+            exit_lds[n] = ex;
+#pragma unroll
+            for (int k = 0; k < KC; ++k)
+                if (k < K) {
+                    f.logits[gn * K + k] = z[k];
+                    f.probs[gn * K + k] = pr[k];
+                }
+        }
+    } else {
+        FinishRows<KC> fr;
+        finish_load_rows<KC>(fr, f, lane);
+        for (int n = wave; n < N; n += kTq4Waves) {
+            const size_t gn = (size_t)g * N + n;
+            float a = 0.f;
+            if (lane < K) {
+                int col = cols_lds[n * K + lane];
+                col = (col >= 0 && col < ROWS) ? col : 0;
+                a = Zl[n * ROWS + col];
+            }
+            const bool bad = overflow || bad_lds[n] != 0;
+            const float r = 1.0f / sqrtf(ssq_lds[n] / (float)d + p.eps);
+            float z[KC], prev[KC];
+    #pragma unroll
+            for (int k = 0; k < KC; ++k) {
+                const float v = __shfl(a, k < K ? k : 0, kWave);
+                z[k] = (k < K) ? (bad ? quiet_nan() : v * r) : 0.f;
+                prev[k] = (k < K) ? prev_lds[n * K + k] : 0.f;
+            }
+            const int ex = finish_score_node<KC>(fr, f, gn, z, prev, lane);
+            if (lane == kWave - 1) exit_lds[n] = ex;
+        }
     }
     if (f.path_exit) {
         __syncthreads();
