@@ -12,7 +12,7 @@
 // codes, so a tree reads its hidden states (N * 2d bytes) and an eighth as many row bytes as on the fp16
 // head; the rows' scales and zero-points (4 * d / group bytes each) are staged in LDS once.
 //
-// Layout per 128-element stage: the row tile [16 * MT rows][128] is expanded from codes to fp16 in
+// Layout per stage of KCH elements: the row tile [16 * MT rows][KCH] is expanded from codes to fp16 in
 // registers (0x6400 | c is the half 1024 + c) and written to double-buffered LDS; k-step j of a stage
 // covers elements 32j .. 32j+31 (lane group q takes 8 consecutive ones), so a quantisation group --
 // a multiple of 32 elements -- ends on a k-step boundary.  Within a k-step the eight elements of a lane
@@ -34,8 +34,16 @@ namespace specee {
 constexpr int kTq4Threads = 512;
 constexpr int kTq4Waves = kTq4Threads / kWave;
 constexpr int kTq4Kh = kTq4Threads / 256;           // wavefronts per node tile
-constexpr int kTq4Kch = 128;                        // elements per stage
-constexpr int kTq4Row = kTq4Kch + 8;                // halves per LDS row
+// Elements per stage: 256 with four row tiles, 128 with eight (the double-buffered row tiles of 256 would not
+// leave room for the scales).  A stage costs about 0.3 us of barrier and LDS turn-around on top of its
+// streaming, so the longer stage is worth a tenth of the loop.
+constexpr size_t kTq4LdsBudget = 150 * 1024;
+static size_t tq4_lds_bytes(int d, int rows, int group, int kch) {
+    return sizeof(half_t) * ((size_t)2 * rows * (kch + 8) + (size_t)2 * (d / group) * rows + (size_t)d);
+}
+static int tq4_kch(int d, int rows, int group) {
+    return rows <= 64 && tq4_lds_bytes(d, rows, group, 256) <= kTq4LdsBudget ? 256 : 128;
+}
 constexpr int kTq4MaxIds = 1024;                    // ids per tree (N * K)
 
 // eight codes of a word as halves, in the order (0,4,1,5,2,6,3,7)
@@ -51,10 +59,12 @@ __device__ __forceinline__ half8 codes_to_half8(uint32_t w) {
     return out;
 }
 
-// MT: row tiles of 16 merged rows (Mcap <= 16 * MT).  KC: as in the other predictor kernels.
-template <int MT, int KC>
+// MT: row tiles of 16 merged rows (Mcap <= 16 * MT).  KC: as in the other predictor kernels.  KCH: elements per stage.
+template <int MT, int KC, int KCH>
 __global__ __launch_bounds__(kTq4Threads) void tree_q4_kernel(TreeQ4Params p, TreeFinishParams f) {
     constexpr int ROWS = 16 * MT;
+    constexpr int kTq4Kch = KCH;
+    constexpr int kTq4Row = kTq4Kch + 8;  // halves per LDS row
     constexpr int JN = kTq4Kch / 32 / kTq4Kh;             // k-steps per stage and wavefront
     constexpr int CPT = ROWS * (kTq4Kch / 16) / kTq4Threads;  // 8-byte code chunks (16 elements) per thread per stage
     extern __shared__ __attribute__((aligned(16))) half_t q4_smem[];
@@ -447,18 +457,18 @@ __global__ __launch_bounds__(kTq4Threads) void tree_q4_kernel(TreeQ4Params p, Tr
 
 bool tree_q4_supported(int d, int N, int K, int Mcap, int group) {
     if (N > 64 || N * K > kTq4MaxIds || Mcap > 128 || group % 32 != 0 || d % group != 0) return false;
-    return tree_q4_lds_bytes(d, Mcap, group) <= 150 * 1024;
+    return tree_q4_lds_bytes(d, Mcap, group) <= kTq4LdsBudget;
 }
 
 size_t tree_q4_lds_bytes(int d, int Mcap, int group) {
     const int rows = Mcap <= 64 ? 64 : 128;
-    return sizeof(half_t) * ((size_t)2 * rows * kTq4Row + (size_t)2 * (d / group) * rows + (size_t)d);
+    return tq4_lds_bytes(d, rows, group, tq4_kch(d, rows, group));
 }
 
-template <int MT, int KC>
+template <int MT, int KC, int KCH>
 static hipError_t launch_tq4(const TreeQ4Params &p, const TreeFinishParams &f, int G, hipStream_t st) {
-    const size_t lds = tree_q4_lds_bytes(p.d, p.Mcap, p.group);
-    auto kern = tree_q4_kernel<MT, KC>;
+    const size_t lds = tq4_lds_bytes(p.d, 16 * MT, p.group, KCH);
+    auto kern = tree_q4_kernel<MT, KC, KCH>;
     if (lds > 48 * 1024)  // per launch: the library keeps no state; a refusal shows as the launch error
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                   (int)lds);
@@ -466,11 +476,16 @@ static hipError_t launch_tq4(const TreeQ4Params &p, const TreeFinishParams &f, i
     return hipGetLastError();
 }
 
+template <int KC>
+static hipError_t launch_tq4_kc(const TreeQ4Params &p, const TreeFinishParams &f, int G, hipStream_t st) {
+    if (p.Mcap > 64) return launch_tq4<8, KC, 128>(p, f, G, st);
+    return tq4_kch(p.d, 64, p.group) == 256 ? launch_tq4<4, KC, 256>(p, f, G, st) : launch_tq4<4, KC, 128>(p, f, G, st);
+}
+
 hipError_t launch_tree_q4(const TreeQ4Params &p, const TreeFinishParams &f, int G, hipStream_t st) {
-    const bool wide = p.Mcap > 64;
-    if (f.K <= 4) return wide ? launch_tq4<8, 4>(p, f, G, st) : launch_tq4<4, 4>(p, f, G, st);
-    if (f.K <= 8) return wide ? launch_tq4<8, 8>(p, f, G, st) : launch_tq4<4, 8>(p, f, G, st);
-    return wide ? launch_tq4<8, 16>(p, f, G, st) : launch_tq4<4, 16>(p, f, G, st);
+    if (f.K <= 4) return launch_tq4_kc<4>(p, f, G, st);
+    if (f.K <= 8) return launch_tq4_kc<8>(p, f, G, st);
+    return launch_tq4_kc<16>(p, f, G, st);
 }
 
 }  // namespace specee

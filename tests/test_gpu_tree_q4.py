@@ -69,6 +69,8 @@ def ref(oracle, t, Mcap, parent="auto"):
     (4096, 2000, 4, 512, 60, 9, 128, 64, False),  # the 7B tree shape on a small vocabulary
     (64, 40, 16, 8, 5, 2, 32, 40, True),          # K = KMAX, tiny
     (32, 9, 1, 1, 1, 1, 32, 1, False),            # smallest legal tree
+    (10240, 64, 4, 64, 20, 2, 32, 64, True),      # so many groups that the scales leave room for the short stage only
+    (1280, 300, 8, 128, 33, 3, 320, 64, False),   # group neither a power of two nor a divisor of the stage
 ])
 def test_tree_q4_shapes(sp, oracle, d, V, K, H, N, G, group, Mcap, bias):
     t = make(d + N + K, d, V, K, H, N, G, group, min(Mcap, V), bias)
