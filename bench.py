@@ -599,7 +599,13 @@ def main():
         byts = c4.L * c4.B * c4.d * 2 + nrows * c4.d * 2 + c4.d * 2 + c4.L * (3 * c4.K * H + H) * 2
         extra["c4_13b_one_launch_sweep"] = {"us_per_launch": us, **spread(), "evals_per_s": c4.L * c4.B / us * 1e6,
                                             "algorithmic_bytes": byts, "achieved_GBps": byts / us / 1e3,
-                                            "frac_of_8TBps": byts / us / 1e3 / HBM_PEAK_GBS}
+                                            "frac_of_8TBps": byts / us / 1e3 / HBM_PEAK_GBS,
+                                            "distinct_rows": int(nrows), "row_reads": int(c4.L * c4.B * c4.K),
+                                            "path": "specee_predict_sweep, one workgroup per (layer, token); the "
+                                                    "distinct rows cross the fabric once and their repeats over "
+                                                    "layers and tokens are served by L2 (no de-duplication pass)"}
+        extra["c4_13b_16seq_per_layer_calls"]["path"] = ("specee_predict per layer, one workgroup per token; rows "
+                                                         "repeated within a layer served by L2")
         del lm4, T4
         torch.cuda.empty_cache()
         lm = None
