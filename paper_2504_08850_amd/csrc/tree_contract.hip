@@ -159,6 +159,16 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
         if (tid < 64) bad_lds[tid] = 0;
     }
 
+    // The first stages of hidden states go out once the ids (and the other prologue loads, requested with them)
+    // have come back: not before -- every workgroup's hidden-state burst ahead of its ids delays the ids -- but
+    // before the merge, so that they stream in while it computes and only the rows remain to be waited for after it.
+    if (FUSED && MODE == 3) {
+        __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int u = 0; u < PD; ++u) issue_b(u, u);
+    }
+
     // ---- merged rows
     int M, Mtrue = 0;
     int32_t *uniq = nullptr;
@@ -220,7 +230,7 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     };
 #pragma unroll
     for (int u = 0; u < PD; ++u) {  // in the order the stages need them
-        if (u >= PD0) issue_b(u, u);
+        if (u >= PD0 && !(FUSED && MODE == 3)) issue_b(u, u);
         issue_a(u, u, all_slices{});
     }
 

@@ -124,6 +124,32 @@ __global__ __launch_bounds__(kTq4Threads) void tree_q4_kernel(TreeQ4Params p, Tr
         *reinterpret_cast<half8 *>(&gam_lds[v * 8]) = gp;
     }
 
+    // ---- the first stages of hidden states go out once the ids (and the other prologue loads) have come back --
+    // not before: every workgroup's burst of them ahead of its ids delays the ids -- and before the merge, so that
+    // they stream in while it computes
+    const int kq = 32 * kh * JN + 8 * q;  // this lane's first element within a stage
+    constexpr int PD = 2;                 // stages in flight
+    static_assert(PD % 2 == 0, "the LDS buffer of a stage is its slot's parity");
+    half8 h_buf[PD][JN];
+    // TAIL: the stage may reach past the end of the rows: loads are clamped into the row (and masked when
+    // consumed); a full stage needs neither
+    auto issue_hidden = [&](auto tail_c, int kc, int slot) {
+        constexpr bool TAIL = decltype(tail_c)::value;
+#pragma unroll
+        for (int j = 0; j < JN; ++j) {
+            const int ko = TAIL ? min(kc * kTq4Kch + kq + 32 * j, d - 8) : kc * kTq4Kch + kq + 32 * j;
+            h_buf[slot][j] = load_half8(hrow + ko);
+        }
+    };
+    const int nfull = d / kTq4Kch;  // stages that lie wholly inside the rows
+    __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int u = 0; u < PD; ++u) {
+        if (u < nfull) issue_hidden(std::false_type{}, u, u);
+        else issue_hidden(std::true_type{}, u, u);
+    }
+
     // ---- merge
     int32_t *uniq = nullptr;
     int col_of[kMergePerThread], own_id[kMergePerThread];
@@ -149,32 +175,23 @@ __global__ __launch_bounds__(kTq4Threads) void tree_q4_kernel(TreeQ4Params p, Tr
         if (row < 0 || row >= p.V) row = 0;  // invalid id: the node is reported NaN, nothing is read out of bounds
         crow[i] = p.qweight + (size_t)row * (d >> 3);
     }
-    const int kq = 32 * kh * JN + 8 * q;  // this lane's first element within a stage
-    // stages in flight
-    constexpr int PD = 2;
-    static_assert(PD % 2 == 0, "the LDS buffer of a stage is its slot's parity");
     uint2 a_buf[PD][CPT];
-    half8 h_buf[PD][JN];
-    // TAIL: the stage may reach past the end of the rows: loads are clamped into the row (and masked when
-    // consumed); a full stage needs neither
-    auto issue = [&](auto tail_c, int kc, int slot) {
+    auto issue_codes = [&](auto tail_c, int kc, int slot) {
         constexpr bool TAIL = decltype(tail_c)::value;
 #pragma unroll
         for (int i = 0; i < CPT; ++i) {
             const int ko = TAIL ? min(kc * kTq4Kch + c_v[i] * 16, d - 16) : kc * kTq4Kch + c_v[i] * 16;
             a_buf[slot][i] = *reinterpret_cast<const uint2 *>(crow[i] + (ko >> 3));
         }
-#pragma unroll
-        for (int j = 0; j < JN; ++j) {
-            const int ko = TAIL ? min(kc * kTq4Kch + kq + 32 * j, d - 8) : kc * kTq4Kch + kq + 32 * j;
-            h_buf[slot][j] = load_half8(hrow + ko);
-        }
     };
-    const int nfull = d / kTq4Kch;  // stages that lie wholly inside the rows
+    auto issue = [&](auto tail_c, int kc, int slot) {
+        issue_codes(tail_c, kc, slot);
+        issue_hidden(tail_c, kc, slot);
+    };
 #pragma unroll
-    for (int u = 0; u < PD; ++u) {
-        if (u < nfull) issue(std::false_type{}, u, u);
-        else issue(std::true_type{}, u, u);
+    for (int u = 0; u < PD; ++u) {  // (the hidden states of these stages went out before the merge)
+        if (u < nfull) issue_codes(std::false_type{}, u, u);
+        else issue_codes(std::true_type{}, u, u);
     }
 
     // ---- publish the merge, park what the scoring phase needs, stage the rows' scales and zero-points
