@@ -467,40 +467,44 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
 
     // ---- MODE 3: score the whole tree here
     __syncthreads();  // every wavefront is done with the row tiles: reuse them for the logits
-    float *Zl = reinterpret_cast<float *>(smem);  // [64 nodes][ROWS]
+    float *Zl = reinterpret_cast<float *>(smem);  // [64 nodes][ROWS], the quads of a node's row rotated by the node
+    // (lane c of a wavefront holds node c: with plain rows, whose length is a multiple of the 64 banks, the sixteen
+    // nodes of a 16-byte access would all fall on the same four banks)
+    auto zq = [&](int n, int quad) { return n * ROWS + ((quad + n) & (ROWS / 4 - 1)) * 4; };
+    auto zcell = [&](int n, int col) { return zq(n, col >> 2) + (col & 3); };
     if (KH == 2 && MT == 16) {
         // the two wavefronts of a node tile hold complementary k-shares: add them in a fixed order, through
         // the cells of the logit array that the sum goes to anyway (a separate staging area would not fit)
         if (kh == 1) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
-                *reinterpret_cast<floatx4 *>(&Zl[(nt_w * 16 + c) * ROWS + mt * 16 + q * 4]) = acc[mt];
+                *reinterpret_cast<floatx4 *>(&Zl[zq(nt_w * 16 + c, mt * 4 + q)]) = acc[mt];
             if (q == 0) ssq_lds[nt_w * 16 + c] = ssq;
         }
         __syncthreads();
         if (kh == 0) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
-                acc[mt] += *reinterpret_cast<const floatx4 *>(&Zl[(nt_w * 16 + c) * ROWS + mt * 16 + q * 4]);
+                acc[mt] += *reinterpret_cast<const floatx4 *>(&Zl[zq(nt_w * 16 + c, mt * 4 + q)]);
             ssq += ssq_lds[nt_w * 16 + c];
         }
         __syncthreads();
     } else if (KH == 2) {
         // the two wavefronts of a node tile hold complementary k-shares: add them in a fixed order
-        float *tmp = Zl + 64 * ROWS;  // [4 tiles][64 lanes][MT quads]
+        float *tmp = Zl + 64 * ROWS;  // [4 tiles][MT quads][64 lanes]: a wavefront's 16-byte accesses are contiguous
         static_assert(KH == 1 || MT == 16 || sizeof(half_t) * kALdsHalves >= sizeof(float) * 2 * 64 * ROWS,
                       "room for the second wavefront's accumulators");
         if (kh == 1) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
-                *reinterpret_cast<floatx4 *>(&tmp[((nt_w * 64 + lane) * MT + mt) * 4]) = acc[mt];
+                *reinterpret_cast<floatx4 *>(&tmp[((nt_w * MT + mt) * 64 + lane) * 4]) = acc[mt];
             if (q == 0) ssq_lds[nt_w * 16 + c] = ssq;
         }
         __syncthreads();
         if (kh == 0) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
-                acc[mt] += *reinterpret_cast<const floatx4 *>(&tmp[((nt_w * 64 + lane) * MT + mt) * 4]);
+                acc[mt] += *reinterpret_cast<const floatx4 *>(&tmp[((nt_w * MT + mt) * 64 + lane) * 4]);
             ssq += ssq_lds[nt_w * 16 + c];
         }
         __syncthreads();
@@ -579,7 +583,7 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
     if (kh == 0) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
-            *reinterpret_cast<floatx4 *>(&Zl[(nt_w * 16 + c) * ROWS + mt * 16 + q * 4]) = acc[mt];
+            *reinterpret_cast<floatx4 *>(&Zl[zq(nt_w * 16 + c, mt * 4 + q)]) = acc[mt];
         if (q == 0) ssq_lds[nt_w * 16 + c] = ssq;
     }
     __syncthreads();
@@ -616,7 +620,7 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
             if (slot && n < N) {
                 int col = cols_lds[n * K + k];
                 col = (col >= 0 && col < ROWS) ? col : 0;
-                v = bad ? quiet_nan() : Zl[n * ROWS + col] * r;
+                v = bad ? quiet_nan() : Zl[zcell(n, col)] * r;
             }
             float zm = slot ? v : -INFINITY;  // fmaxf drops NaN; the sums below carry it to every lane
             zm = fmaxf(zm, __shfl_xor(zm, 16, kWave));
@@ -644,7 +648,7 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
                 if (k < K && n < N) {
                     int col = cols_lds[n * K + k];
                     col = (col >= 0 && col < ROWS) ? col : 0;
-                    v = bad ? quiet_nan() : Zl[n * ROWS + col] * r;
+                    v = bad ? quiet_nan() : Zl[zcell(n, col)] * r;
                 }
                 z[k] = v;
             }
@@ -705,7 +709,7 @@ __global__ __launch_bounds__(THREADS) void tree_contract_kernel(GemmParams p, Tr
             if (lane < K) {
                 int col = cols_lds[n * K + lane];
                 col = (col >= 0 && col < ROWS) ? col : 0;
-                a = Zl[n * ROWS + col];
+                a = Zl[zcell(n, col)];
             }
             const bool bad = overflow || bad_lds[n] != 0;
             const float r = 1.0f / sqrtf(ssq_lds[n] / (float)d + p.eps);

@@ -365,18 +365,22 @@ __global__ __launch_bounds__(kTq4Threads) void tree_q4_kernel(TreeQ4Params p, Tr
     // ---- score the tree: the two k-shares of a node tile are added in a fixed order through the logit array
     // itself
     __syncthreads();
-    float *Zl = reinterpret_cast<float *>(q4_smem);  // [64 nodes][ROWS]
+    float *Zl = reinterpret_cast<float *>(q4_smem);  // [64 nodes][ROWS], the quads of a node's row rotated by the node
+    // (lane c holds node c: with plain rows, a multiple of the 64 banks long, the sixteen nodes of a 16-byte access
+    // would all fall on the same four banks)
+    auto zq = [&](int n, int quad) __attribute__((always_inline)) { return n * ROWS + ((quad + n) & (ROWS / 4 - 1)) * 4; };
+    auto zcell = [&](int n, int col) __attribute__((always_inline)) { return zq(n, col >> 2) + (col & 3); };
     if (kh == kTq4Kh - 1) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
-            *reinterpret_cast<floatx4 *>(&Zl[(nt_w * 16 + c) * ROWS + mt * 16 + q * 4]) = acc[mt];
+            *reinterpret_cast<floatx4 *>(&Zl[zq(nt_w * 16 + c, mt * 4 + q)]) = acc[mt];
         if (q == 0) ssq_lds[nt_w * 16 + c] = ssq;
     }
     __syncthreads();
     if (kTq4Kh == 2 && kh == 0) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-            floatx4 *cell = reinterpret_cast<floatx4 *>(&Zl[(nt_w * 16 + c) * ROWS + mt * 16 + q * 4]);
+            floatx4 *cell = reinterpret_cast<floatx4 *>(&Zl[zq(nt_w * 16 + c, mt * 4 + q)]);
             *cell = acc[mt] + *cell;
         }
         if (q == 0) ssq_lds[nt_w * 16 + c] += ssq;
@@ -401,7 +405,7 @@ __global__ __launch_bounds__(kTq4Threads) void tree_q4_kernel(TreeQ4Params p, Tr
                 if (k < K && n < N) {
                     int col = cols_lds[n * K + k];
                     col = (col >= 0 && col < ROWS) ? col : 0;
-                    v = bad ? quiet_nan() : Zl[n * ROWS + col] * r;
+                    v = bad ? quiet_nan() : Zl[zcell(n, col)] * r;
                 }
                 z[k] = v;
             }
@@ -451,7 +455,7 @@ __global__ __launch_bounds__(kTq4Threads) void tree_q4_kernel(TreeQ4Params p, Tr
             if (lane < K) {
                 int col = cols_lds[n * K + lane];
                 col = (col >= 0 && col < ROWS) ? col : 0;
-                a = Zl[n * ROWS + col];
+                a = Zl[zcell(n, col)];
             }
             const bool bad = overflow || bad_lds[n] != 0;
             const float r = 1.0f / sqrtf(ssq_lds[n] / (float)d + p.eps);
