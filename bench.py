@@ -322,6 +322,7 @@ def main():
         tp["B=16384_zipf_ids"] = {"us_per_launch": us, **spread(8), "evals_per_s": B / us * 1e6,
                                   "distinct_rows": int(len(np.unique(ids_h))), "algorithmic_bytes": byts,
                                   "achieved_GBps": byts / us / 1e3, "frac_of_8TBps": byts / us / 1e3 / HBM_PEAK_GBS,
+                                  "traffic": MEASURED_TRAFFIC.get("predict_B16384_zipf"),
                                   "path": "specee_predict, one workgroup per token; repeated rows served by L2"}
         # the same batch through the merged mapping: groups of Ng tokens scored as one "tree" each against the
         # union of their ids (specee_predict_tree without parents), so that a row shared inside a group is read once
@@ -467,7 +468,8 @@ def main():
         head_bytes = V * (row_bytes) + d * 4 + V * 4
         extra["lm_head_gemv_q4_32000x4096"] = {"us_per_call": us, **spread(8), "algorithmic_bytes": head_bytes,
                                                "achieved_GBps": head_bytes / us / 1e3,
-                                               "frac_of_8TBps": head_bytes / us / 1e3 / HBM_PEAK_GBS}
+                                               "frac_of_8TBps": head_bytes / us / 1e3 / HBM_PEAK_GBS,
+                                               "traffic": MEASURED_TRAFFIC.get("lm_head_gemv_q4_7b")}
         vids = up(synth.ids_uniform_distinct(1, K, V, 5))
         vo_q = sp.verify_q4(hid8[:1], gamma, qd, sd, zd, group, vids)
         vws_q = torch.empty(sp.workspace_bytes(sp.OP_VERIFY_Q4, sp.Dims(d, V, K, 1, 1e-5, 0.5), 1), dtype=torch.uint8,
@@ -477,7 +479,8 @@ def main():
         us = ev_time(g.replay, 30, 5) * 1e3 / 8
         extra["specee_verify_q4_32000x4096"] = {"us_per_call": us, **spread(8),
                                                 "achieved_GBps": V * row_bytes / us / 1e3,
-                                                "frac_of_8TBps": V * row_bytes / us / 1e3 / HBM_PEAK_GBS}
+                                                "frac_of_8TBps": V * row_bytes / us / 1e3 / HBM_PEAK_GBS,
+                                                "traffic": MEASURED_TRAFFIC.get("verify_q4_7b")}
         # token trees on the quantised head: 256 trees of the 60-node shape per launch, one workgroup per tree
         c3 = synth.CONFIGS["C3"]
         Gq = 256
@@ -494,7 +497,8 @@ def main():
         bq = Gq * c3.N * d * 2 + sum(len(np.unique(x)) for x in ids_hq) * row_bytes + d * 2 + (3 * K * H + H) * 2
         extra["q4_tree_batch_G256"] = {"us_per_launch": us, **spread(4), "node_evals_per_s": Gq * c3.N / us * 1e6,
                                        "bytes_with_rows_counted_per_tree": bq,
-                                       "frac_of_8TBps_rows_per_tree": bq / us / 1e3 / HBM_PEAK_GBS}
+                                       "frac_of_8TBps_rows_per_tree": bq / us / 1e3 / HBM_PEAK_GBS,
+                                       "traffic": MEASURED_TRAFFIC.get("tree_q4_batch_G256")}
         del hq, iq
         del qd, sd, zd
 
