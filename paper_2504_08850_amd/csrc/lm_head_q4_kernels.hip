@@ -19,26 +19,28 @@ namespace specee {
 
 constexpr int kQ4HeadThreads = 512;
 constexpr int kQ4HeadWaves = kQ4HeadThreads / kWave;
-constexpr int kQ4HeadRows = 4;  // rows in flight per wavefront
+constexpr int kQ4HeadRows = 4;    // rows in flight per wavefront
+constexpr int kQ4HeadChunks = 1;  // 16-byte chunks of each of them
 
-// sum over the 32 elements of one 16-byte chunk of codes of x_i * c_i; x from the LDS planes.
+// sum over the 32 elements of one 16-byte chunk of codes of x_i * c_i.
 // Byte j of word i holds elements 8i+2j (low nibble) and 8i+2j+1 (high): with a = x0 - x1/16 and
-// b = x1/16, x0*lo + x1*hi = a*lo + b*byte, so the high nibbles are never extracted.
+// b = x1/16, x0*lo + x1*hi = a*lo + b*byte, so the high nibbles are never extracted.  The LDS planes hold
+// a and b already (pairs (a, b) in element order: the workgroup transforms x once, after the group sums), so a
+// lane spends two instructions per weight pair-half and holds no derived values: the registers that would keep
+// x, a and b of a chunk alive across the rows in flight were what limited the kernel to two wavefronts per SIMD.
 __device__ __forceinline__ float q4_chunk_dot(const uintx4 w, const floatx4 *xa, const floatx4 *xb, int v0) {
     float pd = 0.f;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const floatx4 lo4 = xa[v0 + i], hi4 = xb[v0 + i];  // elements 0..3 and 4..7 of vector v0 + i
-        const float x[8] = {lo4[0], lo4[1], lo4[2], lo4[3], hi4[0], hi4[1], hi4[2], hi4[3]};
+        const floatx4 lo4 = xa[v0 + i], hi4 = xb[v0 + i];  // (a, b) of element pairs 0,1 and 2,3 of vector v0 + i
+        const float ab[8] = {lo4[0], lo4[1], lo4[2], lo4[3], hi4[0], hi4[1], hi4[2], hi4[3]};
         const uint32_t word = w[i];
         uint32_t lo = word & 0x0f0f0f0fu;
         asm("" : "+v"(lo));  // keeps the mask a mask: the byte selects below then fold into the conversions
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const float b = x[2 * j + 1] * 0.0625f;
-            const float a = x[2 * j] - b;
-            pd += a * (float)((lo >> (8 * j)) & 0xffu);
-            pd += b * (float)((word >> (8 * j)) & 0xffu);
+            pd += ab[2 * j] * (float)((lo >> (8 * j)) & 0xffu);
+            pd += ab[2 * j + 1] * (float)((word >> (8 * j)) & 0xffu);
         }
     }
     return pd;
@@ -48,7 +50,7 @@ __device__ __forceinline__ float q4_chunk_dot(const uintx4 w, const floatx4 *xa,
 // Otherwise a lane owns single words (8 elements, always inside one group since group % 8 == 0).
 // ARGMAX: one arg-max candidate per workgroup and hidden state instead of the V logits.
 template <bool ARGMAX, bool WIDE>
-__global__ __launch_bounds__(kQ4HeadThreads) void lm_head_q4_kernel(int d, int V, float eps, const half_t *hidden,
+__global__ __launch_bounds__(kQ4HeadThreads, 4) void lm_head_q4_kernel(int d, int V, float eps, const half_t *hidden,
                                                                     const half_t *gamma, const uint32_t *qweight,
                                                                     const half_t *scales, const half_t *zeros,
                                                                     int group, float *out, int rows_per_wg,
@@ -98,6 +100,23 @@ __global__ __launch_bounds__(kQ4HeadThreads) void lm_head_q4_kernel(int d, int V
         xs[g] = s;
     }
     __syncthreads();
+    if (WIDE) {
+        // x -> (a, b) in place, every thread on the vectors it wrote above
+        for (int v = tid; v < nv; v += kQ4HeadThreads) {
+            floatx4 a = xa[v], b = xb[v];
+#pragma unroll
+            for (int e = 0; e < 4; e += 2) {
+                const float b0 = a[e + 1] * 0.0625f, b1 = b[e + 1] * 0.0625f;
+                a[e] -= b0;
+                a[e + 1] = b0;
+                b[e] -= b1;
+                b[e + 1] = b1;
+            }
+            xa[v] = a;
+            xb[v] = b;
+        }
+        __syncthreads();
+    }
 
     const int row_begin = blockIdx.x * rows_per_wg;
     const int row_end = min(V, row_begin + rows_per_wg);
@@ -119,12 +138,13 @@ __global__ __launch_bounds__(kQ4HeadThreads) void lm_head_q4_kernel(int d, int V
         for (int q = 0; q < R; ++q) acc[q] = 0.f;
         if (WIDE) {
             const int nc = d >> 5;
-            for (int c0 = lane; c0 < nc; c0 += 2 * kWave) {  // two chunks per row in flight, clamped and masked
-                uintx4 w[R][2];
-                half_t sc[R][2];
-                int cc[2];
+            constexpr int U = kQ4HeadChunks;  // chunks per row in flight, clamped and masked
+            for (int c0 = lane; c0 < nc; c0 += U * kWave) {
+                uintx4 w[R][U];
+                half_t sc[R][U];
+                int cc[U];
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
+                for (int u = 0; u < U; ++u) {
                     cc[u] = min(c0 + u * kWave, nc - 1);
                     const int gi = (cc[u] * 32) / group;
 #pragma unroll
@@ -134,7 +154,7 @@ __global__ __launch_bounds__(kQ4HeadThreads) void lm_head_q4_kernel(int d, int V
                     }
                 }
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
+                for (int u = 0; u < U; ++u) {
                     const bool in = c0 + u * kWave < nc;
 #pragma unroll
                     for (int q = 0; q < R; ++q) {
