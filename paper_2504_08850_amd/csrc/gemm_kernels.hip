@@ -38,7 +38,8 @@ constexpr int kLdsRow = kKC + 8;  // halves per LDS row: 144 bytes, keeps 16-byt
 // branches (loads past the end are issued on clamped addresses and contribute zeros): a load
 // under a branch makes the compiler drain every outstanding load at the join.
 template <int TPW, int MODE, int PD>
-__global__ __launch_bounds__(kGemmThreads) void full_head_gemm_kernel(GemmParams p) {
+// (two wavefronts per SIMD asked for: unbounded, the 256-row shape took 272 registers, i.e. one workgroup per CU)
+__global__ __launch_bounds__(kGemmThreads, 2) void full_head_gemm_kernel(GemmParams p) {
     __shared__ __attribute__((aligned(16))) half_t lds_hi[2][kNB][kLdsRow];
     __shared__ __attribute__((aligned(16))) half_t lds_lo[2][kNB][kLdsRow];
     __shared__ float lds_ssq[kNB];
