@@ -213,7 +213,14 @@ def main():
                 gs[it[0] % len(gs)].replay()
                 it[0] += 1
             ms = ev_time(rot, 400, 40)
-            extra["c2_one_launch_sweep"] = {"us_per_sweep": ms * 1e3, "evals_per_s": L / (ms * 1e-3), **spread()}
+            extra["c2_one_launch_sweep"] = {"us_per_sweep": ms * 1e3, "evals_per_s": L / (ms * 1e-3), **spread(),
+                                            "note": "one graph launch per sweep: includes the host's launch of the graph"}
+            # the same sweeps back to back inside one graph (no host launch between them)
+            nb = min(R, 16)
+            gb = capture(lambda: [sp.predict_sweep(sets[r][0], gamma, lm, sets[r][1], W1, w2, out=so) for r in range(nb)])
+            msb = ev_time(gb.replay, 50, 5) / nb
+            extra["c2_one_launch_sweep"]["us_per_sweep_back_to_back"] = msb * 1e3
+            extra["c2_one_launch_sweep"]["back_to_back_spread"] = spread(nb)
 
     # ------------------------------------------------------------------ C1: isolated single call, cold vs warm
     if want("single") and not args.no_extra:
@@ -600,10 +607,18 @@ def main():
         so = sp.predict_sweep(T4["hidden"], T4["gamma"], lm4, T4["ids"], T4["W1"], T4["w2"])
         g = capture(lambda: sp.predict_sweep(T4["hidden"], T4["gamma"], lm4, T4["ids"], T4["W1"], T4["w2"], out=so))
         us = ev_time(g.replay, 100, 10) * 1e3
+        sweep_spread = spread()
+        g8 = capture(lambda: [sp.predict_sweep(T4["hidden"], T4["gamma"], lm4, T4["ids"], T4["W1"], T4["w2"], out=so)
+                              for _ in range(8)])
+        us_b2b = ev_time(g8.replay, 50, 5) * 1e3 / 8
         byts = c4.L * c4.B * c4.d * 2 + nrows * c4.d * 2 + c4.d * 2 + c4.L * (3 * c4.K * H + H) * 2
-        extra["c4_13b_one_launch_sweep"] = {"us_per_launch": us, **spread(), "evals_per_s": c4.L * c4.B / us * 1e6,
+        extra["c4_13b_one_launch_sweep"] = {"us_per_launch": us, **sweep_spread, "evals_per_s": c4.L * c4.B / us * 1e6,
                                             "algorithmic_bytes": byts, "achieved_GBps": byts / us / 1e3,
                                             "frac_of_8TBps": byts / us / 1e3 / HBM_PEAK_GBS,
+                                            "us_per_launch_back_to_back": us_b2b,
+                                            "frac_of_8TBps_back_to_back": byts / us_b2b / 1e3 / HBM_PEAK_GBS,
+                                            "note": "us_per_launch is one graph launch per sweep and includes the host's "
+                                                    "launch of the graph; back_to_back is eight sweeps inside one graph",
                                             "distinct_rows": int(nrows), "row_reads": int(c4.L * c4.B * c4.K),
                                             "path": "specee_predict_sweep, one workgroup per (layer, token); the "
                                                     "distinct rows cross the fabric once and their repeats over "
