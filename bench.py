@@ -563,6 +563,12 @@ def main():
         r1["never_fires_us_per_token"] = us
         r1["never_fires_spread"] = spread()
         r1["never_fires_us_per_layer"] = us / L
+        # four tokens' loops back to back inside one graph: the device time without the host's launch of a graph
+        g4 = capture(lambda: [sp.layer_loop(hid_l, gamma, lm, ids_rand, W1, w2, threshold=2.0, out=lo, workspace=lws)
+                              for _ in range(4)])
+        us4 = ev_time(g4.replay, 50, 5) * 1e3 / 4
+        r1["never_fires_back_to_back_us_per_token"] = us4
+        r1["never_fires_back_to_back_us_per_layer"] = us4 / L
         g = one_launch(-1.0, ids_rand)
         us = ev_time(g.replay, 20, 3) * 1e3
         torch.cuda.synchronize()
