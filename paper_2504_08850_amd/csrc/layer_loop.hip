@@ -37,8 +37,9 @@ template <int KC, int VPT, bool EXACT, bool STREAM>
 __global__ __launch_bounds__(kLoopThreads) void layer_loop_kernel(LoopParams p) {
     constexpr bool KEEP = KC * VPT <= 16 && KC <= 8;
     extern __shared__ float4 loop_lds_x[];  // verification: x = h * gamma as two float4 planes, [2][d/8]
-    __shared__ float red[kLoopWaves][KC + 1];
-    __shared__ float red_u[kLoopWaves];
+    __shared__ __attribute__((aligned(16))) float red[KC + 1][kLoopWaves];  // [value][wavefront]: a value's partial
+    __shared__ __attribute__((aligned(16))) float red_u[kLoopWaves];        // sums are two 16-byte reads
+    static_assert(kLoopWaves == 8, "the cross-wavefront sums below read two float4 per value");
     __shared__ float cv[kLoopWaves];
     __shared__ int ci[kLoopWaves];
     __shared__ int met_lds;
@@ -86,6 +87,18 @@ __global__ __launch_bounds__(kLoopThreads) void layer_loop_kernel(LoopParams p) 
             }
     };
     if (KEEP) load_rows();
+    // KEEP: the rows stay for the whole call, so they are kept as floats with the RMSNorm weight folded in
+    // (the product of two halves is exact in fp32): a layer then costs one conversion of its hidden state
+    // and K + 1 FMAs per element instead of twice as many instructions.
+    float wg[KEEP ? KC : 1][KEEP ? VPT : 1][8];
+    if (KEEP) {
+#pragma unroll
+        for (int k = 0; k < KC; ++k)
+#pragma unroll
+            for (int u = 0; u < VPT; ++u)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) wg[KEEP ? k : 0][KEEP ? u : 0][e] = (float)wv[k][u][e] * (float)gv[u][e];
+    }
 
     const int row_begin = min(p.V, w * p.rows_per_wg);
     const int row_end = min(p.V, row_begin + p.rows_per_wg);
@@ -138,29 +151,32 @@ __global__ __launch_bounds__(kLoopThreads) void layer_loop_kernel(LoopParams p) 
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const float hf = (float)hv[u][e];
-                const float x = hf * (float)gv[u][e];
                 ssq += hf * hf;
+                if (KEEP) {
 #pragma unroll
-                for (int k = 0; k < KC; ++k) acc[k] += x * (float)wv[k][u][e];
+                    for (int k = 0; k < KC; ++k) acc[k] += hf * wg[KEEP ? k : 0][KEEP ? u : 0][e];
+                } else {
+                    const float x = hf * (float)gv[u][e];
+#pragma unroll
+                    for (int k = 0; k < KC; ++k) acc[k] += x * (float)wv[k][u][e];
+                }
             }
         ssq = wave_sum_to_last_row(ssq);
 #pragma unroll
         for (int k = 0; k < KC; ++k) acc[k] = wave_sum_to_last_row(acc[k]);
         if (lane == kWave - 1) {
-            red[wave][0] = ssq;
+            red[0][wave] = ssq;
 #pragma unroll
-            for (int k = 0; k < KC; ++k) red[wave][1 + k] = acc[k];
+            for (int k = 0; k < KC; ++k) red[1 + k][wave] = acc[k];
         }
         __syncthreads();
-        ssq = 0.f;
+        auto sum8 = [&](const float *v) {  // wavefront order, as before: ((((((v0 + v1) + v2) + ...
+            const floatx4 a = *reinterpret_cast<const floatx4 *>(v), c4 = *reinterpret_cast<const floatx4 *>(v + 4);
+            return ((((((a[0] + a[1]) + a[2]) + a[3]) + c4[0]) + c4[1]) + c4[2]) + c4[3];
+        };
+        ssq = sum8(red[0]);
 #pragma unroll
-        for (int k = 0; k < KC; ++k) acc[k] = 0.f;
-#pragma unroll
-        for (int q = 0; q < kLoopWaves; ++q) {
-            ssq += red[q][0];
-#pragma unroll
-            for (int k = 0; k < KC; ++k) acc[k] += red[q][1 + k];
-        }
+        for (int k = 0; k < KC; ++k) acc[k] = sum8(red[1 + k]);
         const float r = 1.0f / sqrtf(ssq * (1.0f / (float)d) + p.eps);
         float z[KC], pr[KC];
 #pragma unroll
@@ -171,8 +187,13 @@ __global__ __launch_bounds__(kLoopThreads) void layer_loop_kernel(LoopParams p) 
         if (lane == kWave - 1) red_u[wave] = part;
         __syncthreads();
         float uo = p.b2 ? (float)b2raw : 0.f;
+        {
+            const floatx4 a = *reinterpret_cast<const floatx4 *>(red_u), c4 = *reinterpret_cast<const floatx4 *>(red_u + 4);
 #pragma unroll
-        for (int q = 0; q < kLoopWaves; ++q) uo += red_u[q];
+            for (int q = 0; q < 4; ++q) uo += a[q];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) uo += c4[q];
+        }
         const float sc = sigmoidf(uo);
         const bool fire = sc > p.threshold;  // the same bits in every thread of every workgroup of the group
         if (writer && tid == 0) {
