@@ -343,6 +343,35 @@ def layer_loop(hidden, gamma, lm_head, ids, W1, w2, b1=None, b2=None, prev0=None
                 token=token)
 
 
+def layer_loop_q4(hidden, gamma, qweight, scales, zeros, group, ids, W1, w2, b1=None, b2=None, prev0=None, active=None,
+                  eps=1e-5, threshold=0.5):
+    """layer_loop on the 4-bit group-quantised LM head (format of predict_q4)."""
+    hidden, gamma = _h(hidden), _h(gamma)
+    qweight = np.ascontiguousarray(qweight).view(np.uint32)
+    scales, zeros = _h(scales), _h(zeros)
+    ids, prev0, active = _i(ids), _f(prev0), _i(active)
+    W1, w2, b1, b2 = _h(W1), _h(w2), _h(b1), _h(b2)
+    L, B, d = hidden.shape
+    V = qweight.shape[0]
+    K = ids.shape[1]
+    H = w2.shape[1]
+    assert qweight.shape == (V, d // 8) and scales.shape == (V, d // group) and zeros.shape == scales.shape
+    assert W1.shape == (L, H, 3 * K) and w2.shape == (L, H) and ids.shape == (B, K)
+    logits = np.zeros((L, B, K)); probs = np.zeros((L, B, K)); scores = np.zeros((L, B))
+    ex = np.zeros((L, B), dtype=np.int32); vt = np.zeros((L, B), dtype=np.int32); hit = np.zeros((L, B), dtype=np.int32)
+    exit_layer = np.zeros(B, dtype=np.int32); token = np.zeros(B, dtype=np.int32)
+    u16, u32, i32, f32, f64 = C.c_uint16, C.c_uint32, C.c_int32, C.c_float, C.c_double
+    rc = lib().specee_layer_loop_q4_ref(
+        C.c_int(d), C.c_int(V), C.c_int(K), C.c_int(H), C.c_double(eps), C.c_float(threshold),
+        C.c_int(L), C.c_int(B), _p(hidden, u16), _p(gamma, u16), _p(qweight, u32), _p(scales, u16), _p(zeros, u16),
+        C.c_int(group), _p(ids, i32), _p(prev0, f32), _p(W1, u16), _p(b1, u16), _p(w2, u16), _p(b2, u16),
+        _p(active, i32), _p(logits, f64), _p(probs, f64), _p(scores, f64), _p(ex, i32), _p(vt, i32), _p(hit, i32),
+        _p(exit_layer, i32), _p(token, i32))
+    _check(rc, "specee_layer_loop_q4_ref")
+    return dict(logits=logits, probs=probs, scores=scores, exit=ex, ver_token=vt, hit=hit, exit_layer=exit_layer,
+                token=token)
+
+
 def schedule(exit_layers, L: int, Q: int = 5, radius: int = 2, offline_mask=None):
     exit_layers, offline_mask = _i(exit_layers), _i(offline_mask)
     T = exit_layers.size

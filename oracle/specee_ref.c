@@ -608,6 +608,63 @@ int specee_layer_loop_ref(int d, int V, int K, int H, double eps, float threshol
 }
 
 /*
+ * The early-exit decode loop on the 4-bit group-quantised LM head (Sec. 4.3.3 and 5.3 in the
+ * weight-quantised setting of Sec. 7.1 / 7.3): specee_layer_loop_ref with the predictor and the
+ * verification taken on rows scale * (code - zero).  Same outputs, same not-evaluated values.
+ */
+int specee_layer_loop_q4_ref(int d, int V, int K, int H, double eps, float threshold, int L, int B,
+                             const uint16_t *hidden, const uint16_t *gamma, const uint32_t *qweight,
+                             const uint16_t *scales, const uint16_t *zeros, int group, const int32_t *ids,
+                             const float *prev0, const uint16_t *W1, const uint16_t *b1, const uint16_t *w2,
+                             const uint16_t *b2, const int32_t *active, double *logits, double *probs,
+                             double *scores, int32_t *exit_flags, int32_t *ver_token, int32_t *hit,
+                             int32_t *exit_layer, int32_t *token) {
+    if (check_dims(d, V, K, H, B) || L < 0) return REF_EINVAL;
+    for (size_t i = 0; i < (size_t)L * B * K; ++i) logits[i] = probs[i] = 0.0;
+    for (size_t i = 0; i < (size_t)L * B; ++i) {
+        scores[i] = 0.0;
+        exit_flags[i] = 0;
+        ver_token[i] = -1;
+        hit[i] = 0;
+    }
+    int rc_all = REF_OK;
+#pragma omp parallel for num_threads(g_threads) schedule(dynamic, 1) if (B > 1)
+    for (int b = 0; b < B; ++b) {
+        float carry[64];
+        for (int k = 0; k < K; ++k) carry[k] = prev0 ? prev0[b * K + k] : 0.0f;
+        exit_layer[b] = -1;
+        token[b] = -1;
+        for (int l = 0; l < L; ++l) {
+            if (active && !active[l]) continue;
+            const size_t o = (size_t)l * B + b;
+            int rc = specee_predict_q4_ref(d, V, K, H, eps, threshold, 1, hidden + o * d, gamma, qweight, scales, zeros,
+                                           group, ids + b * K, carry, W1 + (size_t)l * H * 3 * K,
+                                           b1 ? b1 + (size_t)l * H : NULL, w2 + (size_t)l * H, b2 ? b2 + l : NULL,
+                                           logits + o * K, probs + o * K, NULL, scores + o, exit_flags + o);
+            if (rc != REF_OK) {
+                rc_all = rc;
+                break;
+            }
+            for (int k = 0; k < K; ++k) carry[k] = (float)probs[o * K + k];
+            if (!exit_flags[o]) continue;
+            double mx;
+            rc = specee_verify_q4_ref(d, V, K, eps, 1, hidden + o * d, gamma, qweight, scales, zeros, group,
+                                      ids + b * K, ver_token + o, &mx, hit + o);
+            if (rc != REF_OK) {
+                rc_all = rc;
+                break;
+            }
+            if (hit[o]) {
+                exit_layer[b] = l;
+                token[b] = ver_token[o];
+                break;
+            }
+        }
+    }
+    return rc_all;
+}
+
+/*
  * Online scheduling (Sec. 5.3): a circular queue holds the exit layers of the
  * last Q tokens; counter[i] is the number of queued exit layers within
  * `radius` of layer i (itself included).  A layer's predictor is active when

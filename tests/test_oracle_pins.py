@@ -534,6 +534,61 @@ def test_layer_loop_nothing_is_evaluated_after_the_exit_or_on_inactive_layers(or
     assert np.array_equal(first["scores"], got["scores"][3])
 
 
+def loop_case_q4(seed, L=6, B=5, d=32, V=23, K=3, H=16, group=16):
+    """A decode-loop case on a quantised head whose weights fp16 holds exactly (power-of-two scales, integer
+    zero-points), together with that fp16 head."""
+    t = loop_case(seed, L=L, B=B, d=d, V=V, K=K, H=H)
+    rng = np.random.default_rng(seed + 1000)
+    codes = rng.integers(0, 16, size=(V, d)).astype(np.uint32)
+    q = (codes.reshape(V, d // 8, 8) << (4 * np.arange(8, dtype=np.uint32))).sum(axis=2, dtype=np.uint32)
+    scales = (2.0 ** rng.integers(-6, -2, size=(V, d // group))).astype(np.float16)
+    zeros = rng.integers(0, 16, size=(V, d // group)).astype(np.float16)
+    w = f64(scales).repeat(group, axis=1) * (codes.astype(np.float64) - f64(zeros).repeat(group, axis=1))
+    w16 = w.astype(np.float16)
+    assert np.array_equal(f64(w16), w)
+    t["lm_head"] = w16
+    return t, q, scales, zeros, group
+
+
+@pytest.mark.parametrize("threshold", [0.4, -1.0])
+def test_layer_loop_q4_is_the_pinned_loop_on_representable_weights(oracle, threshold):
+    t, q, scales, zeros, group = loop_case_q4(51)
+    t = plant_hits(t, [3, 0, None, 1, 5])
+    got = oracle.layer_loop_q4(t["hidden"], t["gamma"], q, scales, zeros, group, t["ids"], t["W1"], t["w2"], t["b1"],
+                               t["b2"], threshold=threshold)
+    ref = oracle.layer_loop(t["hidden"], t["gamma"], t["lm_head"], t["ids"], t["W1"], t["w2"], t["b1"], t["b2"],
+                            threshold=threshold)
+    lib = numpy_loop(t, threshold)
+    assert np.all(np.abs(ref["scores"][ref["scores"] != 0] - threshold) > 1e-6)
+    for k in ("exit", "ver_token", "hit", "exit_layer", "token"):
+        assert np.array_equal(got[k], ref[k]), k
+        assert np.array_equal(got[k], lib[k]), k
+    for k in ("logits", "probs", "scores"):
+        np.testing.assert_allclose(got[k], ref[k], rtol=1e-10, atol=1e-12)
+    if threshold < 0:
+        assert (got["exit_layer"] >= 0).sum() >= 3 and got["exit_layer"][1] == 0
+
+
+def test_layer_loop_q4_that_never_fires_is_the_chain_of_quantised_predictors(oracle):
+    t, codes, q, scales, zeros, group = q4_case(52, d=64, V=19, K=3, H=16, B=4, group=16)
+    L, B = 5, 4
+    lt = loop_case(52, L=L, B=B, d=64, V=19, K=3, H=16)
+    active = np.array([1, 0, 1, 1, 0], np.int32)
+    got = oracle.layer_loop_q4(lt["hidden"], lt["gamma"], q, scales, zeros, group, lt["ids"], lt["W1"], lt["w2"],
+                               lt["b1"], lt["b2"], active=active, threshold=2.0)
+    carry = np.zeros((B, 3), np.float32)
+    for l in range(L):
+        if not active[l]:
+            assert not got["scores"][l].any() and not got["probs"][l].any()
+            continue
+        one = oracle.predict_q4(lt["hidden"][l], lt["gamma"], q, scales, zeros, group, lt["ids"], carry, lt["W1"][l],
+                                lt["w2"][l], lt["b1"][l], lt["b2"][l:l + 1], threshold=2.0)
+        for k in ("logits", "probs", "scores"):
+            assert np.array_equal(got[k][l], one[k]), (k, l)
+        carry = one["probs"].astype(np.float32)
+    assert np.all(got["exit_layer"] == -1) and np.all(got["ver_token"] == -1) and not got["hit"].any()
+
+
 # ---------------------------------------------------------------- online scheduling
 def test_schedule_constant_exit_layer_closed_form(oracle):
     L, Q, e = 12, 5, 7
