@@ -582,6 +582,31 @@ def main():
         r1["status"] = int(lo["status"][0])
         r1["launches_per_token"] = 2
         extra["layer_loop_one_launch_7b"] = r1
+        # the same loop on the 4-bit group-quantised head (specee_layer_loop_q4)
+        qh_l, sh_l, zh_l = synth.quantize_q4(lm_h, 128)
+        qd_l, sd_l, zd_l = up(qh_l.view(np.int32)), up(sh_l), up(zh_l)
+        ids_q = up(t2["ids"]).clone()
+        lq = sp.layer_loop_q4(hid_l, gamma, qd_l, sd_l, zd_l, 128, ids_q, W1, w2, threshold=2.0)
+        lqws = lq.pop("_workspace")
+
+        def one_launch_q4(threshold, ids_, reps=1):
+            return capture(lambda: [sp.layer_loop_q4(hid_l, gamma, qd_l, sd_l, zd_l, 128, ids_, W1, w2,
+                                                     threshold=threshold, out=lq, workspace=lqws) for _ in range(reps)])
+        rq = {}
+        rq["never_fires_back_to_back_us_per_token"] = ev_time(one_launch_q4(2.0, ids_q, 4).replay, 50, 5) * 1e3 / 4
+        rq["never_fires_back_to_back_us_per_layer"] = rq["never_fires_back_to_back_us_per_token"] / L
+        rq["never_fires_spread"] = spread(4)
+        rq["always_fires_never_hits_us_per_token"] = ev_time(one_launch_q4(-1.0, ids_q).replay, 20, 3) * 1e3
+        torch.cuda.synchronize()
+        rq["always_fires_never_hits_verifications"] = int(lq["exit"].sum())
+        full10q = sp.lm_head_gemv_q4(hid_l[10], gamma, qd_l, sd_l, zd_l, 128)
+        ids_q[0, 0] = int(full10q.argmax())
+        rq["fires_everywhere_accepted_us_per_token"] = ev_time(one_launch_q4(-1.0, ids_q).replay, 50, 5) * 1e3
+        torch.cuda.synchronize()
+        rq["fires_everywhere_accepted_exit_layer"] = int(lq["exit_layer"][0])
+        rq["status"] = int(lq["status"][0])
+        extra["layer_loop_one_launch_q4_7b"] = rq
+        del qd_l, sd_l, zd_l
 
     # ------------------------------------------------------------------ C4: 13B shape, 16 sequences x 40 layers
     if want("c4") and not args.no_extra:

@@ -310,6 +310,23 @@ int specee_layer_loop(const specee_dims *dims, int L, int B, const specee_half *
                       int32_t *token, int32_t *status, long long spin_limit, void *workspace,
                       size_t workspace_bytes, void *stream);
 
+/*
+ * specee_layer_loop on the 4-bit group-quantised LM head of specee_predict_q4 (same
+ * format, same reading): the weight-quantised setting of the paper's cloud
+ * evaluation runs the whole predict -> verify loop on the quantised model
+ * (Sec. 7.1 "Quantization", Sec. 7.3; loop: Sec. 4.3.3, Sec. 5.3).  Arguments,
+ * outputs, status, bounded waits and residency requirements as specee_layer_loop;
+ * the predictor is specee_predict_q4's and the verification specee_verify_q4's.
+ * Limits: d <= 8192, B <= 64, K <= 8; group a multiple of 8 that divides d, qweight
+ * 4-byte aligned.  Workspace: SPECEE_OP_LAYER_LOOP with n = B.
+ */
+int specee_layer_loop_q4(const specee_dims *dims, int L, int B, const specee_half *hidden, const specee_half *gamma,
+                         const uint32_t *qweight, const specee_half *scales, const specee_half *zeros, int group,
+                         const int32_t *ids, const float *prev0, const specee_mlp *mlp /* HOST */,
+                         const int32_t *active, float *logits, float *probs, float *scores, int32_t *exit_flags,
+                         int32_t *ver_token, int32_t *hit, int32_t *exit_layer, int32_t *token, int32_t *status,
+                         long long spin_limit, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Bytes of device workspace `op` needs for n tokens / nodes (Mcap: tree only).
  * Pure host function; 0 means none; (size_t)-1 means invalid arguments. */
 size_t specee_workspace_bytes(int op, const specee_dims *dims, int n, int Mcap);

@@ -41,7 +41,10 @@ struct LoopParams {
     float eps, threshold;
     const half_t *hidden;   // [L][B][d]
     const half_t *gamma;    // [d]
-    const half_t *lm_head;  // [V][d]
+    const half_t *lm_head;  // [V][d] (fp16 head), or null with the quantised head below
+    const uint32_t *qweight;            // [V][d/8] 4-bit codes, or null
+    const half_t *qscales, *qzeros;     // [V][d/group]
+    int group;
     const int32_t *ids;     // [B][K]
     const float *prev0;     // [B][K] or null
     const half_t *W1, *b1, *w2, *b2;  // leading layer dimension L

@@ -23,6 +23,7 @@
 // (another kernel holds the CUs) ends with status 1 instead of hanging.
 #include "device_utils.h"
 #include "head_stream.h"
+#include "q4_head_stream.h"
 #include "kernels.h"
 #include "predictor_tail.h"
 
@@ -33,10 +34,17 @@ constexpr int kLoopWaves = kLoopThreads / kWave;
 
 // KC / EXACT / VPT as in predict_kernel.  KEEP: the K rows stay in registers across layers (up to 64
 // registers of them; wider shapes read their rows again at every layer, from L2).
-template <int KC, int VPT, bool EXACT, bool STREAM>
+// HEAD: 0 = fp16 LM head, 1 = 4-bit group-quantised head read in 16-byte chunks (group % 32 == 0, aligned rows),
+// 2 = quantised head read word by word.  On a quantised head the token's K rows are dequantised once, into
+// the float registers that hold them anyway (with the RMSNorm weight folded in), so the predictor of a layer is
+// the same code; the verification streams the codes (q4_head_rows).  Needs KEEP (K <= 8).
+template <int KC, int VPT, bool EXACT, bool STREAM, int HEAD = 0>
 __global__ __launch_bounds__(kLoopThreads) void layer_loop_kernel(LoopParams p) {
     constexpr bool KEEP = KC * VPT <= 16 && KC <= 8;
+    constexpr bool Q4 = HEAD != 0;
+    static_assert(!Q4 || KEEP, "the quantised head needs the rows kept in registers");
     extern __shared__ float4 loop_lds_x[];  // verification: x = h * gamma as two float4 planes, [2][d/8]
+                                            // (quantised head: then [d/group] per-group sums of x)
     __shared__ __attribute__((aligned(16))) float red[KC + 1][kLoopWaves];  // [value][wavefront]: a value's partial
     __shared__ __attribute__((aligned(16))) float red_u[kLoopWaves];        // sums are two 16-byte reads
     static_assert(kLoopWaves == 8, "the cross-wavefront sums below read two float4 per value");
@@ -68,12 +76,14 @@ __global__ __launch_bounds__(kLoopThreads) void layer_loop_kernel(LoopParams p) 
             if (k < K) prev[k] = p.prev0[(size_t)b * K + k];
     }
     const half_t *rows[KC];
+    size_t rowi[KC];
     bool bad_id = false;
 #pragma unroll
     for (int k = 0; k < KC; ++k) {
         const bool ok = idv[k] >= 0 && idv[k] < p.V;
         if (k < K && !ok) bad_id = true;
-        rows[k] = p.lm_head + (size_t)(ok ? idv[k] : 0) * d;
+        rowi[k] = (size_t)(ok ? idv[k] : 0);
+        rows[k] = Q4 ? nullptr : p.lm_head + rowi[k] * d;
     }
     half8 wv[KC][VPT];
     auto load_rows = [&]() {
@@ -86,18 +96,38 @@ __global__ __launch_bounds__(kLoopThreads) void layer_loop_kernel(LoopParams p) 
                 wv[k][u] = (k < K && v < nv) ? x : zero_half8();
             }
     };
-    if (KEEP) load_rows();
+    if (KEEP && !Q4) load_rows();
     // KEEP: the rows stay for the whole call, so they are kept as floats with the RMSNorm weight folded in
     // (the product of two halves is exact in fp32): a layer then costs one conversion of its hidden state
     // and K + 1 FMAs per element instead of twice as many instructions.
     float wg[KEEP ? KC : 1][KEEP ? VPT : 1][8];
-    if (KEEP) {
+    if (KEEP && !Q4) {
 #pragma unroll
         for (int k = 0; k < KC; ++k)
 #pragma unroll
             for (int u = 0; u < VPT; ++u)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) wg[KEEP ? k : 0][KEEP ? u : 0][e] = (float)wv[k][u][e] * (float)gv[u][e];
+    }
+    if (Q4) {
+        // element e of vector v is the code in bits 4e of word v of the row; its group is (8v) / group
+        const int ng = d / p.group;
+#pragma unroll
+        for (int k = 0; k < KC; ++k)
+#pragma unroll
+            for (int u = 0; u < VPT; ++u) {
+                const int v = tid + u * kLoopThreads;
+                const int vc = min(v, nv - 1);
+                const uint32_t word = p.qweight[rowi[k] * nv + vc];
+                const int gi = (vc * 8) / p.group;
+                const float sc = (float)p.qscales[rowi[k] * ng + gi], zp = (float)p.qzeros[rowi[k] * ng + gi];
+                const bool live = k < K && v < nv;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float wq = sc * ((float)((word >> (4 * e)) & 15u) - zp);
+                    wg[KEEP ? k : 0][KEEP ? u : 0][e] = live ? wq * (float)gv[u][e] : 0.f;
+                }
+            }
     }
 
     const int row_begin = min(p.V, w * p.rows_per_wg);
@@ -236,7 +266,19 @@ __global__ __launch_bounds__(kLoopThreads) void layer_loop_kernel(LoopParams p) 
         __syncthreads();
         float bv = -INFINITY;
         int bi = 0x7fffffff;
-        head_argmax_rows<STREAM>(p.lm_head, d, row_begin, row_end, wave, kLoopWaves, lane, xa, xb, r, bv, bi);
+        if (Q4) {
+            float *xs = reinterpret_cast<float *>(xb + nv);
+            q4_prepare_planes<kLoopThreads, HEAD == 1>(xa, xb, xs, nv, d / p.group, p.group, tid);
+            q4_head_rows<HEAD == 1>(p.qweight, p.qscales, p.qzeros, d, p.group, row_begin, row_end, wave, kLoopWaves, lane,
+                                    xa, xb, xs, r, [&](int row, float v) {
+                                        if (v > bv) {  // rows ascend: the strict comparison keeps the lowest row
+                                            bv = v;
+                                            bi = row;
+                                        }
+                                    });
+        } else {
+            head_argmax_rows<STREAM>(p.lm_head, d, row_begin, row_end, wave, kLoopWaves, lane, xa, xb, r, bv, bi);
+        }
         if (lane == 0) {
             cv[wave] = bv;
             ci[wave] = bi;
@@ -343,11 +385,36 @@ __global__ __launch_bounds__(kLoopThreads) void layer_loop_kernel(LoopParams p) 
     }
 }
 
+// An empty layer stack: every token runs "the whole stack" without an exit.  No input is touched.
+__global__ void layer_loop_empty_kernel(int32_t *exit_layer, int32_t *token, int32_t *status, int B) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < B) {
+        exit_layer[b] = -1;
+        token[b] = -1;
+        status[b] = 0;
+    }
+}
+
 template <int KC, int VPT, bool EXACT>
 static hipError_t launch_loop_one(LoopParams p, int max_wgs, hipStream_t s) {
     const bool stream = head_streams(p.d, p.V);
-    auto kern = stream ? layer_loop_kernel<KC, VPT, EXACT, true> : layer_loop_kernel<KC, VPT, EXACT, false>;
-    const size_t lds = (size_t)p.d * sizeof(float);
+    constexpr bool kCanQ4 = KC * VPT <= 16 && KC <= 8;
+    void (*kern)(LoopParams) = stream ? layer_loop_kernel<KC, VPT, EXACT, true> : layer_loop_kernel<KC, VPT, EXACT, false>;
+    size_t lds = (size_t)p.d * sizeof(float);
+    int quantum = kLoopWaves * kHeadRows;
+    if (p.qweight) {
+        if constexpr (kCanQ4) {
+            const bool wide = p.group % 32 == 0 && p.d % 32 == 0 && (reinterpret_cast<uintptr_t>(p.qweight) & 15) == 0;
+            kern = wide ? layer_loop_kernel<KC, VPT, EXACT, false, 1> : layer_loop_kernel<KC, VPT, EXACT, false, 2>;
+            lds += (size_t)(p.d / p.group) * sizeof(float);
+            quantum = kLoopWaves * kQ4HeadRows;
+        } else {
+            return hipErrorInvalidValue;
+        }
+    }
+    if (lds > 48 * 1024)  // per launch: the library keeps no state; a refusal shows as the launch error
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)lds);
     // every workgroup of a group must be resident while the group meets: size the grid from what the
     // runtime says fits on the device
     int dev = 0, cus = 0, per_cu = 0;
@@ -360,7 +427,6 @@ static hipError_t launch_loop_one(LoopParams p, int max_wgs, hipStream_t s) {
     if (fit > max_wgs) fit = max_wgs;
     const int Pg = (int)(fit / p.B);
     if (Pg < 1) return hipErrorInvalidConfiguration;
-    const int quantum = kLoopWaves * kHeadRows;
     p.rows_per_wg = (((p.V + Pg - 1) / Pg + quantum - 1) / quantum) * quantum;
     hipLaunchKernelGGL(kern, dim3(Pg, p.B), dim3(kLoopThreads), lds, s, p);
     return hipGetLastError();
@@ -375,6 +441,10 @@ static hipError_t launch_loop_vpt(const LoopParams &p, int max_wgs, hipStream_t 
 // d <= 8192 (two 16-byte vectors per thread and row).  max_wgs bounds the grid (the workspace holds two
 // candidates per workgroup).
 hipError_t launch_layer_loop(const LoopParams &p, int max_wgs, hipStream_t s) {
+    if (p.L == 0) {
+        hipLaunchKernelGGL(layer_loop_empty_kernel, dim3(1), dim3(64), 0, s, p.exit_layer, p.token, p.status, p.B);
+        return hipGetLastError();
+    }
     if (p.K == 4) return launch_loop_vpt<4, true>(p, max_wgs, s);
     if (p.K == 8) return launch_loop_vpt<8, true>(p, max_wgs, s);
     if (p.K < 4) return launch_loop_vpt<4, false>(p, max_wgs, s);

@@ -504,20 +504,27 @@ int specee_predict_tree_q4(const specee_dims *dm, int G, int N, int Mcap, const 
     return launch_tree_q4(tp, fp, G, static_cast<hipStream_t>(stream)) == hipSuccess ? SPECEE_OK : SPECEE_EHIP;
 }
 
-int specee_layer_loop(const specee_dims *dm, int L, int B, const specee_half *hidden, const specee_half *gamma,
-                      const specee_half *lm_head, const int32_t *ids, const float *prev0, const specee_mlp *mlp,
-                      const int32_t *active, float *logits, float *probs, float *scores, int32_t *exit_flags,
-                      int32_t *ver_token, int32_t *hit, int32_t *exit_layer, int32_t *token, int32_t *status,
-                      long long spin_limit, void *workspace, size_t workspace_bytes, void *stream) {
+}  // extern "C" (the common body below is internal)
+
+// specee_layer_loop and specee_layer_loop_q4: lm_head, or the quantised head (qweight non-null)
+static int layer_loop_common(const specee_dims *dm, int L, int B, const specee_half *hidden, const specee_half *gamma,
+                             const specee_half *lm_head, const uint32_t *qweight, const specee_half *scales,
+                             const specee_half *zeros, int group, const int32_t *ids, const float *prev0,
+                             const specee_mlp *mlp, const int32_t *active, float *logits, float *probs, float *scores,
+                             int32_t *exit_flags, int32_t *ver_token, int32_t *hit, int32_t *exit_layer,
+                             int32_t *token, int32_t *status, long long spin_limit, void *workspace,
+                             size_t workspace_bytes, void *stream, bool q4) {
     int rc = check_dims(dm, true);
     if (rc) return rc;
     if (dm->d > 8192 || B < 0 || B > kLoopMaxTokens || L < 0 || L > 65535 || spin_limit < 0) return SPECEE_EINVAL;
+    if (q4 && (dm->K > 8 || group < 8 || group % 8 != 0 || dm->d % group != 0)) return SPECEE_EINVAL;
     if (B == 0) return SPECEE_OK;
     if (L > 0 && (rc = check_mlp(mlp))) return rc;
     if (!exit_layer || !token || !status) return SPECEE_EINVAL;
-    if (L > 0 && (!hidden || !gamma || !lm_head || !ids || !logits || !probs || !scores || !exit_flags || !ver_token ||
-                  !hit))
+    if (L > 0 && (!hidden || !gamma || !ids || !logits || !probs || !scores || !exit_flags || !ver_token || !hit))
         return SPECEE_EINVAL;
+    if (L > 0 && !q4 && !lm_head) return SPECEE_EINVAL;
+    if (L > 0 && q4 && (rc = check_q4(dm, qweight, scales, zeros, group))) return rc;
     if (misaligned(hidden) || misaligned(gamma) || misaligned(lm_head) || misaligned(workspace)) return SPECEE_EALIGN;
     const LoopLayout lay = loop_layout(B);
     if (!workspace || workspace_bytes < lay.total) return SPECEE_EWORKSPACE;
@@ -525,7 +532,10 @@ int specee_layer_loop(const specee_dims *dm, int L, int B, const specee_half *hi
     LoopParams p{};
     p.d = dm->d; p.V = dm->V; p.K = dm->K; p.H = dm->H; p.L = L; p.B = B;
     p.eps = dm->eps; p.threshold = dm->threshold;
-    p.hidden = H(hidden); p.gamma = H(gamma); p.lm_head = H(lm_head); p.ids = ids; p.prev0 = prev0;
+    p.hidden = H(hidden); p.gamma = H(gamma); p.lm_head = q4 ? nullptr : H(lm_head); p.ids = ids; p.prev0 = prev0;
+    if (q4) {
+        p.qweight = qweight; p.qscales = H(scales); p.qzeros = H(zeros); p.group = group;
+    }
     if (mlp) {
         p.W1 = H(mlp->W1); p.b1 = H(mlp->b1); p.w2 = H(mlp->w2); p.b2 = H(mlp->b2);
     }
@@ -538,9 +548,33 @@ int specee_layer_loop(const specee_dims *dm, int L, int B, const specee_half *hi
     p.cand_idx = reinterpret_cast<int32_t *>(ws + lay.idx_off);
     p.spin_limit = spin_limit > 0 ? spin_limit : (1ll << 20);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (launch_zero_i32(p.arrive, lay.flag_ints, st) != hipSuccess) return SPECEE_EHIP;
+    // (an empty stack is handled by the launcher without touching any input: they may all be null then)
+    if (L > 0 && launch_zero_i32(p.arrive, lay.flag_ints, st) != hipSuccess) return SPECEE_EHIP;
     // the launcher caps the grid at kLoopMaxWgs workgroups; each candidate buffer holds one entry per workgroup
     return launch_layer_loop(p, kLoopMaxWgs, st) == hipSuccess ? SPECEE_OK : SPECEE_EHIP;
+}
+
+extern "C" {
+
+int specee_layer_loop(const specee_dims *dm, int L, int B, const specee_half *hidden, const specee_half *gamma,
+                      const specee_half *lm_head, const int32_t *ids, const float *prev0, const specee_mlp *mlp,
+                      const int32_t *active, float *logits, float *probs, float *scores, int32_t *exit_flags,
+                      int32_t *ver_token, int32_t *hit, int32_t *exit_layer, int32_t *token, int32_t *status,
+                      long long spin_limit, void *workspace, size_t workspace_bytes, void *stream) {
+    return layer_loop_common(dm, L, B, hidden, gamma, lm_head, nullptr, nullptr, nullptr, 0, ids, prev0, mlp, active,
+                             logits, probs, scores, exit_flags, ver_token, hit, exit_layer, token, status, spin_limit,
+                             workspace, workspace_bytes, stream, false);
+}
+
+int specee_layer_loop_q4(const specee_dims *dm, int L, int B, const specee_half *hidden, const specee_half *gamma,
+                         const uint32_t *qweight, const specee_half *scales, const specee_half *zeros, int group,
+                         const int32_t *ids, const float *prev0, const specee_mlp *mlp, const int32_t *active,
+                         float *logits, float *probs, float *scores, int32_t *exit_flags, int32_t *ver_token,
+                         int32_t *hit, int32_t *exit_layer, int32_t *token, int32_t *status, long long spin_limit,
+                         void *workspace, size_t workspace_bytes, void *stream) {
+    return layer_loop_common(dm, L, B, hidden, gamma, nullptr, qweight, scales, zeros, group, ids, prev0, mlp, active,
+                             logits, probs, scores, exit_flags, ver_token, hit, exit_layer, token, status, spin_limit,
+                             workspace, workspace_bytes, stream, true);
 }
 
 int specee_verify(const specee_dims *dm, int N, const specee_half *hidden, const specee_half *gamma,

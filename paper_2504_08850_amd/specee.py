@@ -206,6 +206,39 @@ def layer_loop(hidden, gamma, lm_head, ids, W1, w2, b1=None, b2=None, prev0=None
     return out
 
 
+def layer_loop_q4(hidden, gamma, qweight, scales, zeros, group, ids, W1, w2, b1=None, b2=None, prev0=None, active=None,
+                  eps=1e-5, threshold=0.5, spin_limit=0, out=None, workspace=None, stream=None):
+    """specee_layer_loop_q4: layer_loop on the 4-bit group-quantised LM head (qweight int32/uint32 [V][d/8])."""
+    L, B, d = hidden.shape
+    V = qweight.shape[0]
+    K = ids.shape[1]
+    H = w2.shape[1]
+    dev = hidden.device
+    assert tuple(qweight.shape) == (V, d // 8) and tuple(scales.shape) == (V, d // group) == tuple(zeros.shape)
+    if out is None:
+        i32, f32 = torch.int32, torch.float32
+        out = dict(logits=torch.empty((L, B, K), dtype=f32, device=dev), probs=torch.empty((L, B, K), dtype=f32, device=dev),
+                   scores=torch.empty((L, B), dtype=f32, device=dev), exit=torch.empty((L, B), dtype=i32, device=dev),
+                   ver_token=torch.empty((L, B), dtype=i32, device=dev), hit=torch.empty((L, B), dtype=i32, device=dev),
+                   exit_layer=torch.empty((B,), dtype=i32, device=dev), token=torch.empty((B,), dtype=i32, device=dev),
+                   status=torch.empty((B,), dtype=i32, device=dev))
+    dims = _dims(d, V, K, H, eps, threshold)
+    mlp = _mlp(W1, w2, b1, b2)
+    workspace, wbytes = _workspace(OP_LAYER_LOOP, dims, B, 0, workspace, dev)
+    f16 = torch.float16
+    rc = lib().specee_layer_loop_q4(C.byref(dims), C.c_int(L), C.c_int(B), _ptr(hidden, f16), _ptr(gamma, f16),
+                                    _ptr(qweight, torch.int32), _ptr(scales, f16), _ptr(zeros, f16), C.c_int(group),
+                                    _ptr(ids, torch.int32), _ptr(prev0, torch.float32), C.byref(mlp),
+                                    _ptr(active, torch.int32), _ptr(out["logits"]), _ptr(out["probs"]),
+                                    _ptr(out["scores"]), _ptr(out["exit"]), _ptr(out["ver_token"]), _ptr(out["hit"]),
+                                    _ptr(out["exit_layer"]), _ptr(out["token"]), _ptr(out["status"]),
+                                    C.c_longlong(int(spin_limit)), _ptr(workspace), wbytes, _stream(stream))
+    if rc:
+        raise SpeceeError("specee_layer_loop_q4", rc)
+    out["_workspace"] = workspace
+    return out
+
+
 def predict_tree(hidden, gamma, lm_head, ids, prev_probs, W1, w2, b1=None, b2=None, parent=None, Mcap=64,
                  eps=1e-5, threshold=0.5, want_path=None, out=None, workspace=None, stream=None):
     """specee_predict_tree: hidden [G][N][d] (or [N][d] for a single tree)."""

@@ -32,6 +32,8 @@ def declared_functions():
 def test_header_declares_the_expected_entry_points():
     names = declared_functions()
     for must in ("specee_predict", "specee_predict_tree", "lm_head_gemv", "specee_predict_sweep", "specee_verify",
+                 "specee_layer_loop", "specee_predict_q4", "lm_head_gemv_q4", "specee_verify_q4",
+                 "specee_predict_tree_q4", "specee_layer_loop_q4", "specee_predict_tree_static", "specee_status_word",
                  "specee_workspace_bytes", "specee_strerror", "specee_version"):
         assert must in names
 

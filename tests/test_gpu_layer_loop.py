@@ -275,6 +275,18 @@ def test_layer_loop_bounded_wait_gives_up_instead_of_hanging(sp, oracle):
     assert np.all(host(out2["status"]) == 0) and np.array_equal(host(out2["exit_layer"]), ref["exit_layer"])
 
 
+def test_layer_loop_empty_stack_touches_no_input(sp):
+    """L = 0: every token "runs the whole stack" (exit layer -1, token -1, status 0); the inputs may be empty."""
+    z = lambda shape, dt: torch.zeros(shape, dtype=dt, device="cuda")
+    f16, i32 = torch.float16, torch.int32
+    d, V, K, H, B = 64, 10, 4, 8, 5
+    out = sp.layer_loop(z((0, B, d), f16), z((d,), f16), z((V, d), f16), z((B, K), i32), z((0, H, 3 * K), f16),
+                        z((0, H), f16))
+    torch.cuda.synchronize()
+    assert host(out["exit_layer"]).tolist() == [-1] * B and host(out["token"]).tolist() == [-1] * B
+    assert host(out["status"]).tolist() == [0] * B
+
+
 def test_layer_loop_argument_errors(sp):
     z = lambda shape, dt: torch.zeros(shape, dtype=dt, device="cuda")
     f16, i32 = torch.float16, torch.int32
