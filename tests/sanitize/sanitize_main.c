@@ -47,6 +47,10 @@ int specee_layer_loop_ref(int, int, int, int, double, float, int, int, const uin
                           const uint16_t *, const int32_t *, const float *, const uint16_t *, const uint16_t *,
                           const uint16_t *, const uint16_t *, const int32_t *, double *, double *, double *, int32_t *,
                           int32_t *, int32_t *, int32_t *, int32_t *);
+int specee_layer_loop_q4_ref(int, int, int, int, double, float, int, int, const uint16_t *, const uint16_t *,
+                             const uint32_t *, const uint16_t *, const uint16_t *, int, const int32_t *, const float *,
+                             const uint16_t *, const uint16_t *, const uint16_t *, const uint16_t *, const int32_t *,
+                             double *, double *, double *, int32_t *, int32_t *, int32_t *, int32_t *, int32_t *);
 int specee_schedule_ref(int, int, int, int, const int32_t *, const int32_t *, int32_t *, int32_t *);
 void specee_ref_set_threads(int);
 
@@ -101,6 +105,8 @@ int main(void) {
                                    logits, probs, scores, ex, first));
     CHECK(specee_layer_loop_ref(d, V, K, H, 1e-5, -1.0f, L, B, hidden, gamma, lm, ids, prev, W1, b1, w2, b2, active,
                                 logits, probs, scores, ex, vt, hit, el, tok));
+    CHECK(specee_layer_loop_q4_ref(d, V, K, H, 1e-5, -1.0f, L, B, hidden, gamma, qw, qs, qz, group, ids, prev, W1, b1,
+                                   w2, b2, active, logits, probs, scores, ex, vt, hit, el, tok));
     int32_t merged[G * Mcap], M[G], cols[G * N * K], texit[G * N], tpath[G * N];
     double Z[G * N * Mcap], tl[G * N * K], tp[G * N * K], ts[G * N];
     CHECK(specee_merge_ref(tids, N * K, merged, Mcap, M, cols));
