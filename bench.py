@@ -581,6 +581,18 @@ def main():
         r1["fires_everywhere_accepted_exit_layer"] = int(lo["exit_layer"][0])
         r1["status"] = int(lo["status"][0])
         r1["launches_per_token"] = 2
+        # sixteen tokens walk the stack in the same launch (a group of 16 workgroups each)
+        B16 = 16
+        hid16 = up(np.concatenate([synth.make("C2", seed=100 + i, lm=np.zeros((1, 1), np.float16))["hidden"]
+                                   for i in range(B16)], axis=1))       # [L][16][d]
+        ids16 = up(synth.ids_uniform_distinct(B16, K, V, 321))
+        l16 = sp.layer_loop(hid16, gamma, lm, ids16, W1, w2, threshold=2.0)
+        w16 = l16.pop("_workspace")
+        g16 = capture(lambda: [sp.layer_loop(hid16, gamma, lm, ids16, W1, w2, threshold=2.0, out=l16, workspace=w16)
+                               for _ in range(4)])
+        us16 = ev_time(g16.replay, 50, 5) * 1e3 / 4
+        r1["sixteen_tokens_never_fires_back_to_back_us"] = us16
+        r1["sixteen_tokens_never_fires_us_per_token_layer"] = us16 / (B16 * L)
         extra["layer_loop_one_launch_7b"] = r1
         # the same loop on the 4-bit group-quantised head (specee_layer_loop_q4)
         qh_l, sh_l, zh_l = synth.quantize_q4(lm_h, 128)
