@@ -593,6 +593,18 @@ def main():
         us16 = ev_time(g16.replay, 50, 5) * 1e3 / 4
         r1["sixteen_tokens_never_fires_back_to_back_us"] = us16
         r1["sixteen_tokens_never_fires_us_per_token_layer"] = us16 / (B16 * L)
+        # the scheduler's active set (Sec. 5.3): the last five tokens left the model at layers 19..24, two layers either
+        # side of each stay active, plus an offline subset of every eighth layer
+        sched = sp.Scheduler(L, Q=5, radius=2, offline_mask=[1 if l % 8 == 0 else 0 for l in range(L)])
+        for e in (22, 19, 24, 21, 22):
+            sched.push(e)
+        act_h = sched.active()
+        act_d = up(np.asarray(act_h, np.int32))
+        ga = capture(lambda: [sp.layer_loop(hid_l, gamma, lm, ids_rand, W1, w2, active=act_d, threshold=2.0, out=lo,
+                                            workspace=lws) for _ in range(4)])
+        usa = ev_time(ga.replay, 50, 5) * 1e3 / 4
+        r1["scheduled_active_layers"] = int(sum(act_h))
+        r1["scheduled_never_fires_back_to_back_us_per_token"] = usa
         extra["layer_loop_one_launch_7b"] = r1
         # the same loop on the 4-bit group-quantised head (specee_layer_loop_q4)
         qh_l, sh_l, zh_l = synth.quantize_q4(lm_h, 128)
