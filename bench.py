@@ -192,7 +192,7 @@ def main():
             "config": {"workload": "C2: 32-layer exit sweep for one token, d=4096 V=32000 K=4, MLP 12->512->1, "
                                    "32 dependent specee_predict launches per step (HIP graph replay), "
                                    f"{R} rotating input sets", "batch": 1, "layers": L},
-            "roofline": {"bound": "hbm", "kernel": "predict_kernel<4,1,false,true>", "achieved": achieved,
+            "roofline": {"bound": "hbm", "kernel": "predict_kernel<4,2,false,true,256,2>", "achieved": achieved,
                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                          "algorithmic_bytes_per_launch": alg,
                          "traffic": MEASURED_TRAFFIC.get("predict_c2"),
