@@ -31,6 +31,14 @@ namespace specee {
 
 constexpr int kLoopThreads = 512;
 constexpr int kLoopWaves = kLoopThreads / kWave;
+struct LoopRare {
+    float *logits, *probs, *scores;
+    int32_t *exit_flags, *ver_token, *hit, *exit_layer, *token, *status;
+    float *cand_val;
+    int32_t *cand_idx, *arrive, *abort;
+    long long spin_limit;
+};
+constexpr int kLoopMaskLds = 1024;  // layers of the active mask kept in LDS (deeper stacks read the rest in place)
 
 // KC / EXACT / VPT as in predict_kernel.  KEEP: the K rows stay in registers across layers (up to 64
 // registers of them; wider shapes read their rows again at every layer, from L2).
@@ -51,6 +59,11 @@ __global__ __launch_bounds__(kLoopThreads) void layer_loop_kernel(LoopParams p) 
     __shared__ float cv[kLoopWaves];
     __shared__ int ci[kLoopWaves];
     __shared__ int met_lds;
+    // Parameters that only the thread that writes outputs or meets the group needs: parked in LDS, because as kernel
+    // arguments they stay in scalar registers for the whole loop, and with two dozen of them the compiler spills
+    // scalars into vector lanes and reloads them in every layer.
+    __shared__ LoopRare rare;
+    __shared__ unsigned char act_lds[kLoopMaskLds];
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
     const int w = blockIdx.x, b = blockIdx.y, Pg = gridDim.x, B = p.B;
@@ -135,10 +148,50 @@ __global__ __launch_bounds__(kLoopThreads) void layer_loop_kernel(LoopParams p) 
     int meetings = 0;       // verifications so far: the arrival counter stands at meetings * Pg afterwards
     int exit_layer = -1, exit_token = -1;
     int status = 0;
+    // The mask is read once.  Up to 128 layers it becomes two 64-bit words in scalar registers (one ballot each), and
+    // the next active layer is a shift and a count of trailing zeros; deeper stacks keep the first kLoopMaskLds
+    // layers of it in LDS.  Scanning it in global memory costs a dependent round trip per inactive layer -- half a
+    // microsecond each, a third of a layer's evaluation.
+    if (threadIdx.x == 0) {
+        rare.logits = p.logits; rare.probs = p.probs; rare.scores = p.scores; rare.exit_flags = p.exit_flags;
+        rare.ver_token = p.ver_token; rare.hit = p.hit; rare.exit_layer = p.exit_layer; rare.token = p.token;
+        rare.status = p.status; rare.cand_val = p.cand_val; rare.cand_idx = p.cand_idx; rare.arrive = p.arrive;
+        rare.abort = p.abort; rare.spin_limit = p.spin_limit;
+    }
+    unsigned long long m0 = ~0ull, m1 = ~0ull;
+    const bool mask_bits = L <= 128;
+    if (p.active) {
+        if (mask_bits) {
+            const int a0 = lane < L ? p.active[lane] : 0, a1 = lane + 64 < L ? p.active[lane + 64] : 0;
+            m0 = __ballot(a0 != 0);
+            m1 = __ballot(a1 != 0);
+        } else {
+            for (int i = tid; i < min(L, kLoopMaskLds); i += kLoopThreads) act_lds[i] = p.active[i] != 0 ? 1 : 0;
+        }
+    }
+    __syncthreads();
+    auto is_active = [&](int q) {
+        if (!p.active) return true;
+        if (mask_bits) return (((q < 64 ? m0 : m1) >> (q & 63)) & 1ull) != 0;
+        // (in a scalar register: a value read from LDS counts as divergent, and the layer index, with every address
+        // derived from it, would move to the vector units)
+        const int a = q < kLoopMaskLds ? (int)act_lds[q] : (int)(p.active[q] != 0);
+        return __builtin_amdgcn_readfirstlane(a) != 0;
+    };
     // first layer from l0 on whose predictor is active (L if none); uniform over the grid
     auto next_active = [&](int l0) {
         int q = l0;
-        while (q < L && p.active && p.active[q] == 0) ++q;
+        if (!p.active || q >= L) return min(q, L);  // (no mask: the compiler keeps a copy of the loop that steps by one)
+        if (mask_bits) {
+            if (q < 64) {
+                const unsigned long long r = m0 >> q;
+                if (r) return min(L, q + (int)__builtin_ctzll(r));
+                q = 64;
+            }
+            const unsigned long long r = q < 128 ? m1 >> (q - 64) : 0ull;
+            return r ? min(L, q + (int)__builtin_ctzll(r)) : L;
+        }
+        while (q < L && !is_active(q)) ++q;
         return q;
     };
     // A layer's inputs -- its hidden state, this thread's predictor row and the output bias -- are requested
@@ -156,11 +209,15 @@ __global__ __launch_bounds__(kLoopThreads) void layer_loop_kernel(LoopParams p) 
         b2_pf = (p.b2 ? p.b2 : p.gamma)[p.b2 ? q : 0];  // always a valid address; masked at use
     };
     int l = next_active(0);
+    int lnext = l < L ? next_active(l + 1) : L;  // known one layer ahead, so that the scan of the mask is never
+                                                 // between a layer's start and the request of the next one's inputs
     int evaluated_upto = -1;  // last layer whose outputs below are final
     if (l < L) prefetch(l);
     while (l < L) {
         const size_t tok = (size_t)l * B + b;
-        const int lnext = next_active(l + 1);
+        // the layer after the next: looked up before this layer's requests go out -- an LDS read behind them would
+        // wait for the scalar load among them too (LDS and scalar memory share a counter), a trip to memory per layer
+        const int lnext2 = lnext < L ? next_active(lnext + 1) : L;
         const half_t *W1 = p.W1 + (size_t)l * H * 3 * K;
         const half_t *w2 = p.w2 + (size_t)l * H;
         const half_t *b1 = p.b1 ? p.b1 + (size_t)l * H : nullptr;
@@ -227,17 +284,17 @@ __global__ __launch_bounds__(kLoopThreads) void layer_loop_kernel(LoopParams p) 
         const float sc = sigmoidf(uo);
         const bool fire = sc > p.threshold;  // the same bits in every thread of every workgroup of the group
         if (writer && tid == 0) {
-            p.scores[tok] = sc;
-            p.exit_flags[tok] = fire ? 1 : 0;
+            rare.scores[tok] = sc;
+            rare.exit_flags[tok] = fire ? 1 : 0;
 #pragma unroll
             for (int k = 0; k < KC; ++k)
                 if (k < K) {
-                    p.logits[tok * K + k] = z[k];
-                    p.probs[tok * K + k] = pr[k];
+                    rare.logits[tok * K + k] = z[k];
+                    rare.probs[tok * K + k] = pr[k];
                 }
             if (!fire) {
-                p.ver_token[tok] = -1;
-                p.hit[tok] = 0;
+                rare.ver_token[tok] = -1;
+                rare.hit[tok] = 0;
             }
         }
 #pragma unroll
@@ -245,6 +302,7 @@ __global__ __launch_bounds__(kLoopThreads) void layer_loop_kernel(LoopParams p) 
         if (!fire) {
             evaluated_upto = l;
             l = lnext;
+            lnext = lnext2;
             continue;
         }
 
@@ -294,21 +352,21 @@ __global__ __launch_bounds__(kLoopThreads) void layer_loop_kernel(LoopParams p) 
                     bv = cv[q];
                     bi = ci[q];
                 }
-            __hip_atomic_store(p.cand_val + cbase + w, bv, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(p.cand_idx + cbase + w, bi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(rare.cand_val + cbase + w, bv, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(rare.cand_idx + cbase + w, bi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);  // the candidate has landed where every XCD reads it
-            __hip_atomic_fetch_add(p.arrive + b, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_fetch_add(rare.arrive + b, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             const int target = (meetings + 1) * Pg;
             int met = 0;
-            for (long long it = 0; it < p.spin_limit; ++it) {
-                if (__hip_atomic_load(p.arrive + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) {
+            for (long long it = 0; it < rare.spin_limit; ++it) {
+                if (__hip_atomic_load(rare.arrive + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) {
                     met = 1;
                     break;
                 }
-                if (__hip_atomic_load(p.abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) break;
+                if (__hip_atomic_load(rare.abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) break;
                 __builtin_amdgcn_s_sleep(8);
             }
-            if (!met) __hip_atomic_store(p.abort, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (!met) __hip_atomic_store(rare.abort, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             met_lds = met;
         }
         __syncthreads();
@@ -321,8 +379,8 @@ __global__ __launch_bounds__(kLoopThreads) void layer_loop_kernel(LoopParams p) 
         bv = -INFINITY;
         bi = 0x7fffffff;
         for (int i = tid; i < Pg; i += kLoopThreads) {
-            const float v = __hip_atomic_load(p.cand_val + cbase + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const int ix = __hip_atomic_load(p.cand_idx + cbase + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const float v = __hip_atomic_load(rare.cand_val + cbase + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int ix = __hip_atomic_load(rare.cand_idx + cbase + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (v > bv || (v == bv && ix < bi)) {
                 bv = v;
                 bi = ix;
@@ -348,8 +406,8 @@ __global__ __launch_bounds__(kLoopThreads) void layer_loop_kernel(LoopParams p) 
         for (int k = 0; k < KC; ++k)
             if (k < K && idv[k] == bi) hit = true;
         if (writer && tid == 0) {
-            p.ver_token[tok] = bi;
-            p.hit[tok] = hit ? 1 : 0;
+            rare.ver_token[tok] = bi;
+            rare.hit[tok] = hit ? 1 : 0;
         }
         evaluated_upto = l;
         if (hit) {  // the token leaves the model at this layer
@@ -359,28 +417,29 @@ __global__ __launch_bounds__(kLoopThreads) void layer_loop_kernel(LoopParams p) 
         }
         __syncthreads();  // cv / ci are rewritten by the next verification
         l = lnext;
+        lnext = lnext2;
     }
 
     // ---- layers that were not evaluated (inactive, after the exit, or from a failed meeting on): defined outputs
     if (writer) {
         for (int ll = 0; ll < L; ++ll) {
-            if (ll <= evaluated_upto && !(p.active && p.active[ll] == 0)) continue;
+            if (ll <= evaluated_upto && is_active(ll)) continue;
             const size_t tok = (size_t)ll * B + b;
             if (tid < K) {
-                p.logits[tok * K + tid] = 0.f;
-                p.probs[tok * K + tid] = 0.f;
+                rare.logits[tok * K + tid] = 0.f;
+                rare.probs[tok * K + tid] = 0.f;
             }
             if (tid == 0) {
-                p.scores[tok] = 0.f;
-                p.exit_flags[tok] = 0;
-                p.ver_token[tok] = -1;
-                p.hit[tok] = 0;
+                rare.scores[tok] = 0.f;
+                rare.exit_flags[tok] = 0;
+                rare.ver_token[tok] = -1;
+                rare.hit[tok] = 0;
             }
         }
         if (tid == 0) {
-            p.exit_layer[b] = exit_layer;
-            p.token[b] = exit_token;
-            p.status[b] = status;
+            rare.exit_layer[b] = exit_layer;
+            rare.token[b] = exit_token;
+            rare.status[b] = status;
         }
     }
 }

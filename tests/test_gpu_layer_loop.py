@@ -275,6 +275,21 @@ def test_layer_loop_bounded_wait_gives_up_instead_of_hanging(sp, oracle):
     assert np.all(host(out2["status"]) == 0) and np.array_equal(host(out2["exit_layer"]), ref["exit_layer"])
 
 
+def test_layer_loop_deep_stack_with_a_sparse_active_mask(sp, oracle):
+    """More than 128 layers (the mask no longer fits the two scalar words) with most predictors switched off."""
+    L = 150
+    t, _ = loop_inputs(3, 64, 40, 4, 8, L, 3, [None, None, None])
+    rng = np.random.default_rng(5)
+    active = (rng.random(L) < 0.3).astype(np.int32)
+    active[[0, 63, 64, 127, 128, 149]] = [1, 1, 0, 1, 1, 1]
+    ref = check_loop(oracle, sp, t, 2.0, active=active, what="deep stack, never fires")
+    assert np.all(ref["scores"][active == 0] == 0) and np.all(ref["scores"][active == 1] != 0)
+    t2, _ = loop_inputs(3, 64, 40, 4, 8, 100, 3, [None, None, None])      # 65..128 layers: both mask words
+    a2 = (rng.random(100) < 0.4).astype(np.int32)
+    a2[[0, 63, 64, 99]] = [0, 1, 1, 1]
+    check_loop(oracle, sp, t2, 2.0, active=a2, what="100 layers, never fires")
+
+
 def test_layer_loop_empty_stack_touches_no_input(sp):
     """L = 0: every token "runs the whole stack" (exit layer -1, token -1, status 0); the inputs may be empty."""
     z = lambda shape, dt: torch.zeros(shape, dtype=dt, device="cuda")
